@@ -1,0 +1,158 @@
+/*
+ * libqamw -- QAM-W per-weight-matrix codec for AMD MI355X (gfx950).
+ *
+ * The codec of arxiv 2605.26339, Sec. 3: a weight matrix W (d_out x d_in) is coded row by row.
+ *   encode: W D_s (Sec. B.2) -> row norm r, u = w/r (Sec. 3.1 step 1) -> y = F S u, the sign-masked
+ *           block-Hadamard rotation (Defs 1-3, Lemma 1) -> adjacent coordinates paired (step 3)
+ *           -> each pair divided by sigma_k (step 4, Eq. 1) -> nearest entry of one 2^B-point 2-D
+ *           codebook (Sec. 3.5) -> B-bit indices bit-packed per row (step 6).
+ *   decode: unpack -> centroid lookup -> times sigma_k -> u~ = S F y^ -> times r -> D_s^-1 -> bf16
+ *           (Sec. 3.2, Sec. B.2; the pipeline dequantises to BF16 before the matmul, Sec. 1).
+ *
+ * Conventions
+ *   - C ABI, every function returns an int status (QAMW_OK = 0).  No exception crosses the boundary.
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device memory of the
+ *     current device.  The caller owns every buffer; the library allocates no device memory and
+ *     keeps no state between calls (qamw_encode_noalloc-style variants, if present, say otherwise).
+ *   - Device entry points validate their arguments on the host, synchronously, BEFORE any launch
+ *     and return an error code without touching the outputs; otherwise they enqueue their kernels
+ *     on `stream` (a hipStream_t passed as void*, NULL = the default stream) and return without
+ *     waiting.  A launch failure is reported as QAMW_ERR_DEVICE.  Outputs are unspecified after
+ *     an error.  Behaviour on non-finite input values is unspecified.
+ *   - Matrices are row-major with an explicit leading dimension in ELEMENTS.
+ *   - P = d_in/2 pairs per row, K = 2^bits codewords.  Pair k of a row is columns (2k, 2k+1).
+ *
+ * Packed layout (the paper leaves it open; this is the library's definition): per row, pair k
+ * occupies bits [k*bits, (k+1)*bits) of the row's bit stream, least significant bit first; stream
+ * bit n is bit (n mod 8) of byte floor(n/8); unused bits are zero; the row stride in bytes is
+ * qamw_packed_row_bytes() = ceil(P*bits/8) rounded up to a multiple of 4.
+ *
+ * Arithmetic (fp32 unless noted), in this order, each result rounded once:
+ *   ws = W*s;  r = fp32(sqrt(sum_j ws^2 accumulated in fp64));  u = ws / r (IEEE division; r = 0: u = 0);
+ *   v = sign*u;  per block of `block` columns, butterflies with stride 1, 2, 4, ..., block/2:
+ *   (a, b) <- (a+b, a-b);  y = t * fp32(block^-1/2);  x_k = (y_2k, y_2k+1) * g_k with
+ *   g_k = 1/sigma_k (IEEE division), or fp32(sqrt(d_in)) when no sigma is given.
+ *   Nearest codeword: exact fp32 squared distances decide; lowest index wins exact ties.
+ *   decode: y^ = sigma_k * c[idx];  same butterflies;  times fp32(block^-1/2);  times sign;
+ *   times r;  times fp32(1/s_j);  bf16 round-to-nearest-even.
+ */
+#ifndef QAMW_H
+#define QAMW_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    QAMW_OK = 0,
+    QAMW_ERR_INVALID_ARG = 1, /* NULL required pointer, value out of range                */
+    QAMW_ERR_SHAPE = 2,       /* d_in odd, block not a power of two / not dividing d_in,  */
+                              /* leading dimension smaller than the row                   */
+    QAMW_ERR_UNSUPPORTED = 3, /* a valid request this build has no kernel for             */
+    QAMW_ERR_DEVICE = 4       /* HIP reported an error at launch                          */
+};
+
+enum { QAMW_DTYPE_F32 = 0, QAMW_DTYPE_BF16 = 1 };
+
+enum { QAMW_MAX_BITS = 12, QAMW_MAX_BLOCK = 1024 };
+
+/* Text for a status code (static storage, never NULL). */
+const char *qamw_status_string(int status);
+
+/* ---------------------------------------------------------------------------------------------
+ * Host helpers (no GPU involved)
+ * ------------------------------------------------------------------------------------------ */
+
+/* Row stride of the packed stream in bytes: ceil((d_in/2)*bits/8) rounded up to 4 (Sec. 3.1 step 6;
+ * Sec. 3.6 mentions row-level packing and alignment without fixing them).
+ * Errors: d_in <= 0 or odd -> SHAPE; bits outside [1,12] or out NULL -> INVALID_ARG. */
+int qamw_packed_row_bytes(int d_in, int bits, size_t *out);
+
+/* Block-size rule of Sec. 3.3: the largest power of two dividing d_in, capped at 1024
+ * (worked examples there: 2048 -> 1024, 5632 -> 512). */
+int qamw_paper_block_size(int d_in, int *block_out);
+
+/* Eq. 3: bpw = bits/2 + 16/d_in; with_f16_scales adds the per-input-channel scale metadata of
+ * Sec. 3.7, 16 bits per column, i.e. 16/d_out per weight. */
+int qamw_bpw(int d_in, int d_out, int bits, int with_f16_scales, double *out);
+
+/* Def. 3: the +-1 sign mask from a 64-bit seed.  Generator (the paper names none): word n of the
+ * stream is the SplitMix64 output function applied to seed + (n+1)*0x9E3779B97F4A7C15; element j
+ * takes bit (j mod 64) of word floor(j/64); 0 -> +1, 1 -> -1.  signs_out: host, d_in int8. */
+int qamw_sign_mask(uint64_t seed, int d_in, int8_t *signs_out);
+
+/* Sec. B.2: s_j proportional to act_rms_j^alpha, geometric mean normalised to one, then clamped to
+ * [1/16, 16] (no renormalisation after the clamp).  act_rms below 1e-30 is floored.  Host arrays
+ * of d_in floats.  alpha outside [0, 1] -> INVALID_ARG. */
+int qamw_channel_scales(const float *act_rms, int d_in, float alpha, float *s_out);
+
+/* Sec. 3.5, Eq. 2: Lloyd iterations for a 2^bits-point codebook on n_samples draws of the unit
+ * circular Gaussian (CPU, off the hot path; multi-threaded, result independent of thread count).
+ * Samples: draw i uses words 2i and 2i+1 of the SplitMix64 stream above as uniforms (top 53 bits;
+ * u1 in (0,1], u2 in [0,1)) and the Box-Muller map.  Initial points: golden-angle spiral with
+ * radii at the (i+0.5)/K quantiles of a circular Gaussian of variance 2 per axis.  Each iteration
+ * assigns every sample to its nearest point (fp64, lowest index on ties) and, unless it is the
+ * last, moves every point to the mean of its cell (an empty cell moves onto the sample with the
+ * largest error).  Stops when the relative change of the mean squared error drops below tol, or
+ * after max_iters assignments.
+ * codebook_out: host, 2^bits x 2 floats (x, y).  mse_out / iters_out: nullable.
+ * Errors: bits outside [1,12], n_samples < 2^bits, max_iters < 1, tol < 0, NULL output. */
+int qamw_train_codebook(int bits, uint64_t n_samples, uint64_t seed, int max_iters, double tol,
+                        float *codebook_out, double *mse_out, int *iters_out);
+
+/* ---------------------------------------------------------------------------------------------
+ * Device entry points.  Common arguments:
+ *   dtype       QAMW_DTYPE_F32 or QAMW_DTYPE_BF16: element type of W (bf16 is widened exactly)
+ *   d_out,d_in  matrix shape; d_in even
+ *   ldw         leading dimension of W in elements, >= d_in
+ *   chan_scale  device, d_in floats s_j > 0, or NULL (= all ones)          [Sec. B.2]
+ *   signs       device, d_in int8 in {+1,-1}, or NULL (= all +1)           [Def. 3]
+ *   pair_sigma  device, P floats sigma_k > 0, or NULL (= 1/sqrt(d_in))     [Eq. 1]
+ *   codebook    device, K x 2 floats                                       [Sec. 3.5]
+ *   bits        1..12;  hadamard_block: power of two, 2..1024, dividing d_in
+ *   stream      hipStream_t as void*
+ * Errors common to all: NULL required pointer, d_out/d_in <= 0, bits out of range -> INVALID_ARG;
+ * odd d_in, bad block, ldw < d_in -> SHAPE.
+ * ------------------------------------------------------------------------------------------ */
+
+/* Eq. 1: sigma_k = mean over the first n = min(d_out, max_rows) rows of |z_k| / sqrt(pi/2), where
+ * z_k are the pairs of the unit-normalised, rotated rows (encoder steps 1-3); amplitudes and the
+ * mean in fp64; an estimate that is not positive is replaced by 1/sqrt(d_in).
+ * row_norms_ws: device workspace of n floats (receives those rows' norms).
+ * sigma_out: device, P floats.  max_rows < 1 -> INVALID_ARG. */
+int qamw_calibrate_sigma(const void *W, int dtype, int d_out, int d_in, int64_t ldw,
+                         const float *chan_scale, const int8_t *signs, int hadamard_block,
+                         int max_rows, float *row_norms_ws, float *sigma_out, void *stream);
+
+/* Encoder of Sec. 3.1 with the channel scaling of Sec. B.2.
+ * packed_out: device, d_out * qamw_packed_row_bytes(d_in, bits) bytes, fully overwritten.
+ * row_norms_out: device, d_out floats (norm of the SCALED row W D_s). */
+int qamw_encode(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
+                const int8_t *signs, const float *pair_sigma, const float *codebook, int bits,
+                int hadamard_block, uint8_t *packed_out, float *row_norms_out, void *stream);
+
+/* Decoder of Sec. 3.2 with D_s^-1 of Sec. B.2, bf16 output (uint16 bit patterns).
+ * W_out: device, d_out rows of d_in bf16 with leading dimension ldo >= d_in (elements). */
+int qamw_decode(const uint8_t *packed, const float *row_norms, int d_out, int d_in,
+                const float *chan_scale, const int8_t *signs, const float *pair_sigma,
+                const float *codebook, int bits, int hadamard_block, uint16_t *W_out, int64_t ldo,
+                void *stream);
+
+/* Same decoder, writing the fp32 value before the bf16 cast (for accuracy checks). */
+int qamw_decode_f32(const uint8_t *packed, const float *row_norms, int d_out, int d_in,
+                    const float *chan_scale, const int8_t *signs, const float *pair_sigma,
+                    const float *codebook, int bits, int hadamard_block, float *W_out, int64_t ldo,
+                    void *stream);
+
+/* Which implementation the device entry points use: 0 = automatic (fast kernels when the shape
+ * allows, otherwise the general ones), 1 = always the general kernels.  Process-wide, for tests
+ * and measurements; returns the previous value. */
+int qamw_set_kernel_path(int path);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QAMW_H */

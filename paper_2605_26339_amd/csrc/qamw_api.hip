@@ -1,0 +1,114 @@
+// libqamw device entry points: argument validation on the host, then kernel dispatch.
+#include <atomic>
+#include <cmath>
+
+#include "qamw.h"
+#include "qamw_internal.hpp"
+
+namespace {
+
+std::atomic<int> g_kernel_path{0};
+
+int check_common(int d_out, int d_in, int bits, int block) {
+    if (d_out <= 0 || d_in <= 0 || bits < 1 || bits > QAMW_MAX_BITS) return QAMW_ERR_INVALID_ARG;
+    if (d_in & 1) return QAMW_ERR_SHAPE;
+    if (block < 2 || block > QAMW_MAX_BLOCK || (block & (block - 1)) || d_in % block) return QAMW_ERR_SHAPE;
+    return QAMW_OK;
+}
+
+qamw::Problem make_problem(int d_out, int d_in, const float *chan_scale, const int8_t *signs, const float *pair_sigma,
+                           const float *codebook, int bits, int block, void *stream) {
+    qamw::Problem p;
+    p.d_out = d_out;
+    p.d_in = d_in;
+    p.bits = bits;
+    p.K = 1 << bits;
+    p.block = block;
+    p.chan_scale = chan_scale;
+    p.signs = signs;
+    p.pair_sigma = pair_sigma;
+    p.codebook = codebook;
+    p.inv_sqrt_block = (float)(1.0 / std::sqrt((double)block));
+    p.g_default = (float)std::sqrt((double)d_in);
+    p.sigma_default = (float)(1.0 / std::sqrt((double)d_in));
+    size_t rb = 0;
+    qamw_packed_row_bytes(d_in, bits, &rb);
+    p.row_bytes = (int64_t)rb;
+    p.stream = (hipStream_t)stream;
+    return p;
+}
+
+int decode_any(const uint8_t *packed, const float *row_norms, int d_out, int d_in, const float *chan_scale,
+               const int8_t *signs, const float *pair_sigma, const float *codebook, int bits, int block, void *out,
+               int64_t ldo, void *stream, bool bf16) {
+    if (!packed || !row_norms || !codebook || !out) return QAMW_ERR_INVALID_ARG;
+    int rc = check_common(d_out, d_in, bits, block);
+    if (rc != QAMW_OK) return rc;
+    if (ldo < d_in) return QAMW_ERR_SHAPE;
+    qamw::Problem p = make_problem(d_out, d_in, chan_scale, signs, pair_sigma, codebook, bits, block, stream);
+    hipError_t e;
+    if (g_kernel_path.load() == 0 && qamw::fast_decode_supported(p))
+        e = qamw::launch_decode_fast(packed, row_norms, p, out, ldo, bf16);
+    else
+        e = qamw::launch_decode_general(packed, row_norms, p, out, ldo, bf16);
+    return e == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
+}
+
+}  // namespace
+
+extern "C" {
+
+int qamw_set_kernel_path(int path) {
+    if (path != 0 && path != 1) return g_kernel_path.load();
+    return g_kernel_path.exchange(path);
+}
+
+int qamw_calibrate_sigma(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
+                         const int8_t *signs, int hadamard_block, int max_rows, float *row_norms_ws,
+                         float *sigma_out, void *stream) {
+    if (!W || !row_norms_ws || !sigma_out || max_rows < 1) return QAMW_ERR_INVALID_ARG;
+    if (dtype != QAMW_DTYPE_F32 && dtype != QAMW_DTYPE_BF16) return QAMW_ERR_INVALID_ARG;
+    int rc = check_common(d_out, d_in, 1, hadamard_block);
+    if (rc != QAMW_OK) return rc;
+    if (ldw < d_in) return QAMW_ERR_SHAPE;
+    qamw::Problem p = make_problem(d_out, d_in, chan_scale, signs, nullptr, nullptr, 1, hadamard_block, stream);
+    const int n = d_out < max_rows ? d_out : max_rows;
+    if (qamw::launch_row_norms(W, dtype, ldw, n, p, row_norms_ws) != hipSuccess) return QAMW_ERR_DEVICE;
+    if (qamw::launch_calibrate_general(W, dtype, ldw, n, p, row_norms_ws, sigma_out) != hipSuccess)
+        return QAMW_ERR_DEVICE;
+    return QAMW_OK;
+}
+
+int qamw_encode(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
+                const int8_t *signs, const float *pair_sigma, const float *codebook, int bits, int hadamard_block,
+                uint8_t *packed_out, float *row_norms_out, void *stream) {
+    if (!W || !codebook || !packed_out || !row_norms_out) return QAMW_ERR_INVALID_ARG;
+    if (dtype != QAMW_DTYPE_F32 && dtype != QAMW_DTYPE_BF16) return QAMW_ERR_INVALID_ARG;
+    int rc = check_common(d_out, d_in, bits, hadamard_block);
+    if (rc != QAMW_OK) return rc;
+    if (ldw < d_in) return QAMW_ERR_SHAPE;
+    qamw::Problem p = make_problem(d_out, d_in, chan_scale, signs, pair_sigma, codebook, bits, hadamard_block, stream);
+    if (qamw::launch_row_norms(W, dtype, ldw, d_out, p, row_norms_out) != hipSuccess) return QAMW_ERR_DEVICE;
+    hipError_t e;
+    if (g_kernel_path.load() == 0 && qamw::fast_encode_supported(p))
+        e = qamw::launch_encode_fast(W, dtype, ldw, p, row_norms_out, packed_out);
+    else
+        e = qamw::launch_encode_general(W, dtype, ldw, p, row_norms_out, packed_out);
+    return e == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
+}
+
+int qamw_decode(const uint8_t *packed, const float *row_norms, int d_out, int d_in, const float *chan_scale,
+                const int8_t *signs, const float *pair_sigma, const float *codebook, int bits, int hadamard_block,
+                uint16_t *W_out, int64_t ldo, void *stream) {
+    return decode_any(packed, row_norms, d_out, d_in, chan_scale, signs, pair_sigma, codebook, bits, hadamard_block,
+                      W_out, ldo, stream, true);
+}
+
+int qamw_decode_f32(const uint8_t *packed, const float *row_norms, int d_out, int d_in, const float *chan_scale,
+                    const int8_t *signs, const float *pair_sigma, const float *codebook, int bits,
+                    int hadamard_block, float *W_out, int64_t ldo, void *stream) {
+    return decode_any(packed, row_norms, d_out, d_in, chan_scale, signs, pair_sigma, codebook, bits, hadamard_block,
+                      W_out, ldo, stream, false);
+}
+
+}  // extern "C"

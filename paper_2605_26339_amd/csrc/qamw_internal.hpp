@@ -1,0 +1,41 @@
+// Internal launch interface between libqamw's entry points and its kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace qamw {
+
+// Everything a codec kernel needs to know about one matrix.  Host-computed constants are passed
+// in so that host and device agree on them bit for bit.
+struct Problem {
+    int d_out = 0, d_in = 0;
+    int bits = 0, K = 0, block = 0;
+    const float *chan_scale = nullptr;   // device, d_in, nullable
+    const int8_t *signs = nullptr;       // device, d_in, nullable
+    const float *pair_sigma = nullptr;   // device, d_in/2, nullable
+    const float *codebook = nullptr;     // device, K x 2
+    float inv_sqrt_block = 0.f;          // fp32(block^-1/2)
+    float g_default = 0.f;               // fp32(sqrt(d_in)): pair gain when no sigma is given
+    float sigma_default = 0.f;           // fp32(d_in^-1/2)
+    int64_t row_bytes = 0;               // packed row stride
+    hipStream_t stream = nullptr;
+};
+
+// General kernels: any even d_in, any power-of-two block <= 1024 dividing d_in.
+hipError_t launch_row_norms(const void *W, int dtype, int64_t ldw, int n_rows, const Problem &p, float *norms);
+hipError_t launch_encode_general(const void *W, int dtype, int64_t ldw, const Problem &p, const float *norms,
+                                 uint8_t *packed);
+hipError_t launch_decode_general(const uint8_t *packed, const float *norms, const Problem &p, void *out,
+                                 int64_t ldo, bool out_bf16);
+hipError_t launch_calibrate_general(const void *W, int dtype, int64_t ldw, int n_rows, const Problem &p,
+                                    const float *norms, float *sigma_out);
+
+// Fast kernels: return hipErrorNotSupported when the shape is outside what they cover.
+bool fast_decode_supported(const Problem &p);
+hipError_t launch_decode_fast(const uint8_t *packed, const float *norms, const Problem &p, void *out,
+                              int64_t ldo, bool out_bf16);
+bool fast_encode_supported(const Problem &p);
+hipError_t launch_encode_fast(const void *W, int dtype, int64_t ldw, const Problem &p, const float *norms,
+                              uint8_t *packed);
+
+}  // namespace qamw

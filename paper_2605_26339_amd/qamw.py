@@ -1,0 +1,193 @@
+"""Thin ctypes binding of libqamw (include/qamw.h).  Argument marshalling only: every step of
+the codec runs in the library's HIP kernels.  torch is used for device memory and streams.
+
+There is no CPU fallback: importing works without a GPU (host helpers run anywhere), but the
+device entry points raise if the library is missing or HIP reports an error.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+OK, ERR_INVALID_ARG, ERR_SHAPE, ERR_UNSUPPORTED, ERR_DEVICE = 0, 1, 2, 3, 4
+DTYPE_F32, DTYPE_BF16 = 0, 1
+
+EXPORTS = [
+    "qamw_status_string", "qamw_packed_row_bytes", "qamw_paper_block_size", "qamw_bpw", "qamw_sign_mask",
+    "qamw_channel_scales", "qamw_train_codebook", "qamw_calibrate_sigma", "qamw_encode", "qamw_decode",
+    "qamw_decode_f32", "qamw_set_kernel_path",
+]
+
+
+class QamwError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libqamw.so (built in-tree).  Builds it only when no library exists at all."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB):
+            _build.build(verbose=False)
+        L = C.CDLL(_build.LIB)
+        L.qamw_status_string.restype = C.c_char_p
+        L.qamw_status_string.argtypes = [C.c_int]
+        vp, i32, i64, u64 = C.c_void_p, C.c_int, C.c_int64, C.c_uint64
+        L.qamw_packed_row_bytes.argtypes = [i32, i32, C.POINTER(C.c_size_t)]
+        L.qamw_paper_block_size.argtypes = [i32, C.POINTER(i32)]
+        L.qamw_bpw.argtypes = [i32, i32, i32, i32, C.POINTER(C.c_double)]
+        L.qamw_sign_mask.argtypes = [u64, i32, vp]
+        L.qamw_channel_scales.argtypes = [vp, i32, C.c_float, vp]
+        L.qamw_train_codebook.argtypes = [i32, u64, u64, i32, C.c_double, vp, C.POINTER(C.c_double), C.POINTER(i32)]
+        L.qamw_calibrate_sigma.argtypes = [vp, i32, i32, i32, i64, vp, vp, i32, i32, vp, vp, vp]
+        L.qamw_encode.argtypes = [vp, i32, i32, i32, i64, vp, vp, vp, vp, i32, i32, vp, vp, vp]
+        L.qamw_decode.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, i64, vp]
+        L.qamw_decode_f32.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, i64, vp]
+        L.qamw_set_kernel_path.argtypes = [i32]
+        for name in EXPORTS:
+            if name != "qamw_status_string":
+                getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().qamw_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != OK:
+        raise QamwError(status, where)
+
+
+# ------------------------------------------------------------------------------ host helpers
+def packed_row_bytes(d_in: int, bits: int) -> int:
+    out = C.c_size_t()
+    _check(lib().qamw_packed_row_bytes(d_in, bits, C.byref(out)), "qamw_packed_row_bytes")
+    return int(out.value)
+
+
+def paper_block_size(d_in: int) -> int:
+    out = C.c_int()
+    _check(lib().qamw_paper_block_size(d_in, C.byref(out)), "qamw_paper_block_size")
+    return int(out.value)
+
+
+def bpw(d_in: int, d_out: int, bits: int, with_f16_scales: bool = False) -> float:
+    out = C.c_double()
+    _check(lib().qamw_bpw(d_in, d_out, bits, int(with_f16_scales), C.byref(out)), "qamw_bpw")
+    return float(out.value)
+
+
+def sign_mask(seed: int, d_in: int) -> np.ndarray:
+    out = np.empty(max(d_in, 0), dtype=np.int8)
+    _check(lib().qamw_sign_mask(seed & (2**64 - 1), d_in, out.ctypes.data), "qamw_sign_mask")
+    return out
+
+
+def channel_scales(act_rms: np.ndarray, alpha: float) -> np.ndarray:
+    a = np.ascontiguousarray(act_rms, dtype=np.float32)
+    out = np.empty_like(a)
+    _check(lib().qamw_channel_scales(a.ctypes.data, a.size, alpha, out.ctypes.data), "qamw_channel_scales")
+    return out
+
+
+def train_codebook(bits: int, n_samples: int = 1 << 20, seed: int = 0, max_iters: int = 200, tol: float = 1e-7):
+    """Returns (codebook float32 [2^bits][2], mse, iterations)."""
+    out = np.empty((1 << max(bits, 0) if 1 <= bits <= 12 else 1, 2), dtype=np.float32)
+    mse, it = C.c_double(), C.c_int()
+    _check(lib().qamw_train_codebook(bits, n_samples, seed & (2**64 - 1), max_iters, tol, out.ctypes.data,
+                                     C.byref(mse), C.byref(it)), "qamw_train_codebook")
+    return out, float(mse.value), int(it.value)
+
+
+def set_kernel_path(path: int) -> int:
+    return int(lib().qamw_set_kernel_path(path))
+
+
+# ------------------------------------------------------------------------------ device entry points
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _dtype_code(W):
+    import torch
+
+    if W.dtype == torch.float32:
+        return DTYPE_F32
+    if W.dtype == torch.bfloat16:
+        return DTYPE_BF16
+    raise TypeError(f"W must be float32 or bfloat16, got {W.dtype}")
+
+
+def _require_cuda(*tensors):
+    for t in tensors:
+        if t is not None and not t.is_cuda:
+            raise ValueError("device entry points take CUDA (HIP) tensors")
+
+
+def calibrate_sigma(W, block: int, chan_scale=None, signs=None, max_rows: int = 1024, stream=None):
+    """Eq. 1 pair scales of matrix W (torch CUDA tensor [d_out][d_in]).  Returns float32 [d_in/2]."""
+    import torch
+
+    _require_cuda(W, chan_scale, signs)
+    d_out, d_in = W.shape
+    n = max(1, min(d_out, max_rows))
+    ws = torch.empty(n, dtype=torch.float32, device=W.device)
+    out = torch.empty(d_in // 2, dtype=torch.float32, device=W.device)
+    _check(lib().qamw_calibrate_sigma(_ptr(W), _dtype_code(W), d_out, d_in, W.stride(0), _ptr(chan_scale), _ptr(signs),
+                                      block, max_rows, _ptr(ws), _ptr(out), _stream(stream)), "qamw_calibrate_sigma")
+    return out
+
+
+def encode(W, codebook, bits: int, block: int, chan_scale=None, signs=None, pair_sigma=None, out=None, stream=None):
+    """Encode W (torch CUDA tensor, fp32 or bf16, row-major, stride(1) == 1).
+    Returns (packed uint8 [d_out][row_bytes], row_norms float32 [d_out])."""
+    import torch
+
+    _require_cuda(W, codebook, chan_scale, signs, pair_sigma)
+    if W.dim() != 2 or W.stride(1) != 1:
+        raise ValueError("W must be 2-D with unit column stride")
+    d_out, d_in = W.shape
+    rb = packed_row_bytes(d_in, bits)
+    if out is None:
+        packed = torch.empty((d_out, rb), dtype=torch.uint8, device=W.device)
+        norms = torch.empty(d_out, dtype=torch.float32, device=W.device)
+    else:
+        packed, norms = out
+    _check(lib().qamw_encode(_ptr(W), _dtype_code(W), d_out, d_in, W.stride(0), _ptr(chan_scale), _ptr(signs),
+                             _ptr(pair_sigma), _ptr(codebook), bits, block, _ptr(packed), _ptr(norms),
+                             _stream(stream)), "qamw_encode")
+    return packed, norms
+
+
+def decode(packed, row_norms, d_in: int, codebook, bits: int, block: int, chan_scale=None, signs=None,
+           pair_sigma=None, out=None, f32: bool = False, stream=None):
+    """Decode to bf16 [d_out][d_in] (or the fp32 value before the cast when f32=True)."""
+    import torch
+
+    _require_cuda(packed, row_norms, codebook, chan_scale, signs, pair_sigma)
+    d_out = row_norms.shape[0]
+    if out is None:
+        out = torch.empty((d_out, d_in), dtype=torch.float32 if f32 else torch.bfloat16, device=packed.device)
+    fn = lib().qamw_decode_f32 if f32 else lib().qamw_decode
+    _check(fn(_ptr(packed), _ptr(row_norms), d_out, d_in, _ptr(chan_scale), _ptr(signs), _ptr(pair_sigma),
+              _ptr(codebook), bits, block, _ptr(out), out.stride(0), _stream(stream)),
+           "qamw_decode_f32" if f32 else "qamw_decode")
+    return out
