@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Benchmark of the QAM-W codec hot path on one MI355X.
+
+A step is one pass of the whole hot path over one model-shaped synthetic weight set that is
+already resident in HBM: for every matrix, pair-scale calibration (Eq. 1), encode (row norms,
+rotation, nearest codeword, bit-pack) and decode to bf16.  Rank 0 prints one JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--layers L]
+
+Timing uses HIP events recorded on the stream the kernels are launched on.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "encode Gpairs/s + decode GB/s (BF16 out), 7B-shaped weights; % of roofline"
+PEAK_FP32_TFLOPS = 157.3          # MI355X vector fp32 (published)
+PEAK_HBM_GBS = 8000.0             # MI355X HBM3E (published)
+FLOPS_PER_EVAL = 4.0              # one distance evaluation = 2 FMA
+
+
+def build_workload(wl, layers, device):
+    """Synthetic weights and side inputs of every matrix, generated on the device."""
+    import torch
+
+    from paper_2605_26339_amd import qamw, synth
+
+    mats = []
+    for layer in range(layers):
+        site_cache = {}
+        for name, d_out, d_in, site in wl.matrices:
+            if site not in site_cache:
+                a = synth.act_rms_host(synth.seed_for(wl.config_id, layer, site), d_in)
+                s = torch.from_numpy(qamw.channel_scales(a, wl.alpha)).to(device)
+                sg = torch.from_numpy(qamw.sign_mask(synth.seed_for(wl.config_id, layer, "mask-" + site), d_in)).to(device)
+                site_cache[site] = (s, sg)
+            s, sg = site_cache[site]
+            W = synth.weight_device(synth.seed_for(wl.config_id, layer, name), d_out, d_in, wl.row_sigma, wl.dtype, device)
+            rb = qamw.packed_row_bytes(d_in, wl.bits)
+            mats.append(dict(name=f"L{layer}.{name}", W=W, s=s, sg=sg, d_out=d_out, d_in=d_in,
+                             packed=torch.empty((d_out, rb), dtype=torch.uint8, device=device),
+                             norms=torch.empty(d_out, dtype=torch.float32, device=device),
+                             out=torch.empty((d_out, d_in), dtype=torch.bfloat16, device=device)))
+    return mats
+
+
+def run_step(mats, wl, cb, timed):
+    """One pass: calibrate + encode + decode every matrix.  Returns per-phase event pairs."""
+    import torch
+
+    from paper_2605_26339_amd import qamw
+
+    ev = []
+    for m in mats:
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(4)] if timed else None
+        if timed:
+            e[0].record()
+        sigma = qamw.calibrate_sigma(m["W"], wl.block, chan_scale=m["s"], signs=m["sg"])
+        if timed:
+            e[1].record()
+        qamw.encode(m["W"], cb, wl.bits, wl.block, chan_scale=m["s"], signs=m["sg"], pair_sigma=sigma,
+                    out=(m["packed"], m["norms"]))
+        if timed:
+            e[2].record()
+        qamw.decode(m["packed"], m["norms"], m["d_in"], cb, wl.bits, wl.block, chan_scale=m["s"], signs=m["sg"],
+                    pair_sigma=sigma, out=m["out"])
+        if timed:
+            e[3].record()
+            ev.append(e)
+    return ev
+
+
+def cpu_baseline(wl, mats, cb_host):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the same workload:
+    the first 2048 rows of the first matrix with d_in = the model width."""
+    import numpy as np
+
+    from oracle import qamw_oracle as orc
+
+    m = mats[0]
+    rows = min(2048, m["d_out"])
+    W = m["W"][:rows].float().cpu().numpy()
+    s, sg = m["s"].cpu().numpy(), m["sg"].cpu().numpy()
+    cores = min(os.cpu_count() or 1, 16)
+    sigma = orc.calibrate_sigma(W, wl.block, chan_scale=s, signs=sg)
+    t0 = time.perf_counter()
+    enc = orc.encode(W, cb_host, wl.bits, wl.block, chan_scale=s, signs=sg, pair_sigma=sigma, want_gaps=False, threads=cores)
+    t1 = time.perf_counter()
+    dec = orc.decode(enc["idx"], enc["norms"], cb_host, wl.bits, wl.block, chan_scale=s, signs=sg, pair_sigma=sigma,
+                     threads=cores)
+    t2 = time.perf_counter()
+    pairs = rows * m["d_in"] // 2
+    dec_bytes = pairs * (wl.bits / 8.0 + 4.0)
+    del dec
+    return {"value": pairs / (t1 - t0) / 1e9, "unit": "Gpairs/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {rows} rows of {m['name']} ({m['d_out']}x{m['d_in']}), fp32 spec mode, "
+                      f"encode {t1 - t0:.2f}s decode {t2 - t1:.2f}s",
+            "decode_value": dec_bytes / (t2 - t1) / 1e9, "decode_unit": "GB/s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="c2_llama2_7b_b11")
+    ap.add_argument("--layers", type=int, default=0, help="0 = the workload's own layer count")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this codec benchmark runs on exactly one GPU (rows and matrices are independent; "
+              "nothing is exchanged between devices). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2605_26339_amd import qamw, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    wl = synth.WORKLOADS[args.workload]
+    layers = args.layers or wl.layers
+    cb_host, cb_mse, cb_iters = qamw.train_codebook(wl.bits, 1 << 20, seed=0)
+    cb = torch.from_numpy(cb_host).to(dev)
+    mats = build_workload(wl, layers, dev)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        run_step(mats, wl, cb, timed=False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    all_ev = []
+    for _ in range(args.steps):
+        all_ev.extend(run_step(mats, wl, cb, timed=True))
+    stop.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    total_ms = start.elapsed_time(stop)
+
+    cal_ms = sum(e[0].elapsed_time(e[1]) for e in all_ev)
+    enc_ms = sum(e[1].elapsed_time(e[2]) for e in all_ev)
+    dec_ms = sum(e[2].elapsed_time(e[3]) for e in all_ev)
+    n_launch = len(all_ev)
+    pairs_step = sum(m["d_out"] * m["d_in"] // 2 for m in mats)
+    pairs = pairs_step * args.steps
+    evals = pairs * wl.K
+    dec_bytes = pairs * (wl.bits / 8.0 + 4.0) + args.steps * sum(4 * m["d_out"] for m in mats)
+    enc_in_bytes = pairs * ((8 if wl.dtype == "f32" else 4) + wl.bits / 8.0)
+
+    enc_tflops = evals * FLOPS_PER_EVAL / (enc_ms * 1e-3) / 1e12
+    dec_gbs = dec_bytes / (dec_ms * 1e-3) / 1e9
+    result = {
+        "metric": METRIC,
+        "value": pairs / ((enc_ms + cal_ms) * 1e-3) / 1e9,
+        "unit": "Gpairs/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": total_ms / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "layers": layers, "matrices": len(mats), "weights": 2 * pairs_step,
+                   "input_dtype": wl.dtype, "bits": wl.bits, "K": wl.K, "hadamard_block": wl.block,
+                   "codebook": f"Lloyd, 2^20 samples, seed 0, mse {cb_mse:.6f}, {cb_iters} iterations"},
+        "encode": {"gpairs_per_s_kernels_only": pairs / (enc_ms * 1e-3) / 1e9,
+                   "gpairs_per_s_with_calibration": pairs / ((enc_ms + cal_ms) * 1e-3) / 1e9,
+                   "ms_per_step": enc_ms / args.steps, "calibration_ms_per_step": cal_ms / args.steps,
+                   "hbm_gb_per_s": enc_in_bytes / (enc_ms * 1e-3) / 1e9},
+        "decode": {"value": dec_gbs, "unit": "GB/s", "ms_per_step": dec_ms / args.steps,
+                   "gpairs_per_s": pairs / (dec_ms * 1e-3) / 1e9},
+        "roofline": {"kernel": "qamw_encode (row norms + nearest-codeword kernel)", "bound": "alu",
+                     "achieved": enc_tflops, "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s",
+                     "frac": enc_tflops / PEAK_FP32_TFLOPS, "traffic": None,
+                     "avg_launch_ms": enc_ms / n_launch,
+                     "algorithmic_flops_per_launch": evals * FLOPS_PER_EVAL / n_launch},
+        "roofline_decode": {"kernel": "qamw_decode", "bound": "hbm", "achieved": dec_gbs, "peak": PEAK_HBM_GBS,
+                            "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS, "traffic": None,
+                            "avg_launch_ms": dec_ms / n_launch,
+                            "algorithmic_bytes_per_launch": dec_bytes / n_launch},
+        "wall_s_timed_region": wall,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, mats, cb_host)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -36,6 +36,10 @@ def lib() -> C.CDLL:
     """Load libqamw.so (built in-tree).  Builds it only when no library exists at all."""
     global _lib
     if _lib is None:
+        # torch ships its own HIP runtime; it must be the one already loaded when libqamw's
+        # dependency on libamdhip64 is resolved, or the two would not share streams and memory.
+        import torch  # noqa: F401
+
         if not os.path.exists(_build.LIB):
             _build.build(verbose=False)
         L = C.CDLL(_build.LIB)
