@@ -86,38 +86,45 @@ __device__ __forceinline__ void load_column_constants(float (&qs)[16], float (&s
     }
 }
 
-// Wave g of the grid owns slab g % n_slabs and the R rows starting at (g / n_slabs) * R.
-// Matrices of a few tens of MB decode in ~10 us, so the kernel is organised around its start-up:
-// every global load a wave will ever need (R rows of packed indices, their norms, the column
-// constants) is issued before the codebook is staged into LDS, and the rows are then processed
-// without further waits on HBM.
+// Persistent kernel.  The grid is sized to the machine (not to the matrix); a block stages the
+// codebook into LDS once, then each wave keeps one slab (so its column constants load once) and
+// walks over groups of R rows with a grid stride, fetching the next group's packed indices and
+// norms while it works on the current one.  The 16 bf16 a lane produces are 32 consecutive
+// bytes; a row chunk is therefore bounced through LDS so that each store instruction writes
+// 1 KB of consecutive bytes (full cache lines) instead of every other 16 bytes.
 template <int BITS, int B, bool OUT_BF16, int R>
 __global__ __launch_bounds__(DF_THREADS) void k_decode_fast(const uint8_t *__restrict__ packed,
                                                             const float *__restrict__ norms, Problem p,
-                                                            void *__restrict__ out, int64_t ldo, int n_slabs) {
-    extern __shared__ float2 cb_lds[];
+                                                            void *__restrict__ out, int64_t ldo, int n_slabs,
+                                                            int waves_per_slab) {
+    extern __shared__ float2 cb_lds[];                          // K codewords, then the per-wave bounce buffers
     const int lane = threadIdx.x & (WAVE - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(blockIdx.x * DF_WAVES + (threadIdx.x >> 6));
+    const int wid = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(blockIdx.x * DF_WAVES + wid);
     const int slab = wave % n_slabs;
-    const int row0 = (wave / n_slabs) * R;
-    const bool wave_has_rows = row0 < p.d_out;                  // uniform over the wave
+    const int first_group = wave / n_slabs;                     // >= waves_per_slab: nothing to do
+    const int n_groups = (p.d_out + R - 1) / R;
     const int last_row = p.d_out - 1;
 
     const LaneSigns<B> ls(lane);
-    const int col0 = slab * SLAB + 16 * slab_pos(lane);
-    const bool active = wave_has_rows && col0 < p.d_in;
+    const int pos = slab_pos(lane);
+    const int col0 = slab * SLAB + 16 * pos;
     const int c = (col0 < p.d_in) ? col0 : 0;                   // idle lanes compute on valid data, store nothing
+    const int slab_cols = min(SLAB, p.d_in - slab * SLAB);      // valid columns of this slab
     const int64_t byte_off = (int64_t)(c >> 4) * BITS;          // 8 fields of BITS bits = BITS bytes per lane
     const uint32_t *pk32 = reinterpret_cast<const uint32_t *>(packed);
     const int64_t total_dw = (int64_t)p.d_out * (p.row_bytes >> 2);
 
-    uint32_t d[R][4];
-    float rn[R];
+    uint32_t nxt[R][4];
+    float rn_nxt[R];
+    int group = (first_group < waves_per_slab) ? first_group : n_groups;   // surplus waves of the last block idle
+    if (group < n_groups) {
 #pragma unroll
-    for (int t = 0; t < R; ++t) {
-        const int row = min(row0 + t, last_row);                // rows past the end re-read the last row
-        load_group(d[t], pk32, (int64_t)row * p.row_bytes + byte_off, total_dw);
-        rn[t] = norms[row];
+        for (int t = 0; t < R; ++t) {
+            const int row = min(group * R + t, last_row);       // rows past the end re-read the last row
+            load_group(nxt[t], pk32, (int64_t)row * p.row_bytes + byte_off, total_dw);
+            rn_nxt[t] = norms[row];
+        }
     }
     float qs[16], sig[8];
     load_column_constants(qs, sig, p, c, ls.parity);
@@ -125,44 +132,78 @@ __global__ __launch_bounds__(DF_THREADS) void k_decode_fast(const uint8_t *__res
     const float2 *cbk = reinterpret_cast<const float2 *>(p.codebook);
     for (int i = threadIdx.x; i < p.K; i += DF_THREADS) cb_lds[i] = cbk[i];
     __syncthreads();
+    uint4 *bounce = reinterpret_cast<uint4 *>(cb_lds + p.K) + wid * (OUT_BF16 ? 128 : 256);
 
+    for (; group < n_groups; group += waves_per_slab) {
+        uint32_t d[R][4];
+        float rn[R];
 #pragma unroll
-    for (int t = 0; t < R; ++t) {
-        const int row = row0 + t;
-        const int sh = (int)(((int64_t)min(row, last_row) * p.row_bytes + byte_off) & 3) * 8;
-        uint32_t w[4];
-        w[0] = __builtin_amdgcn_alignbit(d[t][1], d[t][0], sh);
-        w[1] = __builtin_amdgcn_alignbit(d[t][2], d[t][1], sh);
-        w[2] = __builtin_amdgcn_alignbit(d[t][3], d[t][2], sh);
-        w[3] = d[t][3] >> sh;
-        float x[16];
+        for (int t = 0; t < R; ++t) {
+            rn[t] = rn_nxt[t];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            float2 cw = cb_lds[field<BITS>(w, k)];
-            x[2 * k] = sig[k] * cw.x;
-            x[2 * k + 1] = sig[k] * cw.y;
+            for (int q = 0; q < 4; ++q) d[t][q] = nxt[t][q];
         }
-        fwht_wave<B>(x, ls);
-        const float a = rn[t] * p.inv_sqrt_block;               // row factor r * block^-1/2
-        const bool store = active && row <= last_row;
-        if (OUT_BF16) {
-            uint32_t o[8];
+        if (group + waves_per_slab < n_groups) {
 #pragma unroll
-            for (int e = 0; e < 16; e += 2) {
-                floatx2_t v = {(x[e] * a) * qs[e], (x[e + 1] * a) * qs[e + 1]};
-                o[e >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+            for (int t = 0; t < R; ++t) {
+                const int row = min((group + waves_per_slab) * R + t, last_row);
+                load_group(nxt[t], pk32, (int64_t)row * p.row_bytes + byte_off, total_dw);
+                rn_nxt[t] = norms[row];
             }
-            if (store) {
-                uint4 *dst = reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(out) + (int64_t)row * ldo + col0);
-                dst[0] = make_uint4(o[0], o[1], o[2], o[3]);
-                dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
-            }
-        } else if (store) {
-            float4 *dst = reinterpret_cast<float4 *>(reinterpret_cast<float *>(out) + (int64_t)row * ldo + col0);
+        }
 #pragma unroll
-            for (int e = 0; e < 16; e += 4)
-                dst[e >> 2] = make_float4((x[e] * a) * qs[e], (x[e + 1] * a) * qs[e + 1], (x[e + 2] * a) * qs[e + 2],
-                                          (x[e + 3] * a) * qs[e + 3]);
+        for (int t = 0; t < R; ++t) {
+            const int row = group * R + t;
+            const int sh = (int)(((int64_t)min(row, last_row) * p.row_bytes + byte_off) & 3) * 8;
+            uint32_t w[4];
+            w[0] = __builtin_amdgcn_alignbit(d[t][1], d[t][0], sh);
+            w[1] = __builtin_amdgcn_alignbit(d[t][2], d[t][1], sh);
+            w[2] = __builtin_amdgcn_alignbit(d[t][3], d[t][2], sh);
+            w[3] = d[t][3] >> sh;
+            float x[16];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                float2 cw = cb_lds[field<BITS>(w, k)];
+                x[2 * k] = sig[k] * cw.x;
+                x[2 * k + 1] = sig[k] * cw.y;
+            }
+            fwht_wave<B>(x, ls);
+            const float a = rn[t] * p.inv_sqrt_block;           // row factor r * block^-1/2
+            if (OUT_BF16) {
+                uint32_t o[8];
+#pragma unroll
+                for (int e = 0; e < 16; e += 2) {
+                    floatx2_t v = {(x[e] * a) * qs[e], (x[e + 1] * a) * qs[e + 1]};
+                    o[e >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+                }
+                // lane `pos` owns bytes [32 pos, 32 pos + 32) of the chunk; lane l stores bytes [16 l, +16) and [1024 + 16 l, +16)
+                bounce[2 * pos] = make_uint4(o[0], o[1], o[2], o[3]);
+                bounce[2 * pos + 1] = make_uint4(o[4], o[5], o[6], o[7]);
+                __builtin_amdgcn_wave_barrier();
+                const uint4 lo = bounce[lane], hi = bounce[64 + lane];
+                __builtin_amdgcn_wave_barrier();
+                if (row <= last_row) {
+                    uint4 *dst = reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(out) + (int64_t)row * ldo + slab * SLAB);
+                    if (8 * lane < slab_cols) dst[lane] = lo;
+                    if (512 + 8 * lane < slab_cols) dst[64 + lane] = hi;
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; e += 4)
+                    bounce[4 * pos + (e >> 2)] = __builtin_bit_cast(uint4, make_float4((x[e] * a) * qs[e], (x[e + 1] * a) * qs[e + 1],
+                                                                                      (x[e + 2] * a) * qs[e + 2], (x[e + 3] * a) * qs[e + 3]));
+                __builtin_amdgcn_wave_barrier();
+                uint4 v[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) v[q] = bounce[64 * q + lane];
+                __builtin_amdgcn_wave_barrier();
+                if (row <= last_row) {
+                    uint4 *dst = reinterpret_cast<uint4 *>(reinterpret_cast<float *>(out) + (int64_t)row * ldo + slab * SLAB);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        if (256 * q + 4 * lane < slab_cols) dst[64 * q + lane] = v[q];
+                }
+            }
         }
     }
 }
@@ -174,7 +215,8 @@ bool fast_decode_supported(const Problem &p) {
     return p.block >= 64;                                        // 64, 128, 256, 512, 1024
 }
 
-constexpr int DF_ROWS = 4;   // rows per wave
+constexpr int DF_ROWS = 4;            // rows a wave handles per step
+constexpr int DF_BLOCKS_PER_CU = 6;    // resident blocks per compute unit the grid is sized for
 
 template <int BITS, int B>
 static hipError_t launch_bb(const uint8_t *packed, const float *norms, const Problem &p, void *out, int64_t ldo,
@@ -187,16 +229,21 @@ static hipError_t launch_bb(const uint8_t *packed, const float *norms, const Pro
         return hipErrorNotSupported;
     if ((reinterpret_cast<uintptr_t>(packed) & 3)) return hipErrorNotSupported;
     const int n_slabs = (p.d_in + SLAB - 1) / SLAB;
-    const int64_t n_waves = (int64_t)n_slabs * ((p.d_out + DF_ROWS - 1) / DF_ROWS);
-    const int64_t blocks = (n_waves + DF_WAVES - 1) / DF_WAVES;
-    if (blocks > 0x7fffffff) return hipErrorNotSupported;
-    const size_t lds = (size_t)p.K * sizeof(float2);
+    const int n_groups = (p.d_out + DF_ROWS - 1) / DF_ROWS;
+    // waves that share a slab: enough to fill the machine (256 CUs x DF_BLOCKS_PER_CU blocks), no more than the work
+    int max_wps = (256 * DF_BLOCKS_PER_CU * DF_WAVES) / n_slabs;
+    if (max_wps < 1) max_wps = 1;
+    const int steps = (n_groups + max_wps - 1) / max_wps;           // row groups each wave walks through
+    const int waves_per_slab = (n_groups + steps - 1) / steps;     // evened out: no wave does more than `steps`
+    const int64_t n_waves = (int64_t)waves_per_slab * n_slabs;
+    const unsigned blocks = (unsigned)((n_waves + DF_WAVES - 1) / DF_WAVES);
+    const size_t lds = (size_t)p.K * sizeof(float2) + (size_t)DF_WAVES * (out_bf16 ? 2048 : 4096);
     if (out_bf16)
-        hipLaunchKernelGGL((k_decode_fast<BITS, B, true, DF_ROWS>), dim3((unsigned)blocks), dim3(DF_THREADS), lds, p.stream,
-                           packed, norms, p, out, ldo, n_slabs);
+        hipLaunchKernelGGL((k_decode_fast<BITS, B, true, DF_ROWS>), dim3(blocks), dim3(DF_THREADS), lds, p.stream, packed,
+                           norms, p, out, ldo, n_slabs, waves_per_slab);
     else
-        hipLaunchKernelGGL((k_decode_fast<BITS, B, false, DF_ROWS>), dim3((unsigned)blocks), dim3(DF_THREADS), lds, p.stream,
-                           packed, norms, p, out, ldo, n_slabs);
+        hipLaunchKernelGGL((k_decode_fast<BITS, B, false, DF_ROWS>), dim3(blocks), dim3(DF_THREADS), lds, p.stream, packed,
+                           norms, p, out, ldo, n_slabs, waves_per_slab);
     return hipGetLastError();
 }
 

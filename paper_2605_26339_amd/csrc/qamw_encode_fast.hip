@@ -1,9 +1,295 @@
-// Shape-specialised encoder (placeholder: not yet enabled).
+// Shape-specialised QAM-W encoder (Sec. 3.1 with the channel scaling of Sec. B.2).
+//
+// A wave owns one row's slab of 1024 columns = 512 pairs, 8 pairs per lane.  The front half
+// (scale, normalise, sign, block Walsh-Hadamard, pair gain) runs in registers and reproduces
+// the library's fp32 arithmetic bit for bit.  The nearest-codeword search then scores all K
+// codewords for the lane's 8 points with the expansion  ||c||^2 - 2 x.c  (2 FMA per evaluation,
+// codewords broadcast from LDS), keeping per point the best 16-codeword chunk and the best
+// score outside it.  The expansion only SHORTLISTS: the winner is decided by exact fp32 squared
+// distances inside the best chunk when the runner-up chunk is provably out of reach, and by an
+// exact wave-cooperative scan of the whole codebook otherwise (rare).  Lowest index wins ties.
 #include "qamw_common.hpp"
 #include "qamw_internal.hpp"
+#include "qamw_wave_fwht.hpp"
+
 namespace qamw {
-bool fast_encode_supported(const Problem &) { return false; }
-hipError_t launch_encode_fast(const void *, int, int64_t, const Problem &, const float *, uint8_t *) {
-    return hipErrorNotSupported;
+
+constexpr int EF_THREADS = 256;
+constexpr int EF_WAVES = EF_THREADS / WAVE;
+constexpr int ESLAB = 1024;
+constexpr int NPT = 8;        // points (pairs) per lane
+constexpr int CHUNK = 16;     // codewords per shortlist chunk
+
+__device__ __forceinline__ float min3(float a, float b, float c) { return __builtin_fminf(__builtin_fminf(a, b), c); }
+
+// Exact fp32 squared distance, the quantity that decides the index.
+__device__ __forceinline__ float dist2(float x0, float x1, float2 c) {
+    float e0 = x0 - c.x, e1 = x1 - c.y;
+    return __builtin_fmaf(e1, e1, e0 * e0);
 }
+
+template <int DTYPE, int B>
+__global__ __launch_bounds__(EF_THREADS) void k_encode_fast(const void *__restrict__ W, int64_t ldw, Problem p,
+                                                            const float *__restrict__ norms,
+                                                            uint8_t *__restrict__ packed, int n_slabs, int n_items) {
+    extern __shared__ float lds_raw[];
+    float2 *c01 = reinterpret_cast<float2 *>(lds_raw);          // K x (c0, c1)
+    float *cn = lds_raw + 2 * p.K;                              // K x ||c||^2
+    __shared__ float red[EF_WAVES];
+
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int wid = threadIdx.x >> 6;
+    const int K = p.K;
+
+    // stage the codebook; R^2 = max ||c||^2 enters the shortlist's error bound
+    const float2 *cbk = reinterpret_cast<const float2 *>(p.codebook);
+    float rmax2 = 0.0f;
+    for (int i = threadIdx.x; i < K; i += EF_THREADS) {
+        float2 c = cbk[i];
+        float n2 = __builtin_fmaf(c.y, c.y, c.x * c.x);
+        c01[i] = c;
+        cn[i] = n2;
+        rmax2 = fmaxf(rmax2, n2);
+    }
+#pragma unroll
+    for (int m = 1; m < WAVE; m <<= 1) rmax2 = fmaxf(rmax2, __shfl_xor(rmax2, m, WAVE));
+    if (lane == 0) red[wid] = rmax2;
+    __syncthreads();
+    rmax2 = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    const float R = sqrtf(rmax2) * 1.000001f;
+
+    const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * EF_WAVES + wid);
+    if (item >= n_items) return;
+    const int row = item / n_slabs, slab = item - row * n_slabs;
+    const LaneSigns<B> ls(lane);
+    const int pos = slab_pos(lane);
+    const int col0 = slab * ESLAB + 16 * pos;
+    const bool active = col0 < p.d_in;
+    const int c = active ? col0 : 0;
+
+    // ---------------- front half: x_k = (F S (W D_s / r))_pair k / sigma_k, in registers
+    float x[16];
+    {
+        const int64_t base = (int64_t)row * ldw + c;
+        if (DTYPE == 0) {
+            const float4 *w4 = reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(W) + base);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                float4 v = w4[t];
+                x[4 * t] = v.x; x[4 * t + 1] = v.y; x[4 * t + 2] = v.z; x[4 * t + 3] = v.w;
+            }
+        } else {
+            const uint4 *w4 = reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(W) + base);
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                uint4 v = w4[t];
+                const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    x[8 * t + 2 * q] = __uint_as_float(u[q] << 16);
+                    x[8 * t + 2 * q + 1] = __uint_as_float(u[q] & 0xFFFF0000u);
+                }
+            }
+        }
+        if (p.chan_scale) {
+            const float4 *s4 = reinterpret_cast<const float4 *>(p.chan_scale + c);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                float4 v = s4[t];
+                x[4 * t] *= v.x; x[4 * t + 1] *= v.y; x[4 * t + 2] *= v.z; x[4 * t + 3] *= v.w;
+            }
+        }
+        const float r = norms[row];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) x[e] = (r > 0.0f) ? x[e] / r : 0.0f;      // IEEE division
+        if (p.signs) {
+            const uint4 sg = *reinterpret_cast<const uint4 *>(p.signs + c);
+            const uint32_t wds[4] = {sg.x, sg.y, sg.z, sg.w};
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                uint32_t neg = (wds[e >> 2] >> (8 * (e & 3) + 7)) & 1u;
+                x[e] = __uint_as_float(__float_as_uint(x[e]) ^ (neg << 31));
+            }
+        }
+        fwht_wave<B>(x, ls);
+        float g[NPT];
+        if (p.pair_sigma) {
+            const float4 *g4 = reinterpret_cast<const float4 *>(p.pair_sigma + (c >> 1));
+            float4 a = g4[0], b = g4[1];
+            const float sg8[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+            for (int k = 0; k < NPT; ++k) g[k] = 1.0f / sg8[k];                   // IEEE division
+        } else {
+#pragma unroll
+            for (int k = 0; k < NPT; ++k) g[k] = p.g_default;
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) x[e] = ((x[e] * ls.parity) * p.inv_sqrt_block) * g[e >> 1];
+    }
+
+    // ---------------- shortlist: best chunk by the expansion score
+    float a0[NPT], a1[NPT], m1[NPT], m2[NPT];
+    int best[NPT];
+#pragma unroll
+    for (int j = 0; j < NPT; ++j) {
+        a0[j] = -2.0f * x[2 * j];
+        a1[j] = -2.0f * x[2 * j + 1];
+        m1[j] = INFINITY;
+        m2[j] = INFINITY;
+        best[j] = 0;
+    }
+    const float4 *c01v = reinterpret_cast<const float4 *>(c01);  // two codewords per float4
+    const float4 *cnv = reinterpret_cast<const float4 *>(cn);    // four norms per float4
+    const int n_chunks = K / CHUNK;
+    for (int ch = 0; ch < n_chunks; ++ch) {
+        float cx[CHUNK], cy[CHUNK], cq[CHUNK];
+#pragma unroll
+        for (int t = 0; t < CHUNK / 2; ++t) {
+            float4 v = c01v[ch * (CHUNK / 2) + t];
+            cx[2 * t] = v.x; cy[2 * t] = v.y; cx[2 * t + 1] = v.z; cy[2 * t + 1] = v.w;
+        }
+#pragma unroll
+        for (int t = 0; t < CHUNK / 4; ++t) {
+            float4 v = cnv[ch * (CHUNK / 4) + t];
+            cq[4 * t] = v.x; cq[4 * t + 1] = v.y; cq[4 * t + 2] = v.z; cq[4 * t + 3] = v.w;
+        }
+#pragma unroll
+        for (int j = 0; j < NPT; ++j) {
+            float s[CHUNK];
+#pragma unroll
+            for (int k = 0; k < CHUNK; ++k) s[k] = __builtin_fmaf(a0[j], cx[k], __builtin_fmaf(a1[j], cy[k], cq[k]));
+            float t0 = min3(s[0], s[1], s[2]);
+            float t1 = min3(s[3], s[4], s[5]);
+            float t2 = min3(s[6], s[7], s[8]);
+            float t3 = min3(s[9], s[10], s[11]);
+            float t4 = min3(s[12], s[13], s[14]);
+            float cm = min3(min3(t0, t1, t2), min3(t3, t4, s[15]), INFINITY);
+            best[j] = (cm < m1[j]) ? ch : best[j];
+            m2[j] = __builtin_amdgcn_fmed3f(m1[j], m2[j], cm);   // m1 <= m2: second smallest chunk minimum
+            m1[j] = __builtin_fminf(m1[j], cm);
+        }
+    }
+
+    // ---------------- decide: exact distances inside the best chunk, or the full exact scan
+    // Error model.  n1 = |x0|+|x1| >= ||x||.  Every computed score differs from the true
+    // ||c||^2 - 2 x.c by at most E(c) = 2^-21 (||c|| + n1)^2.  The true nearest codeword and every
+    // codeword that could be mistaken for it lie within rho = d_best + 1/16 of x, i.e. have norm at
+    // most n1 + rho, so for them E <= eps = 2^-21 (2 n1 + rho)^2; codewords further out score at least
+    // 2^-8 worse than the minimum and cannot interfere.  If the second-best chunk's minimum
+    // exceeds the best by more than 2 eps, the nearest codeword is inside the best chunk.
+    int idx[NPT];
+    unsigned flagged = 0;
+#pragma unroll
+    for (int j = 0; j < NPT; ++j) {
+        const float x0 = x[2 * j], x1 = x[2 * j + 1];
+        const float n1 = fabsf(x0) + fabsf(x1);
+        const float emax = 4.77e-7f * (R + n1) * (R + n1);                     // 2^-21 (R + n1)^2
+        const float xx = __builtin_fmaf(x1, x1, x0 * x0);
+        const float d2 = fmaxf(m1[j] + xx * 1.000001f + emax, 0.0f);           // >= true best squared distance
+        const float rho = sqrtf(d2) * 1.000001f + 0.0625f;
+        const float eps = 4.78e-7f * (2.0f * n1 + rho) * (2.0f * n1 + rho);
+        const bool safe = (m2[j] - m1[j] > 2.0f * eps) && (emax < 1.0e-3f);
+        float bd = INFINITY;
+        int bi = best[j] * CHUNK;
+#pragma unroll
+        for (int k = 0; k < CHUNK; ++k) {
+            float dd = dist2(x0, x1, c01[best[j] * CHUNK + k]);
+            if (dd < bd) {
+                bd = dd;
+                bi = best[j] * CHUNK + k;
+            }
+        }
+        idx[j] = bi;
+        if (!safe) flagged |= 1u << j;
+    }
+#pragma unroll
+    for (int j = 0; j < NPT; ++j) {
+        unsigned long long mask = __ballot((flagged >> j) & 1u);
+        while (mask) {
+            const int src = __ffsll((long long)mask) - 1;
+            mask &= mask - 1;
+            const float x0 = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(x[2 * j]), src));
+            const float x1 = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(x[2 * j + 1]), src));
+            float bd = INFINITY;
+            int bi = 0x7fffffff;
+            for (int k = lane; k < K; k += WAVE) {
+                float dd = dist2(x0, x1, c01[k]);
+                if (dd < bd) {
+                    bd = dd;
+                    bi = k;
+                }
+            }
+#pragma unroll
+            for (int m = 1; m < WAVE; m <<= 1) {
+                float od = __shfl_xor(bd, m, WAVE);
+                int oi = __shfl_xor(bi, m, WAVE);
+                if (od < bd || (od == bd && oi < bi)) {
+                    bd = od;
+                    bi = oi;
+                }
+            }
+            if (lane == src) idx[j] = bi;
+        }
+    }
+
+    // ---------------- pack: the lane's 8 fields are exactly `bits` bytes, byte aligned in the row
+    if (active) {
+        const int bits = p.bits;
+        uint8_t *dst = packed + (int64_t)row * p.row_bytes + (int64_t)(c >> 4) * bits;
+        unsigned __int128 acc = 0;
+#pragma unroll
+        for (int j = 0; j < NPT; ++j) acc |= (unsigned __int128)(unsigned)idx[j] << (j * bits);
+        for (int t = 0; t < bits; ++t) dst[t] = (uint8_t)(acc >> (8 * t));
+        if (col0 + 16 == p.d_in) {                              // last lane of the row zeroes the padding
+            const int64_t used = (int64_t)(p.d_in >> 4) * bits;
+            uint8_t *rowp = packed + (int64_t)row * p.row_bytes;
+            for (int64_t t = used; t < p.row_bytes; ++t) rowp[t] = 0;
+        }
+    }
+}
+
+bool fast_encode_supported(const Problem &p) {
+    const int unit = p.block > 16 ? p.block : 16;
+    if (p.d_in % unit) return false;
+    if (p.K % CHUNK || p.bits > 11) return false;
+    return p.block >= 64;
+}
+
+template <int DTYPE, int B>
+static hipError_t launch_db(const void *W, int64_t ldw, const Problem &p, const float *norms, uint8_t *packed) {
+    const int n_slabs = (p.d_in + ESLAB - 1) / ESLAB;
+    const int64_t n_items = (int64_t)p.d_out * n_slabs;
+    if (n_items > 0x7fffffff) return hipErrorNotSupported;
+    const unsigned blocks = (unsigned)((n_items + EF_WAVES - 1) / EF_WAVES);
+    const size_t lds = (size_t)p.K * 3 * sizeof(float);
+    hipLaunchKernelGGL((k_encode_fast<DTYPE, B>), dim3(blocks), dim3(EF_THREADS), lds, p.stream, W, ldw, p, norms, packed,
+                       n_slabs, (int)n_items);
+    return hipGetLastError();
+}
+
+template <int DTYPE>
+static hipError_t launch_d(const void *W, int64_t ldw, const Problem &p, const float *norms, uint8_t *packed) {
+    switch (p.block) {
+        case 64: return launch_db<DTYPE, 64>(W, ldw, p, norms, packed);
+        case 128: return launch_db<DTYPE, 128>(W, ldw, p, norms, packed);
+        case 256: return launch_db<DTYPE, 256>(W, ldw, p, norms, packed);
+        case 512: return launch_db<DTYPE, 512>(W, ldw, p, norms, packed);
+        case 1024: return launch_db<DTYPE, 1024>(W, ldw, p, norms, packed);
+        default: return hipErrorNotSupported;
+    }
+}
+
+hipError_t launch_encode_fast(const void *W, int dtype, int64_t ldw, const Problem &p, const float *norms,
+                              uint8_t *packed) {
+    // vector loads: rows and side arrays must be 16-byte aligned
+    const int64_t row_align = dtype == 0 ? 4 : 8;
+    bool ok = (ldw % row_align == 0) && ((reinterpret_cast<uintptr_t>(W) & 15) == 0) &&
+              (((reinterpret_cast<uintptr_t>(p.chan_scale) | reinterpret_cast<uintptr_t>(p.signs) |
+                 reinterpret_cast<uintptr_t>(p.pair_sigma) | reinterpret_cast<uintptr_t>(p.codebook)) & 15) == 0);
+    hipError_t e = hipErrorNotSupported;
+    if (ok) e = dtype == 0 ? launch_d<0>(W, ldw, p, norms, packed) : launch_d<1>(W, ldw, p, norms, packed);
+    if (e == hipErrorNotSupported) return launch_encode_general(W, dtype, ldw, p, norms, packed);
+    return e;
+}
+
 }  // namespace qamw
