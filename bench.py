@@ -46,6 +46,7 @@ def build_workload(wl, layers, device):
             W = synth.weight_device(synth.seed_for(wl.config_id, layer, name), d_out, d_in, wl.row_sigma, wl.dtype, device)
             rb = qamw.packed_row_bytes(d_in, wl.bits)
             mats.append(dict(name=f"L{layer}.{name}", W=W, s=s, sg=sg, d_out=d_out, d_in=d_in,
+                             sigma=torch.empty(d_in // 2, dtype=torch.float32, device=device),
                              packed=torch.empty((d_out, rb), dtype=torch.uint8, device=device),
                              norms=torch.empty(d_out, dtype=torch.float32, device=device),
                              out=torch.empty((d_out, d_in), dtype=torch.bfloat16, device=device)))
@@ -59,11 +60,12 @@ def run_step(mats, wl, cb, timed):
     from paper_2605_26339_amd import qamw
 
     ev = []
+    ws = run_step.workspace
     for m in mats:
         e = [torch.cuda.Event(enable_timing=True) for _ in range(4)] if timed else None
         if timed:
             e[0].record()
-        sigma = qamw.calibrate_sigma(m["W"], wl.block, chan_scale=m["s"], signs=m["sg"])
+        sigma = qamw.calibrate_sigma(m["W"], wl.block, chan_scale=m["s"], signs=m["sg"], workspace=ws, out=m["sigma"])
         if timed:
             e[1].record()
         qamw.encode(m["W"], cb, wl.bits, wl.block, chan_scale=m["s"], signs=m["sg"], pair_sigma=sigma,
@@ -134,6 +136,8 @@ def main():
     cb_host, cb_mse, cb_iters = qamw.train_codebook(wl.bits, 1 << 20, seed=0)
     cb = torch.from_numpy(cb_host).to(dev)
     mats = build_workload(wl, layers, dev)
+    run_step.workspace = torch.empty(max(qamw.calibrate_workspace_bytes(m["d_in"], m["d_out"]) for m in mats),
+                                     dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
 
     for _ in range(args.warmup):

@@ -12,8 +12,8 @@
  * Conventions
  *   - C ABI, every function returns an int status (QAMW_OK = 0).  No exception crosses the boundary.
  *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device memory of the
- *     current device.  The caller owns every buffer; the library allocates no device memory and
- *     keeps no state between calls (qamw_encode_noalloc-style variants, if present, say otherwise).
+ *     current device.  The caller owns every buffer, scratch included; the library allocates no
+ *     device memory and keeps no state between calls (qamw_set_kernel_path is the one switch).
  *   - Device entry points validate their arguments on the host, synchronously, BEFORE any launch
  *     and return an error code without touching the outputs; otherwise they enqueue their kernels
  *     on `stream` (a hipStream_t passed as void*, NULL = the default stream) and return without
@@ -121,11 +121,15 @@ int qamw_train_codebook(int bits, uint64_t n_samples, uint64_t seed, int max_ite
 /* Eq. 1: sigma_k = mean over the first n = min(d_out, max_rows) rows of |z_k| / sqrt(pi/2), where
  * z_k are the pairs of the unit-normalised, rotated rows (encoder steps 1-3); amplitudes and the
  * mean in fp64; an estimate that is not positive is replaced by 1/sqrt(d_in).
- * row_norms_ws: device workspace of n floats (receives those rows' norms).
- * sigma_out: device, P floats.  max_rows < 1 -> INVALID_ARG. */
+ * workspace: device scratch of at least qamw_calibrate_workspace_bytes() bytes, 16-byte aligned,
+ * owned by the caller (holds those rows' norms and per-row-group partial sums; contents are
+ * unspecified afterwards).  sigma_out: device, P floats.
+ * Errors: max_rows < 1, workspace NULL / too small / misaligned -> INVALID_ARG. */
+int qamw_calibrate_workspace_bytes(int d_in, int d_out, int max_rows, size_t *bytes_out);
 int qamw_calibrate_sigma(const void *W, int dtype, int d_out, int d_in, int64_t ldw,
                          const float *chan_scale, const int8_t *signs, int hadamard_block,
-                         int max_rows, float *row_norms_ws, float *sigma_out, void *stream);
+                         int max_rows, void *workspace, size_t workspace_bytes, float *sigma_out,
+                         void *stream);
 
 /* Encoder of Sec. 3.1 with the channel scaling of Sec. B.2.
  * packed_out: device, d_out * qamw_packed_row_bytes(d_in, bits) bytes, fully overwritten.

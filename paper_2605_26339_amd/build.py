@@ -10,7 +10,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqamw.so")
 
-SOURCES = ["qamw_host.cpp", "qamw_api.hip", "qamw_general.hip", "qamw_decode_fast.hip", "qamw_encode_fast.hip"]
+SOURCES = ["qamw_host.cpp", "qamw_api.hip", "qamw_general.hip", "qamw_decode_fast.hip", "qamw_encode_fast.hip",
+           "qamw_calibrate_fast.hip"]
 
 # -ffp-contract=off: the codec's fp32 steps are rounded one by one; fused multiply-adds appear only
 # where the source asks for them.  Packed fp32 instructions are disabled for the device pass.
@@ -26,6 +27,11 @@ def hipcc() -> str:
         if cand and (os.path.isabs(cand) and os.path.exists(cand) or not os.path.isabs(cand)):
             return cand
     raise RuntimeError("hipcc not found")
+
+
+# Per-file additions.  The encoder's inner loop is min/med3 chains; without this flag every fminf
+# is preceded by a canonicalising v_max.  NaN inputs are outside the library's contract.
+EXTRA_FLAGS = {"qamw_encode_fast.hip": ["-fno-honor-nans"]}
 
 
 def sources():
@@ -48,7 +54,7 @@ def build(verbose: bool = True) -> str:
     procs = []
     for src in sources():
         obj = os.path.join(bdir, os.path.basename(src) + ".o")
-        cmd = [hipcc(), *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-x", "hip", "-c", src, "-o", obj]
+        cmd = [hipcc(), *HIPCC_FLAGS, *EXTRA_FLAGS.get(os.path.basename(src), []), "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-x", "hip", "-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

@@ -38,6 +38,12 @@ qamw::Problem make_problem(int d_out, int d_in, const float *chan_scale, const i
     return p;
 }
 
+hipError_t launch_norms(const void *W, int dtype, int64_t ldw, int n_rows, const qamw::Problem &p, float *norms) {
+    hipError_t e = hipSuccess;
+    if (g_kernel_path.load() == 0 && qamw::launch_row_norms_fast(W, dtype, ldw, n_rows, p, norms, &e)) return e;
+    return qamw::launch_row_norms(W, dtype, ldw, n_rows, p, norms);
+}
+
 int decode_any(const uint8_t *packed, const float *row_norms, int d_out, int d_in, const float *chan_scale,
                const int8_t *signs, const float *pair_sigma, const float *codebook, int bits, int block, void *out,
                int64_t ldo, void *stream, bool bf16) {
@@ -63,20 +69,38 @@ int qamw_set_kernel_path(int path) {
     return g_kernel_path.exchange(path);
 }
 
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+int qamw_calibrate_workspace_bytes(int d_in, int d_out, int max_rows, size_t *bytes_out) {
+    if (!bytes_out || max_rows < 1 || d_out <= 0) return QAMW_ERR_INVALID_ARG;
+    if (d_in <= 0 || (d_in & 1)) return QAMW_ERR_SHAPE;
+    const int n = d_out < max_rows ? d_out : max_rows;
+    *bytes_out = align_up((size_t)n * sizeof(float), 256) + qamw::calibrate_partial_bytes(d_in, n);
+    return QAMW_OK;
+}
+
 int qamw_calibrate_sigma(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
-                         const int8_t *signs, int hadamard_block, int max_rows, float *row_norms_ws,
-                         float *sigma_out, void *stream) {
-    if (!W || !row_norms_ws || !sigma_out || max_rows < 1) return QAMW_ERR_INVALID_ARG;
+                         const int8_t *signs, int hadamard_block, int max_rows, void *workspace,
+                         size_t workspace_bytes, float *sigma_out, void *stream) {
+    if (!W || !workspace || !sigma_out || max_rows < 1) return QAMW_ERR_INVALID_ARG;
     if (dtype != QAMW_DTYPE_F32 && dtype != QAMW_DTYPE_BF16) return QAMW_ERR_INVALID_ARG;
     int rc = check_common(d_out, d_in, 1, hadamard_block);
     if (rc != QAMW_OK) return rc;
     if (ldw < d_in) return QAMW_ERR_SHAPE;
+    size_t need = 0;
+    qamw_calibrate_workspace_bytes(d_in, d_out, max_rows, &need);
+    if (workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15)) return QAMW_ERR_INVALID_ARG;
     qamw::Problem p = make_problem(d_out, d_in, chan_scale, signs, nullptr, nullptr, 1, hadamard_block, stream);
     const int n = d_out < max_rows ? d_out : max_rows;
-    if (qamw::launch_row_norms(W, dtype, ldw, n, p, row_norms_ws) != hipSuccess) return QAMW_ERR_DEVICE;
-    if (qamw::launch_calibrate_general(W, dtype, ldw, n, p, row_norms_ws, sigma_out) != hipSuccess)
-        return QAMW_ERR_DEVICE;
-    return QAMW_OK;
+    float *row_norms = static_cast<float *>(workspace);
+    double *partial = reinterpret_cast<double *>(static_cast<char *>(workspace) + align_up((size_t)n * sizeof(float), 256));
+    if (launch_norms(W, dtype, ldw, n, p, row_norms) != hipSuccess) return QAMW_ERR_DEVICE;
+    hipError_t e;
+    if (g_kernel_path.load() == 0 && qamw::fast_calibrate_supported(W, dtype, ldw, p))
+        e = qamw::launch_calibrate_fast(W, dtype, ldw, n, p, row_norms, partial, sigma_out);
+    else
+        e = qamw::launch_calibrate_general(W, dtype, ldw, n, p, row_norms, sigma_out);
+    return e == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
 }
 
 int qamw_encode(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
@@ -88,7 +112,7 @@ int qamw_encode(const void *W, int dtype, int d_out, int d_in, int64_t ldw, cons
     if (rc != QAMW_OK) return rc;
     if (ldw < d_in) return QAMW_ERR_SHAPE;
     qamw::Problem p = make_problem(d_out, d_in, chan_scale, signs, pair_sigma, codebook, bits, hadamard_block, stream);
-    if (qamw::launch_row_norms(W, dtype, ldw, d_out, p, row_norms_out) != hipSuccess) return QAMW_ERR_DEVICE;
+    if (launch_norms(W, dtype, ldw, d_out, p, row_norms_out) != hipSuccess) return QAMW_ERR_DEVICE;
     hipError_t e;
     if (g_kernel_path.load() == 0 && qamw::fast_encode_supported(p))
         e = qamw::launch_encode_fast(W, dtype, ldw, p, row_norms_out, packed_out);

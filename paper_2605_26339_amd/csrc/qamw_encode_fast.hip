@@ -8,17 +8,16 @@
 // score outside it.  The expansion only SHORTLISTS: the winner is decided by exact fp32 squared
 // distances inside the best chunk when the runner-up chunk is provably out of reach, and by an
 // exact wave-cooperative scan of the whole codebook otherwise (rare).  Lowest index wins ties.
-#include "qamw_common.hpp"
-#include "qamw_internal.hpp"
-#include "qamw_wave_fwht.hpp"
+#include "qamw_front.hpp"
 
 namespace qamw {
 
 constexpr int EF_THREADS = 256;
 constexpr int EF_WAVES = EF_THREADS / WAVE;
 constexpr int ESLAB = 1024;
+constexpr float BIG = 3.0e38f; // larger than any score or squared distance of finite inputs
 constexpr int NPT = 8;        // points (pairs) per lane
-constexpr int CHUNK = 16;     // codewords per shortlist chunk
+constexpr int CHUNK = 16;     // codewords per shortlist chunk: scored together, rechecked together
 
 __device__ __forceinline__ float min3(float a, float b, float c) { return __builtin_fminf(__builtin_fminf(a, b), c); }
 
@@ -69,49 +68,8 @@ __global__ __launch_bounds__(EF_THREADS) void k_encode_fast(const void *__restri
 
     // ---------------- front half: x_k = (F S (W D_s / r))_pair k / sigma_k, in registers
     float x[16];
+    rotated_unit_row<DTYPE, B>(x, W, (int64_t)row * ldw, c, norms[row], p, ls);
     {
-        const int64_t base = (int64_t)row * ldw + c;
-        if (DTYPE == 0) {
-            const float4 *w4 = reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(W) + base);
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                float4 v = w4[t];
-                x[4 * t] = v.x; x[4 * t + 1] = v.y; x[4 * t + 2] = v.z; x[4 * t + 3] = v.w;
-            }
-        } else {
-            const uint4 *w4 = reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(W) + base);
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                uint4 v = w4[t];
-                const uint32_t u[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    x[8 * t + 2 * q] = __uint_as_float(u[q] << 16);
-                    x[8 * t + 2 * q + 1] = __uint_as_float(u[q] & 0xFFFF0000u);
-                }
-            }
-        }
-        if (p.chan_scale) {
-            const float4 *s4 = reinterpret_cast<const float4 *>(p.chan_scale + c);
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                float4 v = s4[t];
-                x[4 * t] *= v.x; x[4 * t + 1] *= v.y; x[4 * t + 2] *= v.z; x[4 * t + 3] *= v.w;
-            }
-        }
-        const float r = norms[row];
-#pragma unroll
-        for (int e = 0; e < 16; ++e) x[e] = (r > 0.0f) ? x[e] / r : 0.0f;      // IEEE division
-        if (p.signs) {
-            const uint4 sg = *reinterpret_cast<const uint4 *>(p.signs + c);
-            const uint32_t wds[4] = {sg.x, sg.y, sg.z, sg.w};
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                uint32_t neg = (wds[e >> 2] >> (8 * (e & 3) + 7)) & 1u;
-                x[e] = __uint_as_float(__float_as_uint(x[e]) ^ (neg << 31));
-            }
-        }
-        fwht_wave<B>(x, ls);
         float g[NPT];
         if (p.pair_sigma) {
             const float4 *g4 = reinterpret_cast<const float4 *>(p.pair_sigma + (c >> 1));
@@ -124,7 +82,7 @@ __global__ __launch_bounds__(EF_THREADS) void k_encode_fast(const void *__restri
             for (int k = 0; k < NPT; ++k) g[k] = p.g_default;
         }
 #pragma unroll
-        for (int e = 0; e < 16; ++e) x[e] = ((x[e] * ls.parity) * p.inv_sqrt_block) * g[e >> 1];
+        for (int e = 0; e < 16; ++e) x[e] = x[e] * g[e >> 1];
     }
 
     // ---------------- shortlist: best chunk by the expansion score
@@ -134,8 +92,8 @@ __global__ __launch_bounds__(EF_THREADS) void k_encode_fast(const void *__restri
     for (int j = 0; j < NPT; ++j) {
         a0[j] = -2.0f * x[2 * j];
         a1[j] = -2.0f * x[2 * j + 1];
-        m1[j] = INFINITY;
-        m2[j] = INFINITY;
+        m1[j] = BIG;
+        m2[j] = BIG;
         best[j] = 0;
     }
     const float4 *c01v = reinterpret_cast<const float4 *>(c01);  // two codewords per float4
@@ -163,7 +121,7 @@ __global__ __launch_bounds__(EF_THREADS) void k_encode_fast(const void *__restri
             float t2 = min3(s[6], s[7], s[8]);
             float t3 = min3(s[9], s[10], s[11]);
             float t4 = min3(s[12], s[13], s[14]);
-            float cm = min3(min3(t0, t1, t2), min3(t3, t4, s[15]), INFINITY);
+            float cm = __builtin_fminf(min3(t0, t1, t2), min3(t3, t4, s[15]));
             best[j] = (cm < m1[j]) ? ch : best[j];
             m2[j] = __builtin_amdgcn_fmed3f(m1[j], m2[j], cm);   // m1 <= m2: second smallest chunk minimum
             m1[j] = __builtin_fminf(m1[j], cm);
@@ -189,7 +147,7 @@ __global__ __launch_bounds__(EF_THREADS) void k_encode_fast(const void *__restri
         const float rho = sqrtf(d2) * 1.000001f + 0.0625f;
         const float eps = 4.78e-7f * (2.0f * n1 + rho) * (2.0f * n1 + rho);
         const bool safe = (m2[j] - m1[j] > 2.0f * eps) && (emax < 1.0e-3f);
-        float bd = INFINITY;
+        float bd = BIG;
         int bi = best[j] * CHUNK;
 #pragma unroll
         for (int k = 0; k < CHUNK; ++k) {
@@ -201,6 +159,7 @@ __global__ __launch_bounds__(EF_THREADS) void k_encode_fast(const void *__restri
         }
         idx[j] = bi;
         if (!safe) flagged |= 1u << j;
+        asm volatile("" ::: "memory");                          // keep one point's gathers in flight at a time (register budget)
     }
 #pragma unroll
     for (int j = 0; j < NPT; ++j) {
@@ -210,7 +169,7 @@ __global__ __launch_bounds__(EF_THREADS) void k_encode_fast(const void *__restri
             mask &= mask - 1;
             const float x0 = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(x[2 * j]), src));
             const float x1 = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(x[2 * j + 1]), src));
-            float bd = INFINITY;
+            float bd = BIG;
             int bi = 0x7fffffff;
             for (int k = lane; k < K; k += WAVE) {
                 float dd = dist2(x0, x1, c01[k]);
@@ -282,10 +241,7 @@ static hipError_t launch_d(const void *W, int64_t ldw, const Problem &p, const f
 hipError_t launch_encode_fast(const void *W, int dtype, int64_t ldw, const Problem &p, const float *norms,
                               uint8_t *packed) {
     // vector loads: rows and side arrays must be 16-byte aligned
-    const int64_t row_align = dtype == 0 ? 4 : 8;
-    bool ok = (ldw % row_align == 0) && ((reinterpret_cast<uintptr_t>(W) & 15) == 0) &&
-              (((reinterpret_cast<uintptr_t>(p.chan_scale) | reinterpret_cast<uintptr_t>(p.signs) |
-                 reinterpret_cast<uintptr_t>(p.pair_sigma) | reinterpret_cast<uintptr_t>(p.codebook)) & 15) == 0);
+    const bool ok = front_alignment_ok(W, dtype, ldw, p) && ((reinterpret_cast<uintptr_t>(p.codebook) & 15) == 0);
     hipError_t e = hipErrorNotSupported;
     if (ok) e = dtype == 0 ? launch_d<0>(W, ldw, p, norms, packed) : launch_d<1>(W, ldw, p, norms, packed);
     if (e == hipErrorNotSupported) return launch_encode_general(W, dtype, ldw, p, norms, packed);

@@ -1,0 +1,70 @@
+// Encoder front half shared by the fast encode and calibration kernels (Sec. 3.1 steps 1-2 on
+// the channel-scaled row of Sec. B.2): a lane loads its 16 consecutive columns, scales them,
+// divides by the row norm, applies the sign mask and the wave runs the block Walsh-Hadamard
+// transform.  On return y[e] = (F S u)[col0 + e] exactly as the library's fp32 arithmetic defines it.
+#pragma once
+#include "qamw_common.hpp"
+#include "qamw_internal.hpp"
+#include "qamw_wave_fwht.hpp"
+
+namespace qamw {
+
+// c: first of the lane's 16 columns (multiple of 16, < d_in); r: the row's norm.
+// Requires 16-byte aligned rows and side arrays (checked on the host).
+template <int DTYPE, int B>
+__device__ __forceinline__ void rotated_unit_row(float (&y)[16], const void *__restrict__ W, int64_t row_base, int c,
+                                                 float r, const Problem &p, const LaneSigns<B> &ls) {
+    const int64_t base = row_base + c;
+    if (DTYPE == 0) {
+        const float4 *w4 = reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(W) + base);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            float4 v = w4[t];
+            y[4 * t] = v.x; y[4 * t + 1] = v.y; y[4 * t + 2] = v.z; y[4 * t + 3] = v.w;
+        }
+    } else {
+        const uint4 *w4 = reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(W) + base);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            uint4 v = w4[t];
+            const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {                       // bf16 is the upper half of an fp32
+                y[8 * t + 2 * q] = __uint_as_float(u[q] << 16);
+                y[8 * t + 2 * q + 1] = __uint_as_float(u[q] & 0xFFFF0000u);
+            }
+        }
+    }
+    if (p.chan_scale) {
+        const float4 *s4 = reinterpret_cast<const float4 *>(p.chan_scale + c);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            float4 v = s4[t];
+            y[4 * t] *= v.x; y[4 * t + 1] *= v.y; y[4 * t + 2] *= v.z; y[4 * t + 3] *= v.w;
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = (r > 0.0f) ? y[e] / r : 0.0f;          // IEEE division
+    if (p.signs) {
+        const uint4 sg = *reinterpret_cast<const uint4 *>(p.signs + c);
+        const uint32_t wds[4] = {sg.x, sg.y, sg.z, sg.w};
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            uint32_t neg = (wds[e >> 2] >> (8 * (e & 3) + 7)) & 1u;             // int8 -1: sign bit of the byte
+            y[e] = __uint_as_float(__float_as_uint(y[e]) ^ (neg << 31));
+        }
+    }
+    fwht_wave<B>(y, ls);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = (y[e] * ls.parity) * p.inv_sqrt_block;
+}
+
+// Host-side check of what the vector loads above assume.
+inline bool front_alignment_ok(const void *W, int dtype, int64_t ldw, const Problem &p) {
+    const int64_t row_align = dtype == 0 ? 4 : 8;
+    return (ldw % row_align == 0) && ((reinterpret_cast<uintptr_t>(W) & 15) == 0) &&
+           (((reinterpret_cast<uintptr_t>(p.chan_scale) | reinterpret_cast<uintptr_t>(p.signs) |
+              reinterpret_cast<uintptr_t>(p.pair_sigma)) & 15) == 0);
+}
+
+}  // namespace qamw

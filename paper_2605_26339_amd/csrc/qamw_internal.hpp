@@ -30,6 +30,15 @@ hipError_t launch_decode_general(const uint8_t *packed, const float *norms, cons
 hipError_t launch_calibrate_general(const void *W, int dtype, int64_t ldw, int n_rows, const Problem &p,
                                     const float *norms, float *sigma_out);
 
+// Vectorised row norms: returns false (nothing launched) when alignment rules it out.
+bool launch_row_norms_fast(const void *W, int dtype, int64_t ldw, int n_rows, const Problem &p, float *norms,
+                           hipError_t *err);
+// Two-step calibration through caller-provided partial sums (calibrate_partial_bytes() of them).
+size_t calibrate_partial_bytes(int d_in, int n_rows);
+bool fast_calibrate_supported(const void *W, int dtype, int64_t ldw, const Problem &p);
+hipError_t launch_calibrate_fast(const void *W, int dtype, int64_t ldw, int n_rows, const Problem &p, const float *norms,
+                                 double *partial, float *sigma_out);
+
 // Fast kernels: return hipErrorNotSupported when the shape is outside what they cover.
 bool fast_decode_supported(const Problem &p);
 hipError_t launch_decode_fast(const uint8_t *packed, const float *norms, const Problem &p, void *out,

@@ -18,7 +18,7 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
 
 EXPORTS = [
     "qamw_status_string", "qamw_packed_row_bytes", "qamw_paper_block_size", "qamw_bpw", "qamw_sign_mask",
-    "qamw_channel_scales", "qamw_train_codebook", "qamw_calibrate_sigma", "qamw_encode", "qamw_decode",
+    "qamw_channel_scales", "qamw_train_codebook", "qamw_calibrate_workspace_bytes", "qamw_calibrate_sigma", "qamw_encode", "qamw_decode",
     "qamw_decode_f32", "qamw_set_kernel_path",
 ]
 
@@ -52,7 +52,8 @@ def lib() -> C.CDLL:
         L.qamw_sign_mask.argtypes = [u64, i32, vp]
         L.qamw_channel_scales.argtypes = [vp, i32, C.c_float, vp]
         L.qamw_train_codebook.argtypes = [i32, u64, u64, i32, C.c_double, vp, C.POINTER(C.c_double), C.POINTER(i32)]
-        L.qamw_calibrate_sigma.argtypes = [vp, i32, i32, i32, i64, vp, vp, i32, i32, vp, vp, vp]
+        L.qamw_calibrate_workspace_bytes.argtypes = [i32, i32, i32, C.POINTER(C.c_size_t)]
+        L.qamw_calibrate_sigma.argtypes = [vp, i32, i32, i32, i64, vp, vp, i32, i32, vp, C.c_size_t, vp, vp]
         L.qamw_encode.argtypes = [vp, i32, i32, i32, i64, vp, vp, vp, vp, i32, i32, vp, vp, vp]
         L.qamw_decode.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, i64, vp]
         L.qamw_decode_f32.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, i64, vp]
@@ -146,17 +147,27 @@ def _require_cuda(*tensors):
             raise ValueError("device entry points take CUDA (HIP) tensors")
 
 
-def calibrate_sigma(W, block: int, chan_scale=None, signs=None, max_rows: int = 1024, stream=None):
-    """Eq. 1 pair scales of matrix W (torch CUDA tensor [d_out][d_in]).  Returns float32 [d_in/2]."""
+def calibrate_workspace_bytes(d_in: int, d_out: int, max_rows: int = 1024) -> int:
+    out = C.c_size_t()
+    _check(lib().qamw_calibrate_workspace_bytes(d_in, d_out, max_rows, C.byref(out)), "qamw_calibrate_workspace_bytes")
+    return int(out.value)
+
+
+def calibrate_sigma(W, block: int, chan_scale=None, signs=None, max_rows: int = 1024, workspace=None, out=None,
+                    stream=None):
+    """Eq. 1 pair scales of matrix W (torch CUDA tensor [d_out][d_in]).  Returns float32 [d_in/2].
+    `workspace` is a uint8 CUDA tensor of at least calibrate_workspace_bytes(); allocated if absent."""
     import torch
 
-    _require_cuda(W, chan_scale, signs)
+    _require_cuda(W, chan_scale, signs, workspace, out)
     d_out, d_in = W.shape
-    n = max(1, min(d_out, max_rows))
-    ws = torch.empty(n, dtype=torch.float32, device=W.device)
-    out = torch.empty(d_in // 2, dtype=torch.float32, device=W.device)
+    if workspace is None:
+        workspace = torch.empty(calibrate_workspace_bytes(d_in, d_out, max_rows), dtype=torch.uint8, device=W.device)
+    if out is None:
+        out = torch.empty(d_in // 2, dtype=torch.float32, device=W.device)
     _check(lib().qamw_calibrate_sigma(_ptr(W), _dtype_code(W), d_out, d_in, W.stride(0), _ptr(chan_scale), _ptr(signs),
-                                      block, max_rows, _ptr(ws), _ptr(out), _stream(stream)), "qamw_calibrate_sigma")
+                                      block, max_rows, _ptr(workspace), workspace.numel(), _ptr(out), _stream(stream)),
+           "qamw_calibrate_sigma")
     return out
 
 

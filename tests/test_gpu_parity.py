@@ -175,10 +175,11 @@ def test_config0_full_matrix(orc, codebooks):
     assert 0.02 < rel < 0.05
 
 
-def test_calibrate_sigma_matches_oracle(orc):
+def test_calibrate_sigma_matches_oracle(orc, kernel_path):
     for seed, d_out, d_in, block, dtype in [(61, 1500, 512, 128, "f32"), (62, 300, 2048, 1024, "bf16"),
-                                            (63, 64, 1280, 256, "f32"), (64, 10, 96, 2, "f32"), (65, 33, 5632, 512, "f32")]:
-        say(f"[calibrate] {d_out}x{d_in} b={block} {dtype}")
+                                            (63, 64, 1280, 256, "f32"), (64, 10, 96, 2, "f32"), (65, 33, 5632, 512, "f32"),
+                                            (66, 1027, 11008, 256, "bf16"), (67, 5, 3072, 64, "f32")]:
+        say(f"[calibrate] {d_out}x{d_in} b={block} {dtype} path={kernel_path}")
         case = Case(orc, seed, d_out, d_in, 5, block, dtype=dtype, sigma=None, codebook=np.zeros((32, 2), np.float32))
         want = orc.calibrate_sigma(case.W, block, chan_scale=case.s, signs=case.sg)
         got = qamw.calibrate_sigma(case.W_dev, block, chan_scale=case.s_dev, signs=case.sg_dev)

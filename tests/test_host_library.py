@@ -102,17 +102,28 @@ def test_device_entry_points_reject_bad_arguments_before_any_launch():
     assert enc(dtype=7) == qamw.ERR_INVALID_ARG
 
     def cal(**kw):
-        a = {**good, "max_rows": 1024, **kw}
+        a = {**good, "max_rows": 1024, "ws": p, "ws_bytes": 1 << 30, **kw}
         return L.qamw_calibrate_sigma(a["W"], a["dtype"], a["d_out"], a["d_in"], a["ldw"], a["s"], a["sg"], a["block"],
-                                      a["max_rows"], a["norms"], a["packed"], a["stream"])
+                                      a["max_rows"], a["ws"], a["ws_bytes"], a["packed"], a["stream"])
 
     assert cal(W=None) == qamw.ERR_INVALID_ARG
-    assert cal(norms=None) == qamw.ERR_INVALID_ARG
+    assert cal(ws=None) == qamw.ERR_INVALID_ARG
     assert cal(packed=None) == qamw.ERR_INVALID_ARG
     assert cal(max_rows=0) == qamw.ERR_INVALID_ARG
     assert cal(block=3) == qamw.ERR_SHAPE
     assert cal(ldw=10) == qamw.ERR_SHAPE
     assert cal(dtype=2) == qamw.ERR_INVALID_ARG
+    need = qamw.calibrate_workspace_bytes(256, 8, 1024)
+    assert need >= 8 * 4 + 128 * 8
+    assert cal(ws_bytes=need - 1) == qamw.ERR_INVALID_ARG          # workspace too small
+    assert cal(ws=C.c_void_p(0x1004)) == qamw.ERR_INVALID_ARG      # workspace not 16-byte aligned
+    # the workspace grows with the rows used and the row length, and is capped by max_rows
+    assert qamw.calibrate_workspace_bytes(4096, 11008, 1024) == qamw.calibrate_workspace_bytes(4096, 1024, 1024)
+    assert qamw.calibrate_workspace_bytes(4096, 11008, 64) < qamw.calibrate_workspace_bytes(4096, 11008, 1024)
+    out = C.c_size_t()
+    assert L.qamw_calibrate_workspace_bytes(255, 8, 1024, C.byref(out)) == qamw.ERR_SHAPE
+    assert L.qamw_calibrate_workspace_bytes(256, 8, 0, C.byref(out)) == qamw.ERR_INVALID_ARG
+    assert L.qamw_calibrate_workspace_bytes(256, 8, 1024, None) == qamw.ERR_INVALID_ARG
 
 
 def test_kernel_path_switch():
