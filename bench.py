@@ -108,6 +108,17 @@ def cpu_baseline(wl, mats, cb_host):
             "decode_value": dec_bytes / (t2 - t1) / 1e9, "decode_unit": "GB/s"}
 
 
+def measured_traffic(workload):
+    """HBM bytes per launch from the committed rocprofv3 counter summary of this workload (or None)."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.json")
+    try:
+        with open(path) as f:
+            d = json.load(f)
+        return d if d.get("workload") == workload else None
+    except OSError:
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -140,6 +151,12 @@ def main():
                                      dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
 
+    # a plain copy of known size: the reference the HBM byte counters are scaled by (rocprofv3 --pmc runs)
+    probe_src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+    probe_dst = torch.empty_like(probe_src)
+    probe_dst.copy_(probe_src)
+    del probe_src, probe_dst
+
     for _ in range(args.warmup):
         run_step(mats, wl, cb, timed=False)
     torch.cuda.synchronize()
@@ -166,6 +183,7 @@ def main():
 
     enc_tflops = evals * FLOPS_PER_EVAL / (enc_ms * 1e-3) / 1e12
     dec_gbs = dec_bytes / (dec_ms * 1e-3) / 1e9
+    traffic = measured_traffic(wl.name) if layers == wl.layers else None
     result = {
         "metric": METRIC,
         "value": pairs / ((enc_ms + cal_ms) * 1e-3) / 1e9,
@@ -190,11 +208,11 @@ def main():
                    "gpairs_per_s": pairs / (dec_ms * 1e-3) / 1e9},
         "roofline": {"kernel": "qamw_encode (row norms + nearest-codeword kernel)", "bound": "alu",
                      "achieved": enc_tflops, "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s",
-                     "frac": enc_tflops / PEAK_FP32_TFLOPS, "traffic": None,
+                     "frac": enc_tflops / PEAK_FP32_TFLOPS, "traffic": traffic and traffic["encode"],
                      "avg_launch_ms": enc_ms / n_launch,
                      "algorithmic_flops_per_launch": evals * FLOPS_PER_EVAL / n_launch},
         "roofline_decode": {"kernel": "qamw_decode", "bound": "hbm", "achieved": dec_gbs, "peak": PEAK_HBM_GBS,
-                            "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS, "traffic": None,
+                            "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS, "traffic": traffic and traffic["decode"],
                             "avg_launch_ms": dec_ms / n_launch,
                             "algorithmic_bytes_per_launch": dec_bytes / n_launch},
         "wall_s_timed_region": wall,
