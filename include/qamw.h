@@ -151,6 +151,28 @@ int qamw_decode_f32(const uint8_t *packed, const float *row_norms, int d_out, in
                     const float *codebook, int bits, int hadamard_block, float *W_out, int64_t ldo,
                     void *stream);
 
+/* Several matrices that share codebook, bits and hadamard_block decoded to bf16 in ONE launch (the
+ * decoder of Sec. 3.2 is bandwidth bound and a single LLM projection matrix is only microseconds of
+ * HBM time, so per-launch ramp-up and tail are a large part of qamw_decode; a batch amortises them).
+ * items: HOST array of n_items descriptors (read during the call, not retained); every pointer
+ * inside is a device pointer with the meaning it has in qamw_decode.  1 <= n_items <= QAMW_MAX_BATCH.
+ * Results are identical to n_items calls of qamw_decode.  Items the fast kernel cannot take
+ * (shape, alignment) make the whole call fall back to one general launch per item.
+ * Errors: items NULL, n_items out of range, any item invalid as for qamw_decode. */
+typedef struct qamw_decode_item {
+    const uint8_t *packed;       /* d_out * qamw_packed_row_bytes(d_in, bits) bytes            */
+    const float *row_norms;      /* d_out floats                                               */
+    const float *chan_scale;     /* d_in floats or NULL                                        */
+    const int8_t *signs;         /* d_in int8 or NULL                                          */
+    const float *pair_sigma;     /* d_in/2 floats or NULL                                      */
+    uint16_t *W_out;             /* d_out rows of d_in bf16, leading dimension ldo             */
+    int64_t ldo;
+    int32_t d_out, d_in;
+} qamw_decode_item;
+enum { QAMW_MAX_BATCH = 16 };
+int qamw_decode_batch(const qamw_decode_item *items, int n_items, const float *codebook, int bits,
+                      int hadamard_block, void *stream);
+
 /* Which implementation the device entry points use: 0 = automatic (fast kernels when the shape
  * allows, otherwise the general ones), 1 = always the general kernels.  Process-wide, for tests
  * and measurements; returns the previous value. */

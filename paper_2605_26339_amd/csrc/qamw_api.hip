@@ -128,6 +128,35 @@ int qamw_decode(const uint8_t *packed, const float *row_norms, int d_out, int d_
                       W_out, ldo, stream, true);
 }
 
+int qamw_decode_batch(const qamw_decode_item *items, int n_items, const float *codebook, int bits, int hadamard_block,
+                      void *stream) {
+    static_assert(QAMW_MAX_BATCH == qamw::QAMW_DECODE_MAX_BATCH, "batch limits differ");
+    if (!items || !codebook || n_items < 1 || n_items > QAMW_MAX_BATCH) return QAMW_ERR_INVALID_ARG;
+    qamw::DecodeItem its[QAMW_MAX_BATCH];
+    for (int i = 0; i < n_items; ++i) {
+        const qamw_decode_item &q = items[i];
+        if (!q.packed || !q.row_norms || !q.W_out) return QAMW_ERR_INVALID_ARG;
+        int rc = check_common(q.d_out, q.d_in, bits, hadamard_block);
+        if (rc != QAMW_OK) return rc;
+        if (q.ldo < q.d_in) return QAMW_ERR_SHAPE;
+        its[i] = qamw::DecodeItem{q.packed, q.row_norms, q.chan_scale, q.signs, q.pair_sigma, q.W_out, q.ldo, q.d_out, q.d_in};
+    }
+    qamw::Problem shared = make_problem(items[0].d_out, items[0].d_in, nullptr, nullptr, nullptr, codebook, bits,
+                                        hadamard_block, stream);
+    if (g_kernel_path.load() == 0) {
+        hipError_t e = qamw::launch_decode_batch_fast(its, n_items, shared, true);
+        if (e == hipSuccess) return QAMW_OK;
+        if (e != hipErrorNotSupported) return QAMW_ERR_DEVICE;
+    }
+    for (int i = 0; i < n_items; ++i) {                         // nothing was launched: one general launch per item
+        const qamw_decode_item &q = items[i];
+        int rc = decode_any(q.packed, q.row_norms, q.d_out, q.d_in, q.chan_scale, q.signs, q.pair_sigma, codebook, bits,
+                            hadamard_block, q.W_out, q.ldo, stream, true);
+        if (rc != QAMW_OK) return rc;
+    }
+    return QAMW_OK;
+}
+
 int qamw_decode_f32(const uint8_t *packed, const float *row_norms, int d_out, int d_in, const float *chan_scale,
                     const int8_t *signs, const float *pair_sigma, const float *codebook, int bits,
                     int hadamard_block, float *W_out, int64_t ldo, void *stream) {

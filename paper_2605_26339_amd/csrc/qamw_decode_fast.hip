@@ -16,9 +16,13 @@ namespace qamw {
 constexpr int DF_THREADS = 256;
 constexpr int DF_WAVES = DF_THREADS / WAVE;
 constexpr int SLAB = 1024;
+constexpr int DF_MAX_BATCH = QAMW_DECODE_MAX_BATCH;
+constexpr int DF_ROWS = 2;            // rows a wave has in flight at a time
+constexpr int DF_UNIT_ROWS = 16;      // rows of one unit of work (a multiple of DF_ROWS)
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float floatx2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 // Field i (i = 0..7) of a lane's 8*BITS-bit group, the group starting at bit 0 of w[0..2].
 template <int BITS> __device__ __forceinline__ uint32_t field(const uint32_t (&w)[4], int i) {
@@ -86,75 +90,109 @@ __device__ __forceinline__ void load_column_constants(float (&qs)[16], float (&s
     }
 }
 
-// Persistent kernel.  The grid is sized to the machine (not to the matrix); a block stages the
-// codebook into LDS once, then each wave keeps one slab (so its column constants load once) and
-// walks over groups of R rows with a grid stride, fetching the next group's packed indices and
-// norms while it works on the current one.  The 16 bf16 a lane produces are 32 consecutive
-// bytes; a row chunk is therefore bounced through LDS so that each store instruction writes
-// 1 KB of consecutive bytes (full cache lines) instead of every other 16 bytes.
+// One matrix of a decode batch, as the kernel sees it.
+struct DecodeMat {
+    const uint8_t *packed;
+    const float *norms;
+    const float *chan_scale;
+    const int8_t *signs;
+    const float *pair_sigma;
+    void *out;
+    int64_t ldo;
+    int64_t row_bytes;
+    int d_out, d_in, n_slabs, n_groups;
+};
+
+// Work list of one launch.  A unit is (matrix, group of R rows, slab), numbered matrix-major, then
+// row-group-major, slab fastest: unit numbers follow memory order.
+struct DecodeBatch {
+    DecodeMat m[DF_MAX_BATCH];
+    int unit_begin[DF_MAX_BATCH + 1];     // first unit of each matrix; unit_begin[n] = total
+    int n;
+    int K;
+    float inv_sqrt_block, sigma_default;
+    const float *codebook;
+};
+
+// Decode kernel over a batch of matrices.  A block (4 waves) stages the codebook into LDS once; wave w
+// of the grid takes unit w: DF_UNIT_ROWS rows of one 1024-column slab, R rows in flight at a time, with
+// the slab's column constants loaded once.  Units are numbered in memory order and blocks are dispatched
+// in that order, which keeps the reads and writes in flight close together in HBM.  (The loop also
+// supports a grid smaller than the work, n_waves < units, each wave then striding through the units.)
 template <int BITS, int B, bool OUT_BF16, int R>
-__global__ __launch_bounds__(DF_THREADS) void k_decode_fast(const uint8_t *__restrict__ packed,
-                                                            const float *__restrict__ norms, Problem p,
-                                                            void *__restrict__ out, int64_t ldo, int n_slabs,
-                                                            int waves_per_slab) {
-    extern __shared__ float2 cb_lds[];                          // K codewords, then the per-wave bounce buffers
+__global__ __launch_bounds__(DF_THREADS) void k_decode_fast(DecodeBatch bt, int n_waves) {
+    extern __shared__ float2 cb_lds[];                          // K codewords
     const int lane = threadIdx.x & (WAVE - 1);
     const int wid = threadIdx.x >> 6;
     const int wave = __builtin_amdgcn_readfirstlane(blockIdx.x * DF_WAVES + wid);
-    const int slab = wave % n_slabs;
-    const int first_group = wave / n_slabs;                     // >= waves_per_slab: nothing to do
-    const int n_groups = (p.d_out + R - 1) / R;
-    const int last_row = p.d_out - 1;
-
     const LaneSigns<B> ls(lane);
     const int pos = slab_pos(lane);
-    const int col0 = slab * SLAB + 16 * pos;
-    const int c = (col0 < p.d_in) ? col0 : 0;                   // idle lanes compute on valid data, store nothing
-    const int slab_cols = min(SLAB, p.d_in - slab * SLAB);      // valid columns of this slab
-    const int64_t byte_off = (int64_t)(c >> 4) * BITS;          // 8 fields of BITS bits = BITS bytes per lane
-    const uint32_t *pk32 = reinterpret_cast<const uint32_t *>(packed);
-    const int64_t total_dw = (int64_t)p.d_out * (p.row_bytes >> 2);
+    // after the half exchange: whose sub-block this lane stores in the first / second store instruction, and which half
+    const int pos_a = slab_pos(lane & 31), pos_b = slab_pos((lane & 31) + 32), half = lane >> 5;
+    const int total_units = bt.unit_begin[bt.n];
 
-    uint32_t nxt[R][4];
-    float rn_nxt[R];
-    int group = (first_group < waves_per_slab) ? first_group : n_groups;   // surplus waves of the last block idle
-    if (group < n_groups) {
+    struct Unit {
+        int mi, slab, row0;
+    };
+    auto locate = [&](int u, Unit &q) {
+        int mi = 0;
+        while (mi + 1 < bt.n && u >= bt.unit_begin[mi + 1]) ++mi;
+        const int local = u - bt.unit_begin[mi];
+        const int ns = bt.m[mi].n_slabs;
+        // the division runs on the vector ALU; readfirstlane returns the (uniform) results to scalar registers
+        q.mi = mi;
+        q.slab = __builtin_amdgcn_readfirstlane(local % ns);
+        q.row0 = __builtin_amdgcn_readfirstlane((local / ns) * DF_UNIT_ROWS);
+    };
+    auto lane_col = [&](const Unit &q) {                        // first of the lane's 16 columns (0 for idle lanes)
+        const int col0 = q.slab * SLAB + 16 * pos;
+        return (col0 < bt.m[q.mi].d_in) ? col0 : 0;
+    };
+    auto fetch = [&](const Unit &q, int sub, uint32_t (&d)[R][4], float (&rn)[R]) {
+        const DecodeMat &M = bt.m[q.mi];
+        const int64_t byte_off = (int64_t)(lane_col(q) >> 4) * BITS;   // 8 fields of BITS bits = BITS bytes per lane
+        const uint32_t *pk32 = reinterpret_cast<const uint32_t *>(M.packed);
+        const int64_t total_dw = (int64_t)M.d_out * (M.row_bytes >> 2);
 #pragma unroll
         for (int t = 0; t < R; ++t) {
-            const int row = min(group * R + t, last_row);       // rows past the end re-read the last row
-            load_group(nxt[t], pk32, (int64_t)row * p.row_bytes + byte_off, total_dw);
-            rn_nxt[t] = norms[row];
+            const int row = min(q.row0 + sub + t, M.d_out - 1); // rows past the end re-read the last row
+            load_group(d[t], pk32, (int64_t)row * M.row_bytes + byte_off, total_dw);
+            rn[t] = M.norms[row];
         }
-    }
-    float qs[16], sig[8];
-    load_column_constants(qs, sig, p, c, ls.parity);
+    };
 
-    const float2 *cbk = reinterpret_cast<const float2 *>(p.codebook);
-    for (int i = threadIdx.x; i < p.K; i += DF_THREADS) cb_lds[i] = cbk[i];
+    const float2 *cbk = reinterpret_cast<const float2 *>(bt.codebook);
+    for (int i = threadIdx.x; i < bt.K; i += DF_THREADS) cb_lds[i] = cbk[i];
     __syncthreads();
-    uint4 *bounce = reinterpret_cast<uint4 *>(cb_lds + p.K) + wid * (OUT_BF16 ? 128 : 256);
 
-    for (; group < n_groups; group += waves_per_slab) {
+    float qs[16], sig[8];
+    int have_mi = -1, have_slab = -1;
+    for (int u = (wave < n_waves) ? wave : total_units; u < total_units; u += n_waves) {   // surplus waves idle
+        Unit cur;
+        locate(u, cur);
+        const DecodeMat &M = bt.m[cur.mi];
+        const int c = lane_col(cur);
+        if (cur.mi != have_mi || cur.slab != have_slab) {       // uniform over the wave
+            Problem pc;
+            pc.chan_scale = M.chan_scale;
+            pc.signs = M.signs;
+            pc.pair_sigma = M.pair_sigma;
+            pc.sigma_default = bt.sigma_default;
+            load_column_constants(qs, sig, pc, c, ls.parity);
+            have_mi = cur.mi;
+            have_slab = cur.slab;
+        }
+        const int slab_cols = min(SLAB, M.d_in - cur.slab * SLAB);   // valid columns of this slab
+        const int64_t byte_off = (int64_t)(c >> 4) * BITS;
+        const int last_row = M.d_out - 1;
+        for (int sub = 0; sub < DF_UNIT_ROWS && cur.row0 + sub <= last_row; sub += R) {
         uint32_t d[R][4];
         float rn[R];
+        fetch(cur, sub, d, rn);                                 // latency is hidden by the other waves of the SIMD
 #pragma unroll
         for (int t = 0; t < R; ++t) {
-            rn[t] = rn_nxt[t];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) d[t][q] = nxt[t][q];
-        }
-        if (group + waves_per_slab < n_groups) {
-#pragma unroll
-            for (int t = 0; t < R; ++t) {
-                const int row = min((group + waves_per_slab) * R + t, last_row);
-                load_group(nxt[t], pk32, (int64_t)row * p.row_bytes + byte_off, total_dw);
-                rn_nxt[t] = norms[row];
-            }
-        }
-#pragma unroll
-        for (int t = 0; t < R; ++t) {
-            const int row = group * R + t;
-            const int sh = (int)(((int64_t)min(row, last_row) * p.row_bytes + byte_off) & 3) * 8;
+            const int row = cur.row0 + sub + t;
+            const int sh = (int)(((int64_t)min(row, last_row) * M.row_bytes + byte_off) & 3) * 8;
             uint32_t w[4];
             w[0] = __builtin_amdgcn_alignbit(d[t][1], d[t][0], sh);
             w[1] = __builtin_amdgcn_alignbit(d[t][2], d[t][1], sh);
@@ -168,7 +206,7 @@ __global__ __launch_bounds__(DF_THREADS) void k_decode_fast(const uint8_t *__res
                 x[2 * k + 1] = sig[k] * cw.y;
             }
             fwht_wave<B>(x, ls);
-            const float a = rn[t] * p.inv_sqrt_block;           // row factor r * block^-1/2
+            const float a = rn[t] * bt.inv_sqrt_block;          // row factor r * block^-1/2
             if (OUT_BF16) {
                 uint32_t o[8];
 #pragma unroll
@@ -176,34 +214,33 @@ __global__ __launch_bounds__(DF_THREADS) void k_decode_fast(const uint8_t *__res
                     floatx2_t v = {(x[e] * a) * qs[e], (x[e + 1] * a) * qs[e + 1]};
                     o[e >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
                 }
-                // lane `pos` owns bytes [32 pos, 32 pos + 32) of the chunk; lane l stores bytes [16 l, +16) and [1024 + 16 l, +16)
-                bounce[2 * pos] = make_uint4(o[0], o[1], o[2], o[3]);
-                bounce[2 * pos + 1] = make_uint4(o[4], o[5], o[6], o[7]);
-                __builtin_amdgcn_wave_barrier();
-                const uint4 lo = bounce[lane], hi = bounce[64 + lane];
-                __builtin_amdgcn_wave_barrier();
-                if (row <= last_row) {
-                    uint4 *dst = reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(out) + (int64_t)row * ldo + slab * SLAB);
-                    if (8 * lane < slab_cols) dst[lane] = lo;
-                    if (512 + 8 * lane < slab_cols) dst[64 + lane] = hi;
+                // A lane's 16 bf16 are 32 consecutive bytes.  Storing them as they are would make each store
+                // instruction write every other 16 bytes; instead lanes i and i+32 trade one half each
+                // (v_permlane32_swap), after which lanes 0-31 hold the first halves and lanes 32-63 the second
+                // halves of 32 neighbouring sub-blocks: each store instruction then covers 1 KB without holes.
+                uint32_t lo[4] = {o[0], o[1], o[2], o[3]}, hi[4] = {o[4], o[5], o[6], o[7]};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    auto r = __builtin_amdgcn_permlane32_swap(lo[q], hi[q], false, false);   // upper lanes' lo <-> lower lanes' hi
+                    lo[q] = r[0];
+                    hi[q] = r[1];
                 }
-            } else {
+                if (row <= last_row) {
+                    u32x4_t *dst = reinterpret_cast<u32x4_t *>(reinterpret_cast<uint16_t *>(M.out) + (int64_t)row * M.ldo + cur.slab * SLAB);
+                    // instruction A: sub-blocks of lanes 0-31; instruction B: sub-blocks of lanes 32-63.
+                    // The output is written once and not read again by this kernel: streaming stores.
+                    const u32x4_t va = {lo[0], lo[1], lo[2], lo[3]}, vb = {hi[0], hi[1], hi[2], hi[3]};
+                    if (16 * pos_a < slab_cols) __builtin_nontemporal_store(va, dst + 2 * pos_a + half);
+                    if (16 * pos_b < slab_cols) __builtin_nontemporal_store(vb, dst + 2 * pos_b + half);
+                }
+            } else if (row <= last_row && 16 * pos < slab_cols) {   // fp32 output (accuracy checks): plain per-lane stores
+                float4 *dst = reinterpret_cast<float4 *>(reinterpret_cast<float *>(M.out) + (int64_t)row * M.ldo + cur.slab * SLAB + 16 * pos);
 #pragma unroll
                 for (int e = 0; e < 16; e += 4)
-                    bounce[4 * pos + (e >> 2)] = __builtin_bit_cast(uint4, make_float4((x[e] * a) * qs[e], (x[e + 1] * a) * qs[e + 1],
-                                                                                      (x[e + 2] * a) * qs[e + 2], (x[e + 3] * a) * qs[e + 3]));
-                __builtin_amdgcn_wave_barrier();
-                uint4 v[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) v[q] = bounce[64 * q + lane];
-                __builtin_amdgcn_wave_barrier();
-                if (row <= last_row) {
-                    uint4 *dst = reinterpret_cast<uint4 *>(reinterpret_cast<float *>(out) + (int64_t)row * ldo + slab * SLAB);
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        if (256 * q + 4 * lane < slab_cols) dst[64 * q + lane] = v[q];
-                }
+                    dst[e >> 2] = make_float4((x[e] * a) * qs[e], (x[e + 1] * a) * qs[e + 1], (x[e + 2] * a) * qs[e + 2],
+                                              (x[e + 3] * a) * qs[e + 3]);
             }
+        }
         }
     }
 }
@@ -215,57 +252,93 @@ bool fast_decode_supported(const Problem &p) {
     return p.block >= 64;                                        // 64, 128, 256, 512, 1024
 }
 
-constexpr int DF_ROWS = 4;            // rows a wave handles per step
-constexpr int DF_BLOCKS_PER_CU = 6;    // resident blocks per compute unit the grid is sized for
+// Alignment the vector loads and stores of the fast kernel assume.
+static bool decode_alignment_ok(const DecodeItem &it, bool out_bf16) {
+    const int64_t align_elems = out_bf16 ? 8 : 4;
+    if (it.ldo % align_elems || (reinterpret_cast<uintptr_t>(it.out) & 15)) return false;
+    if ((reinterpret_cast<uintptr_t>(it.chan_scale) | reinterpret_cast<uintptr_t>(it.signs) |
+         reinterpret_cast<uintptr_t>(it.pair_sigma)) & 15)
+        return false;
+    return (reinterpret_cast<uintptr_t>(it.packed) & 3) == 0;
+}
+
+static int gcd_int(int a, int b) { return b ? gcd_int(b, a % b) : a; }
 
 template <int BITS, int B>
-static hipError_t launch_bb(const uint8_t *packed, const float *norms, const Problem &p, void *out, int64_t ldo,
-                            bool out_bf16) {
-    // vector stores need 16-byte aligned rows
-    const int64_t align_elems = out_bf16 ? 8 : 4;
-    if (ldo % align_elems || (reinterpret_cast<uintptr_t>(out) & 15)) return hipErrorNotSupported;
-    if ((reinterpret_cast<uintptr_t>(p.chan_scale) | reinterpret_cast<uintptr_t>(p.signs) |
-         reinterpret_cast<uintptr_t>(p.pair_sigma)) & 15)
-        return hipErrorNotSupported;
-    if ((reinterpret_cast<uintptr_t>(packed) & 3)) return hipErrorNotSupported;
-    const int n_slabs = (p.d_in + SLAB - 1) / SLAB;
-    const int n_groups = (p.d_out + DF_ROWS - 1) / DF_ROWS;
-    // waves that share a slab: enough to fill the machine (256 CUs x DF_BLOCKS_PER_CU blocks), no more than the work
-    int max_wps = (256 * DF_BLOCKS_PER_CU * DF_WAVES) / n_slabs;
-    if (max_wps < 1) max_wps = 1;
-    const int steps = (n_groups + max_wps - 1) / max_wps;           // row groups each wave walks through
-    const int waves_per_slab = (n_groups + steps - 1) / steps;     // evened out: no wave does more than `steps`
-    const int64_t n_waves = (int64_t)waves_per_slab * n_slabs;
+static hipError_t launch_bb(const DecodeItem *items, int n, const Problem &p, bool out_bf16) {
+    DecodeBatch bt;
+    int64_t units = 0;
+    int64_t lcm = 1;
+    for (int i = 0; i < n; ++i) {
+        DecodeMat &M = bt.m[i];
+        M.packed = items[i].packed;
+        M.norms = items[i].norms;
+        M.chan_scale = items[i].chan_scale;
+        M.signs = items[i].signs;
+        M.pair_sigma = items[i].pair_sigma;
+        M.out = items[i].out;
+        M.ldo = items[i].ldo;
+        M.d_out = items[i].d_out;
+        M.d_in = items[i].d_in;
+        M.row_bytes = (((int64_t)(M.d_in / 2) * BITS + 31) / 32) * 4;
+        M.n_slabs = (M.d_in + SLAB - 1) / SLAB;
+        M.n_groups = (M.d_out + DF_UNIT_ROWS - 1) / DF_UNIT_ROWS;
+        bt.unit_begin[i] = (int)units;
+        units += (int64_t)M.n_slabs * M.n_groups;
+        if (units > 0x3fffffff) return hipErrorNotSupported;
+        lcm = lcm / gcd_int((int)lcm, M.n_slabs) * M.n_slabs;
+    }
+    for (int i = n; i <= DF_MAX_BATCH; ++i) bt.unit_begin[i] = (int)units;
+    for (int i = n; i < DF_MAX_BATCH; ++i) bt.m[i] = bt.m[0];
+    bt.n = n;
+    bt.K = p.K;
+    bt.inv_sqrt_block = p.inv_sqrt_block;
+    bt.sigma_default = p.sigma_default;
+    bt.codebook = p.codebook;
+    // One unit per wave, blocks dispatched in unit (= memory) order.  (A machine-sized persistent grid with a
+    // stride was measured slower on HBM-bound sizes: its waves move in lockstep through read and write phases.)
+    (void)lcm;
+    const int64_t n_waves = units;
     const unsigned blocks = (unsigned)((n_waves + DF_WAVES - 1) / DF_WAVES);
-    const size_t lds = (size_t)p.K * sizeof(float2) + (size_t)DF_WAVES * (out_bf16 ? 2048 : 4096);
+    const size_t lds = (size_t)p.K * sizeof(float2);
     if (out_bf16)
-        hipLaunchKernelGGL((k_decode_fast<BITS, B, true, DF_ROWS>), dim3(blocks), dim3(DF_THREADS), lds, p.stream, packed,
-                           norms, p, out, ldo, n_slabs, waves_per_slab);
+        hipLaunchKernelGGL((k_decode_fast<BITS, B, true, DF_ROWS>), dim3(blocks), dim3(DF_THREADS), lds, p.stream, bt, (int)n_waves);
     else
-        hipLaunchKernelGGL((k_decode_fast<BITS, B, false, DF_ROWS>), dim3(blocks), dim3(DF_THREADS), lds, p.stream, packed,
-                           norms, p, out, ldo, n_slabs, waves_per_slab);
+        hipLaunchKernelGGL((k_decode_fast<BITS, B, false, DF_ROWS>), dim3(blocks), dim3(DF_THREADS), lds, p.stream, bt, (int)n_waves);
     return hipGetLastError();
 }
 
 template <int BITS>
-static hipError_t launch_b(const uint8_t *packed, const float *norms, const Problem &p, void *out, int64_t ldo,
-                           bool out_bf16) {
+static hipError_t launch_b(const DecodeItem *items, int n, const Problem &p, bool out_bf16) {
     switch (p.block) {
-        case 64: return launch_bb<BITS, 64>(packed, norms, p, out, ldo, out_bf16);
-        case 128: return launch_bb<BITS, 128>(packed, norms, p, out, ldo, out_bf16);
-        case 256: return launch_bb<BITS, 256>(packed, norms, p, out, ldo, out_bf16);
-        case 512: return launch_bb<BITS, 512>(packed, norms, p, out, ldo, out_bf16);
-        case 1024: return launch_bb<BITS, 1024>(packed, norms, p, out, ldo, out_bf16);
+        case 64: return launch_bb<BITS, 64>(items, n, p, out_bf16);
+        case 128: return launch_bb<BITS, 128>(items, n, p, out_bf16);
+        case 256: return launch_bb<BITS, 256>(items, n, p, out_bf16);
+        case 512: return launch_bb<BITS, 512>(items, n, p, out_bf16);
+        case 1024: return launch_bb<BITS, 1024>(items, n, p, out_bf16);
         default: return hipErrorNotSupported;
     }
 }
 
+// Decode n <= DF_MAX_BATCH matrices that share codebook, bits and block in one launch.  p carries the shared
+// fields only.  Returns hipErrorNotSupported (nothing launched) when any item is outside the fast kernel's shapes.
+hipError_t launch_decode_batch_fast(const DecodeItem *items, int n, const Problem &p, bool out_bf16) {
+    if (n < 1 || n > DF_MAX_BATCH) return hipErrorNotSupported;
+    for (int i = 0; i < n; ++i) {
+        Problem q = p;
+        q.d_in = items[i].d_in;
+        if (!fast_decode_supported(q) || !decode_alignment_ok(items[i], out_bf16)) return hipErrorNotSupported;
+    }
+    if (p.bits == 11) return launch_b<11>(items, n, p, out_bf16);
+    if (p.bits == 8) return launch_b<8>(items, n, p, out_bf16);
+    if (p.bits == 7) return launch_b<7>(items, n, p, out_bf16);
+    return hipErrorNotSupported;
+}
+
 hipError_t launch_decode_fast(const uint8_t *packed, const float *norms, const Problem &p, void *out, int64_t ldo,
                               bool out_bf16) {
-    hipError_t e = hipErrorNotSupported;
-    if (p.bits == 11) e = launch_b<11>(packed, norms, p, out, ldo, out_bf16);
-    else if (p.bits == 8) e = launch_b<8>(packed, norms, p, out, ldo, out_bf16);
-    else if (p.bits == 7) e = launch_b<7>(packed, norms, p, out, ldo, out_bf16);
+    DecodeItem it{packed, norms, p.chan_scale, p.signs, p.pair_sigma, out, ldo, p.d_out, p.d_in};
+    hipError_t e = launch_decode_batch_fast(&it, 1, p, out_bf16);
     if (e == hipErrorNotSupported) return launch_decode_general(packed, norms, p, out, ldo, out_bf16);
     return e;
 }

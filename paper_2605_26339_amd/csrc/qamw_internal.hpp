@@ -39,6 +39,21 @@ bool fast_calibrate_supported(const void *W, int dtype, int64_t ldw, const Probl
 hipError_t launch_calibrate_fast(const void *W, int dtype, int64_t ldw, int n_rows, const Problem &p, const float *norms,
                                  double *partial, float *sigma_out);
 
+// One matrix of a decode batch (host-side description).
+constexpr int QAMW_DECODE_MAX_BATCH = 16;
+struct DecodeItem {
+    const uint8_t *packed;
+    const float *norms;
+    const float *chan_scale;
+    const int8_t *signs;
+    const float *pair_sigma;
+    void *out;
+    int64_t ldo;
+    int d_out, d_in;
+};
+// Several matrices sharing codebook, bits and block in ONE launch; hipErrorNotSupported = nothing launched.
+hipError_t launch_decode_batch_fast(const DecodeItem *items, int n, const Problem &p, bool out_bf16);
+
 // Fast kernels: return hipErrorNotSupported when the shape is outside what they cover.
 bool fast_decode_supported(const Problem &p);
 hipError_t launch_decode_fast(const uint8_t *packed, const float *norms, const Problem &p, void *out,

@@ -19,8 +19,18 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
 EXPORTS = [
     "qamw_status_string", "qamw_packed_row_bytes", "qamw_paper_block_size", "qamw_bpw", "qamw_sign_mask",
     "qamw_channel_scales", "qamw_train_codebook", "qamw_calibrate_workspace_bytes", "qamw_calibrate_sigma", "qamw_encode", "qamw_decode",
-    "qamw_decode_f32", "qamw_set_kernel_path",
+    "qamw_decode_f32", "qamw_decode_batch", "qamw_set_kernel_path",
 ]
+
+
+MAX_BATCH = 16
+
+
+class DecodeItem(C.Structure):
+    """qamw_decode_item of include/qamw.h."""
+    _fields_ = [("packed", C.c_void_p), ("row_norms", C.c_void_p), ("chan_scale", C.c_void_p), ("signs", C.c_void_p),
+                ("pair_sigma", C.c_void_p), ("W_out", C.c_void_p), ("ldo", C.c_int64), ("d_out", C.c_int32),
+                ("d_in", C.c_int32)]
 
 
 class QamwError(RuntimeError):
@@ -57,6 +67,7 @@ def lib() -> C.CDLL:
         L.qamw_encode.argtypes = [vp, i32, i32, i32, i64, vp, vp, vp, vp, i32, i32, vp, vp, vp]
         L.qamw_decode.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, i64, vp]
         L.qamw_decode_f32.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, i64, vp]
+        L.qamw_decode_batch.argtypes = [C.POINTER(DecodeItem), i32, vp, i32, i32, vp]
         L.qamw_set_kernel_path.argtypes = [i32]
         for name in EXPORTS:
             if name != "qamw_status_string":
@@ -206,3 +217,21 @@ def decode(packed, row_norms, d_in: int, codebook, bits: int, block: int, chan_s
               _ptr(codebook), bits, block, _ptr(out), out.stride(0), _stream(stream)),
            "qamw_decode_f32" if f32 else "qamw_decode")
     return out
+
+
+def make_decode_items(entries):
+    """Build the host descriptor array for decode_batch from dicts/tuples of torch tensors:
+    each entry = (packed, row_norms, d_in, chan_scale, signs, pair_sigma, out).  Returns (array, keepalive)."""
+    arr = (DecodeItem * len(entries))()
+    for i, (packed, norms, d_in, s, sg, sigma, out) in enumerate(entries):
+        _require_cuda(packed, norms, s, sg, sigma, out)
+        arr[i] = DecodeItem(packed.data_ptr(), norms.data_ptr(), None if s is None else s.data_ptr(),
+                            None if sg is None else sg.data_ptr(), None if sigma is None else sigma.data_ptr(),
+                            out.data_ptr(), out.stride(0), norms.shape[0], d_in)
+    return arr, list(entries)
+
+
+def decode_batch(items, codebook, bits: int, block: int, stream=None):
+    """Decode up to MAX_BATCH matrices (a DecodeItem array from make_decode_items) in one launch."""
+    arr = items[0] if isinstance(items, tuple) else items
+    _check(lib().qamw_decode_batch(arr, len(arr), _ptr(codebook), bits, block, _stream(stream)), "qamw_decode_batch")

@@ -175,6 +175,32 @@ def test_config0_full_matrix(orc, codebooks):
     assert 0.02 < rel < 0.05
 
 
+def test_decode_batch_equals_single_calls(orc, codebooks, kernel_path):
+    """One launch for several matrices of different shapes (ragged slabs, odd row counts) gives exactly
+    what the per-matrix entry point gives, and both match the oracle."""
+    say(f"[batch] path={kernel_path}")
+    bits, block = 11, 128
+    shapes = [(71, 33, 4096), (72, 18, 11008), (73, 7, 1152), (74, 41, 5632), (75, 1, 128), (76, 9, 13824), (77, 5, 2048)]
+    cases = [Case(orc, sd, do, di, bits, block, dtype="bf16", codebook=codebooks[bits]) for sd, do, di in shapes]
+    entries, singles, refs = [], [], []
+    for cs in cases:
+        ref = cs.oracle_encode(orc)
+        packed = torch.from_numpy(orc.pack(ref["idx"], bits)).cuda()
+        norms = torch.from_numpy(ref["norms"].astype(np.float32)).cuda()
+        out = torch.zeros((cs.d_out, cs.d_in), dtype=torch.bfloat16, device="cuda")
+        entries.append((packed, norms, cs.d_in, cs.s_dev, cs.sg_dev, cs.sigma_dev, out))
+        singles.append(qamw.decode(packed, norms, cs.d_in, cs.cb_dev, bits, block, chan_scale=cs.s_dev, signs=cs.sg_dev,
+                                   pair_sigma=cs.sigma_dev))
+        refs.append(ref)
+    items = qamw.make_decode_items(entries)
+    qamw.decode_batch(items, cases[0].cb_dev, bits, block)
+    torch.cuda.synchronize()
+    for cs, e, single, ref in zip(cases, entries, singles, refs):
+        got = e[6].cpu().view(torch.int16).numpy().view(np.uint16)
+        assert np.array_equal(got, single.cpu().view(torch.int16).numpy().view(np.uint16))
+        check_decode(orc, cs, ref["idx"], ref["norms"].astype(np.float32), got_bf16=got)
+
+
 def test_calibrate_sigma_matches_oracle(orc, kernel_path):
     for seed, d_out, d_in, block, dtype in [(61, 1500, 512, 128, "f32"), (62, 300, 2048, 1024, "bf16"),
                                             (63, 64, 1280, 256, "f32"), (64, 10, 96, 2, "f32"), (65, 33, 5632, 512, "f32"),

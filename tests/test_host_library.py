@@ -126,6 +126,29 @@ def test_device_entry_points_reject_bad_arguments_before_any_launch():
     assert L.qamw_calibrate_workspace_bytes(256, 8, 1024, None) == qamw.ERR_INVALID_ARG
 
 
+def test_decode_batch_rejects_bad_arguments():
+    L = qamw.lib()
+    p = 0x1000
+    def item(**kw):
+        a = dict(packed=p, row_norms=p, chan_scale=None, signs=None, pair_sigma=None, W_out=p, ldo=256, d_out=8, d_in=256)
+        a.update(kw)
+        return qamw.DecodeItem(**a)
+    arr = (qamw.DecodeItem * 2)(item(), item())
+    cb = C.c_void_p(p)
+    assert L.qamw_decode_batch(None, 2, cb, 11, 128, None) == qamw.ERR_INVALID_ARG
+    assert L.qamw_decode_batch(arr, 0, cb, 11, 128, None) == qamw.ERR_INVALID_ARG
+    assert L.qamw_decode_batch(arr, qamw.MAX_BATCH + 1, cb, 11, 128, None) == qamw.ERR_INVALID_ARG
+    assert L.qamw_decode_batch(arr, 2, None, 11, 128, None) == qamw.ERR_INVALID_ARG
+    assert L.qamw_decode_batch(arr, 2, cb, 0, 128, None) == qamw.ERR_INVALID_ARG
+    assert L.qamw_decode_batch(arr, 2, cb, 11, 96, None) == qamw.ERR_SHAPE
+    for bad, want in [(item(packed=None), qamw.ERR_INVALID_ARG), (item(W_out=None), qamw.ERR_INVALID_ARG),
+                      (item(row_norms=None), qamw.ERR_INVALID_ARG), (item(d_in=255), qamw.ERR_SHAPE),
+                      (item(ldo=100), qamw.ERR_SHAPE), (item(d_out=0), qamw.ERR_INVALID_ARG),
+                      (item(d_in=384, ldo=384), qamw.ERR_SHAPE)]:
+        arr2 = (qamw.DecodeItem * 2)(item(), bad)
+        assert L.qamw_decode_batch(arr2, 2, cb, 11, 256 if bad.d_in == 384 else 128, None) == want
+
+
 def test_kernel_path_switch():
     prev = qamw.set_kernel_path(1)
     assert qamw.set_kernel_path(0) == 1
