@@ -174,8 +174,10 @@ int qamw_decode_batch(const qamw_decode_item *items, int n_items, const float *c
                       int hadamard_block, void *stream);
 
 /* Which implementation the device entry points use: 0 = automatic (fast kernels when the shape
- * allows, otherwise the general ones), 1 = always the general kernels.  Process-wide, for tests
- * and measurements; returns the previous value. */
+ * allows, otherwise the general ones), 1 = always the general kernels, 2 = as 0 but the encoder's
+ * shortlist runs on the vector ALU instead of the matrix cores.  All three give the same indices.
+ * Process-wide, for tests and measurements; returns the previous value (also for a value out of
+ * range, which changes nothing). */
 int qamw_set_kernel_path(int path);
 
 #ifdef __cplusplus

@@ -40,7 +40,7 @@ qamw::Problem make_problem(int d_out, int d_in, const float *chan_scale, const i
 
 hipError_t launch_norms(const void *W, int dtype, int64_t ldw, int n_rows, const qamw::Problem &p, float *norms) {
     hipError_t e = hipSuccess;
-    if (g_kernel_path.load() == 0 && qamw::launch_row_norms_fast(W, dtype, ldw, n_rows, p, norms, &e)) return e;
+    if (g_kernel_path.load() != 1 && qamw::launch_row_norms_fast(W, dtype, ldw, n_rows, p, norms, &e)) return e;
     return qamw::launch_row_norms(W, dtype, ldw, n_rows, p, norms);
 }
 
@@ -53,7 +53,7 @@ int decode_any(const uint8_t *packed, const float *row_norms, int d_out, int d_i
     if (ldo < d_in) return QAMW_ERR_SHAPE;
     qamw::Problem p = make_problem(d_out, d_in, chan_scale, signs, pair_sigma, codebook, bits, block, stream);
     hipError_t e;
-    if (g_kernel_path.load() == 0 && qamw::fast_decode_supported(p))
+    if (g_kernel_path.load() != 1 && qamw::fast_decode_supported(p))
         e = qamw::launch_decode_fast(packed, row_norms, p, out, ldo, bf16);
     else
         e = qamw::launch_decode_general(packed, row_norms, p, out, ldo, bf16);
@@ -65,7 +65,7 @@ int decode_any(const uint8_t *packed, const float *row_norms, int d_out, int d_i
 extern "C" {
 
 int qamw_set_kernel_path(int path) {
-    if (path != 0 && path != 1) return g_kernel_path.load();
+    if (path < 0 || path > 2) return g_kernel_path.load();
     return g_kernel_path.exchange(path);
 }
 
@@ -96,7 +96,7 @@ int qamw_calibrate_sigma(const void *W, int dtype, int d_out, int d_in, int64_t 
     double *partial = reinterpret_cast<double *>(static_cast<char *>(workspace) + align_up((size_t)n * sizeof(float), 256));
     if (launch_norms(W, dtype, ldw, n, p, row_norms) != hipSuccess) return QAMW_ERR_DEVICE;
     hipError_t e;
-    if (g_kernel_path.load() == 0 && qamw::fast_calibrate_supported(W, dtype, ldw, p))
+    if (g_kernel_path.load() != 1 && qamw::fast_calibrate_supported(W, dtype, ldw, p))
         e = qamw::launch_calibrate_fast(W, dtype, ldw, n, p, row_norms, partial, sigma_out);
     else
         e = qamw::launch_calibrate_general(W, dtype, ldw, n, p, row_norms, sigma_out);
@@ -113,11 +113,12 @@ int qamw_encode(const void *W, int dtype, int d_out, int d_in, int64_t ldw, cons
     if (ldw < d_in) return QAMW_ERR_SHAPE;
     qamw::Problem p = make_problem(d_out, d_in, chan_scale, signs, pair_sigma, codebook, bits, hadamard_block, stream);
     if (launch_norms(W, dtype, ldw, d_out, p, row_norms_out) != hipSuccess) return QAMW_ERR_DEVICE;
-    hipError_t e;
-    if (g_kernel_path.load() == 0 && qamw::fast_encode_supported(p))
+    const int path = g_kernel_path.load();
+    hipError_t e = hipErrorNotSupported;                        // "not supported" = nothing launched yet
+    if (path == 0) e = qamw::launch_encode_mfma(W, dtype, ldw, p, row_norms_out, packed_out);
+    if (e == hipErrorNotSupported && path != 1 && qamw::fast_encode_supported(p))
         e = qamw::launch_encode_fast(W, dtype, ldw, p, row_norms_out, packed_out);
-    else
-        e = qamw::launch_encode_general(W, dtype, ldw, p, row_norms_out, packed_out);
+    if (e == hipErrorNotSupported) e = qamw::launch_encode_general(W, dtype, ldw, p, row_norms_out, packed_out);
     return e == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
 }
 
@@ -143,7 +144,7 @@ int qamw_decode_batch(const qamw_decode_item *items, int n_items, const float *c
     }
     qamw::Problem shared = make_problem(items[0].d_out, items[0].d_in, nullptr, nullptr, nullptr, codebook, bits,
                                         hadamard_block, stream);
-    if (g_kernel_path.load() == 0) {
+    if (g_kernel_path.load() != 1) {
         hipError_t e = qamw::launch_decode_batch_fast(its, n_items, shared, true);
         if (e == hipSuccess) return QAMW_OK;
         if (e != hipErrorNotSupported) return QAMW_ERR_DEVICE;

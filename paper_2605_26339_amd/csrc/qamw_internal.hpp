@@ -61,5 +61,8 @@ hipError_t launch_decode_fast(const uint8_t *packed, const float *norms, const P
 bool fast_encode_supported(const Problem &p);
 hipError_t launch_encode_fast(const void *W, int dtype, int64_t ldw, const Problem &p, const float *norms,
                               uint8_t *packed);
+bool mfma_encode_supported(const Problem &p);
+hipError_t launch_encode_mfma(const void *W, int dtype, int64_t ldw, const Problem &p, const float *norms,
+                              uint8_t *packed);
 
 }  // namespace qamw

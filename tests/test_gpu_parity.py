@@ -31,7 +31,7 @@ def codebooks(orc):
     return out
 
 
-@pytest.fixture(params=[0, 1], ids=["auto", "general"])
+@pytest.fixture(params=[0, 1, 2], ids=["auto", "general", "valu"])
 def kernel_path(request):
     prev = qamw.set_kernel_path(request.param)
     yield request.param
