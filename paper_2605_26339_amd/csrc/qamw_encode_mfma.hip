@@ -1,34 +1,38 @@
 // QAM-W encoder whose shortlist scores come from the matrix cores (Sec. 3.1 / Sec. 3.5).
 //
 // The score matrix  S[c][x] = ||c||^2 - 2 x.c  of a block of 32 codewords against a block of 32
-// points is a (32 x 2)(2 x 32) product plus a bias: a dense contraction with inner dimension 2.
-// The fp32 matrix instruction runs on the same FMA lanes as the vector ALU and buys nothing, but
-// the bf16 matrix cores are separate hardware.  Every fp32 operand is split EXACTLY into three
-// bf16 pieces (8 + 8 + 8 significant bits, by truncation), and one v_mfma_f32_32x32x16_bf16
-// evaluates, per coordinate, the eight piece products hh, hm, mh, hl, mm, lh, ml, lm (only ll,
-// below 2^-32 relative, is dropped) on top of ||c||^2 supplied in the fp32 accumulator.  Piece
-// products are exact in fp32; the only error is the accumulation's rounding, bounded for any
-// summation order by 16 x 2^-24 x (sum of magnitudes) <= 2^-20 (||c|| + |x0| + |x1|)^2 (measured
-// worst case over 2e6 random evaluations: 2^-22.6).  That bound is all the shortlist needs: as in
-// the vector-ALU encoder, the index is decided by exact fp32 squared distances inside the best
-// 16-codeword chunk when the runner-up chunk is provably out of reach, and by an exact scan of
-// the whole codebook otherwise.  The vector ALU is left with the min-reduction of the scores.
+// points is a (32 x 3)(3 x 32) product: a dense contraction with a tiny inner dimension.  The
+// fp32 matrix instruction runs on the same FMA lanes as the vector ALU and buys nothing, but the
+// bf16 matrix cores are separate hardware.  Every fp32 operand is split EXACTLY into three bf16
+// pieces h + m + l (8 + 8 + 8 significant bits, by truncation), and one
+// v_mfma_f32_32x32x16_bf16 sums, per coordinate, the six piece products hh, hm, mh, hl, mm, lh
+// and, in the four inner slots left over, the three pieces of ||c||^2 times 1.  Piece products
+// are exact in fp32.  What is lost: the products ml, lm, ll (at most 2^-22 n1 ||c|| in all, with
+// n1 = |x0| + |x1|) and the rounding of a 15-term fp32 accumulation, which for any summation
+// order is at most 14 x 2^-24 x (sum of magnitudes) < 2^-20 (||c||^2 + 2.02 n1 ||c||).  The
+// kernel budgets 2^-19 (||c|| + n1)^2; the worst error seen over 3e6 random evaluations on the
+// hardware is 2^-21.6 of that scale.  The bound is all the shortlist needs: as in the vector-ALU
+// encoder, the index is decided by exact fp32 squared distances inside the best chunk when the
+// runner-up chunk is provably out of reach, and by an exact scan of the whole codebook
+// otherwise.  The vector ALU is left with the min-reduction of the scores.
 //
 // Work split: a wave owns 512 pairs (one row's 1024-column slab).  Front half in registers as in
 // the vector-ALU encoder; the pairs are then transposed through LDS into the matrix layout
-// (lane = point of a 32-point block, lanes 0-31 / 32-63 = the two coordinates).  A lane's 16
-// accumulator rows {8q + 4h + t} of a 32-codeword block are its shortlist chunk.
+// (lane = point of a 32-point block, lanes 0-31 / 32-63 = the two coordinates).  A chunk is the
+// lane's 16 accumulator rows {8q + 4h + t} of two consecutive 32-codeword blocks.
 #include "qamw_front.hpp"
 
 namespace qamw {
 
-constexpr int MF_THREADS = 256;
+constexpr int MF_THREADS = 512;
 constexpr int MF_WAVES = MF_THREADS / WAVE;
 constexpr int MSLAB = 1024;
 constexpr int NPB = 8;                 // 32-point blocks whose operands and state a wave holds at a time
 constexpr int PB_TOTAL = 16;           // 512 pairs / 32
 constexpr float MBIG = 3.0e38f;
-constexpr int MF_WAVE_LDS_FLOATS = 1024 + 512;   // per wave: 512 points (x0, x1) + 512 indices
+constexpr uint32_t BF16_ONE_ONE = 0x3F803F80u;  // (1.0, 1.0) as two bf16
+constexpr int MF_WAVE_LDS_FLOATS = 1024 + 256;   // per wave: 512 points (x0, x1) + 512 16-bit indices
+constexpr int MF_MAX_LDS_BYTES = (2048 * 4 + MF_WAVES * MF_WAVE_LDS_FLOATS) * 4;   // K = 2048: 72 KB, two workgroups per CU
 
 typedef float f16v_t __attribute__((ext_vector_type(16)));
 typedef __bf16 bf8v_t __attribute__((ext_vector_type(8)));
@@ -58,30 +62,35 @@ __global__ __launch_bounds__(MF_THREADS) void k_encode_mfma(const void *__restri
                                                             uint8_t *__restrict__ packed, int n_slabs, int n_items) {
     extern __shared__ __align__(16) float lds_raw[];
     float2 *c01 = reinterpret_cast<float2 *>(lds_raw);          // K x (c0, c1)
-    float *cn = lds_raw + 2 * p.K;                              // K x ||c||^2
+    uint32_t *e67 = reinterpret_cast<uint32_t *>(lds_raw + 2 * p.K);   // K x 2: bf16 pieces of ||c||^2, (h, m) and (l, 0)
     __shared__ float red[MF_WAVES];
 
     const int lane = threadIdx.x & (WAVE - 1);
     const int wid = threadIdx.x >> 6;
     const int K = p.K;
-    float *wave_area = lds_raw + 3 * K + wid * MF_WAVE_LDS_FLOATS;
+    float *wave_area = lds_raw + 4 * K + wid * MF_WAVE_LDS_FLOATS;
     float2 *pts = reinterpret_cast<float2 *>(wave_area);        // the wave's 512 points, pair order
-    int *idxl = reinterpret_cast<int *>(wave_area + 1024);      // their indices
+    uint16_t *idxl = reinterpret_cast<uint16_t *>(wave_area + 1024);   // their indices
 
     const float2 *cbk = reinterpret_cast<const float2 *>(p.codebook);
     float rmax2 = 0.0f;
     for (int i = threadIdx.x; i < K; i += MF_THREADS) {
         float2 c = cbk[i];
         float n2 = __builtin_fmaf(c.y, c.y, c.x * c.x);
+        uint32_t h, m, l;
+        split3(n2, h, m, l);
         c01[i] = c;
-        cn[i] = n2;
+        e67[2 * i] = pack2(h, m);
+        e67[2 * i + 1] = pack2(l, 0u);
         rmax2 = fmaxf(rmax2, n2);
     }
 #pragma unroll
     for (int m = 1; m < WAVE; m <<= 1) rmax2 = fmaxf(rmax2, __shfl_xor(rmax2, m, WAVE));
     if (lane == 0) red[wid] = rmax2;
     __syncthreads();
-    rmax2 = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    rmax2 = 0.0f;
+#pragma unroll
+    for (int w = 0; w < MF_WAVES; ++w) rmax2 = fmaxf(rmax2, red[w]);
     const float R = sqrtf(rmax2) * 1.000001f;
 
     const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * MF_WAVES + wid);
@@ -118,11 +127,11 @@ __global__ __launch_bounds__(MF_THREADS) void k_encode_mfma(const void *__restri
     const int j = lane & 31, hs = lane >> 5;
     const float *ptsf = reinterpret_cast<const float *>(pts);
     const float *c01f = reinterpret_cast<const float *>(c01);
-    const float4 *cnv = reinterpret_cast<const float4 *>(cn);
     const int n_cblk = K / 32;
 
     for (int pass = 0; pass < PB_TOTAL / NPB; ++pass) {
-        // point-side operands: lane (j, hs) supplies coordinate hs of point j of each block, times -2
+        // point-side operands: lane (j, hs) supplies coordinate hs of point j of each block, times -2,
+        // and 1 in the two slots that meet the pieces of ||c||^2
         bf8v_t bop[NPB];
         float m1[NPB], m2[NPB];
         int best[NPB];
@@ -131,31 +140,34 @@ __global__ __launch_bounds__(MF_THREADS) void k_encode_mfma(const void *__restri
             const float v = -2.0f * ptsf[(32 * (pass * NPB + pb) + j) * 2 + hs];
             uint32_t h, m, l;
             split3(v, h, m, l);
-            const u4v_t u = {pack2(h, m), pack2(h, l), pack2(m, h), pack2(l, m)};      // h m h l m h l m
+            const u4v_t u = {pack2(h, m), pack2(h, l), pack2(m, h), BF16_ONE_ONE};     // h m h l m h 1 1
             bop[pb] = __builtin_bit_cast(bf8v_t, u);
             m1[pb] = MBIG;
             m2[pb] = MBIG;
             best[pb] = 0;
         }
-        for (int cb = 0; cb < n_cblk; ++cb) {
-            // codeword-side operand: coordinate hs of codeword cb*32 + j, pieces ordered to pair with h m h l m h l m
-            uint32_t h, m, l;
-            split3(c01f[(cb * 32 + j) * 2 + hs], h, m, l);
-            const u4v_t ua = {pack2(h, h), pack2(m, h), pack2(m, l), pack2(m, l)};     // h h m h m l m l
-            const bf8v_t aop = __builtin_bit_cast(bf8v_t, ua);
-            // accumulator input: ||c||^2 of the lane's 16 rows 8q + 4hs + t
-            f16v_t cop;
+        const f16v_t zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+        for (int cb = 0; cb < n_cblk; cb += 2) {                   // n_cblk is even
+            // codeword-side operands of blocks cb and cb+1: coordinate hs of codeword 32 cb + j in the
+            // order h h m h m l that meets h m h l m h, then this half's two pieces of ||c||^2
+            bf8v_t aop[2];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 v = cnv[cb * 8 + 2 * q + hs];
-                cop[4 * q] = v.x; cop[4 * q + 1] = v.y; cop[4 * q + 2] = v.z; cop[4 * q + 3] = v.w;
+            for (int u = 0; u < 2; ++u) {
+                uint32_t h, m, l;
+                split3(c01f[((cb + u) * 32 + j) * 2 + hs], h, m, l);
+                const u4v_t ua = {pack2(h, h), pack2(m, h), pack2(m, l), e67[((cb + u) * 32 + j) * 2 + hs]};
+                aop[u] = __builtin_bit_cast(bf8v_t, ua);
             }
 #pragma unroll
             for (int pb = 0; pb < NPB; ++pb) {
-                const f16v_t d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop, bop[pb], cop, 0, 0, 0);
+                const f16v_t d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[0], bop[pb], zero, 0, 0, 0);
+                const f16v_t e = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[1], bop[pb], zero, 0, 0, 0);
                 const float t0 = mmin3(d[0], d[1], d[2]), t1 = mmin3(d[3], d[4], d[5]), t2 = mmin3(d[6], d[7], d[8]);
                 const float t3 = mmin3(d[9], d[10], d[11]), t4 = mmin3(d[12], d[13], d[14]);
-                const float cm = __builtin_fminf(mmin3(t0, t1, t2), mmin3(t3, t4, d[15]));
+                const float s0 = mmin3(e[0], e[1], e[2]), s1 = mmin3(e[3], e[4], e[5]), s2 = mmin3(e[6], e[7], e[8]);
+                const float s3 = mmin3(e[9], e[10], e[11]), s4 = mmin3(e[12], e[13], e[14]);
+                const float r0 = mmin3(t0, t1, t2), r1 = mmin3(t3, t4, d[15]), r2 = mmin3(s0, s1, s2), r3 = mmin3(s3, s4, e[15]);
+                const float cm = __builtin_fminf(mmin3(r0, r1, r2), r3);
                 best[pb] = (cm < m1[pb]) ? cb : best[pb];
                 m2[pb] = __builtin_amdgcn_fmed3f(m1[pb], m2[pb], cm);   // m1 <= m2: second smallest chunk minimum
                 m1[pb] = __builtin_fminf(m1[pb], cm);
@@ -172,35 +184,38 @@ __global__ __launch_bounds__(MF_THREADS) void k_encode_mfma(const void *__restri
             const bool other = o1 < m1[pb];
             const float M1 = __builtin_fminf(m1[pb], o1);
             const float M2 = __builtin_fminf(__builtin_fmaxf(m1[pb], o1), __builtin_fminf(m2[pb], o2));
-            const int cbb = other ? ob : best[pb];                 // best 32-codeword block ...
-            const int hb = other ? (hs ^ 1) : hs;                  // ... and which 16 of its rows
+            const int cbb = other ? ob : best[pb];                 // first block of the best chunk ...
+            const int hb = other ? (hs ^ 1) : hs;                  // ... and which 16 rows of its two blocks
             const float2 x = pts[32 * pbg + j];
             const float n1 = fabsf(x.x) + fabsf(x.y);
-            const float emax = 9.54e-7f * (R + n1) * (R + n1);                   // 2^-20 (R + n1)^2
+            const float emax = 1.91e-6f * (R + n1) * (R + n1);                   // 2^-19 (R + n1)^2
             const float xx = __builtin_fmaf(x.y, x.y, x.x * x.x);
             const float d2 = fmaxf(M1 + xx * 1.000001f + emax, 0.0f);            // >= true best squared distance
             const float rho = sqrtf(d2) * 1.000001f + 0.0625f;
-            const float eps = 9.55e-7f * (2.0f * n1 + rho) * (2.0f * n1 + rho);
+            const float eps = 1.92e-6f * (2.0f * n1 + rho) * (2.0f * n1 + rho);
             const bool safe = (M2 - M1 > 2.0f * eps) && (emax < 1.0e-3f);
-            // this lane checks rows 8q + 4hb + t for q = 2hs, 2hs+1 (ascending index), its partner the other two q
+            // this lane checks rows 8q + 4hb + t of both blocks for q = 2hs, 2hs+1 (ascending index), its partner the other two q
             float bd = MBIG;
             int bi = 0x7fffffff;
 #pragma unroll
-            for (int qq = 0; qq < 2; ++qq) {
+            for (int u = 0; u < 2; ++u) {
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const int ci = cbb * 32 + 8 * (2 * hs + qq) + 4 * hb + t;
-                    const float dd = mdist2(x.x, x.y, c01[ci]);
-                    if (dd < bd) {
-                        bd = dd;
-                        bi = ci;
+                for (int qq = 0; qq < 2; ++qq) {
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const int ci = (cbb + u) * 32 + 8 * (2 * hs + qq) + 4 * hb + t;
+                        const float dd = mdist2(x.x, x.y, c01[ci]);
+                        if (dd < bd) {
+                            bd = dd;
+                            bi = ci;
+                        }
                     }
                 }
             }
             const float od = __shfl_xor(bd, 32, WAVE);
             const int oi = __shfl_xor(bi, 32, WAVE);
             if (od < bd || (od == bd && oi < bi)) bi = oi;
-            if (hs == 0) idxl[32 * pbg + j] = bi;
+            if (hs == 0) idxl[32 * pbg + j] = (uint16_t)bi;
             if (!safe && hs == 0) flagged |= 1u << pb;
             asm volatile("" ::: "memory");
         }
@@ -230,7 +245,7 @@ __global__ __launch_bounds__(MF_THREADS) void k_encode_mfma(const void *__restri
                         bi = oi;
                     }
                 }
-                if (lane == src) idxl[32 * pbg + src] = bi;
+                if (lane == src) idxl[32 * pbg + src] = (uint16_t)bi;
             }
         }
     }
@@ -239,12 +254,13 @@ __global__ __launch_bounds__(MF_THREADS) void k_encode_mfma(const void *__restri
     // ---------------- pack: the lane's 8 fields are exactly `bits` bytes, byte aligned in the row
     if (active) {
         const int bits = p.bits;
-        const int4 ia = *reinterpret_cast<const int4 *>(idxl + 8 * pos), ib = *reinterpret_cast<const int4 *>(idxl + 8 * pos + 4);
-        const int idx[8] = {ia.x, ia.y, ia.z, ia.w, ib.x, ib.y, ib.z, ib.w};
+        const uint4 iv = *reinterpret_cast<const uint4 *>(idxl + 8 * pos);
+        const unsigned idx[8] = {iv.x & 0xffffu, iv.x >> 16, iv.y & 0xffffu, iv.y >> 16,
+                                 iv.z & 0xffffu, iv.z >> 16, iv.w & 0xffffu, iv.w >> 16};
         uint8_t *dst = packed + (int64_t)row * p.row_bytes + (int64_t)(c >> 4) * bits;
         unsigned __int128 acc = 0;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) acc |= (unsigned __int128)(unsigned)idx[k] << (k * bits);
+        for (int k = 0; k < 8; ++k) acc |= (unsigned __int128)idx[k] << (k * bits);
         for (int t = 0; t < bits; ++t) dst[t] = (uint8_t)(acc >> (8 * t));
         if (col0 + 16 == p.d_in) {                              // last lane of the row zeroes the padding
             const int64_t used = (int64_t)(p.d_in >> 4) * bits;
@@ -257,7 +273,7 @@ __global__ __launch_bounds__(MF_THREADS) void k_encode_mfma(const void *__restri
 bool mfma_encode_supported(const Problem &p) {
     const int unit = p.block > 16 ? p.block : 16;
     if (p.d_in % unit) return false;
-    if (p.K % 32 || p.bits > 11) return false;
+    if (p.K % 64 || p.bits > 11) return false;          // whole chunks of two 32-codeword blocks
     return p.block >= 64;
 }
 
@@ -267,7 +283,17 @@ static hipError_t launch_mdb(const void *W, int64_t ldw, const Problem &p, const
     const int64_t n_items = (int64_t)p.d_out * n_slabs;
     if (n_items > 0x7fffffff) return hipErrorNotSupported;
     const unsigned blocks = (unsigned)((n_items + MF_WAVES - 1) / MF_WAVES);
-    const size_t lds = ((size_t)p.K * 3 + (size_t)MF_WAVES * MF_WAVE_LDS_FLOATS) * sizeof(float);
+    const size_t lds = ((size_t)p.K * 4 + (size_t)MF_WAVES * MF_WAVE_LDS_FLOATS) * sizeof(float);
+    if (lds > 64 * 1024) {
+        // More than the default 64 KB of LDS per workgroup has to be asked for (a host-side setting
+        // of the current device, cheap enough to repeat on every launch).
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_mfma<DTYPE, B>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, MF_MAX_LDS_BYTES);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            return hipErrorNotSupported;
+        }
+    }
     hipLaunchKernelGGL((k_encode_mfma<DTYPE, B>), dim3(blocks), dim3(MF_THREADS), lds, p.stream, W, ldw, p, norms, packed,
                        n_slabs, (int)n_items);
     return hipGetLastError();
