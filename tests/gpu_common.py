@@ -27,7 +27,7 @@ class Case:
         self.W = W32
         self.s = orc.channel_scales(synth.act_rms_host(seed + 1, d_in), 0.3) if scale else None
         self.sg = orc.sign_mask(seed + 2, d_in) if signs else None
-        if sigma == "calibrated":
+        if isinstance(sigma, str) and sigma == "calibrated":
             self.sigma = orc.calibrate_sigma(self.W, block, chan_scale=self.s, signs=self.sg)
         else:
             self.sigma = sigma                                  # None or an explicit array

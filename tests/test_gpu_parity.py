@@ -22,7 +22,7 @@ def codebooks(orc):
     (B=7, B=11 on 2^20 samples, seed 0) from the library's CPU trainer."""
     out = {}
     xy = orc.gauss_samples(0, 1 << 13)
-    for bits in (1, 3, 5):
+    for bits in (1, 3, 5, 6):
         out[bits] = orc.lloyd(xy, 1 << bits, max_iters=30, tol=1e-5)[0].astype(np.float32)
     out[7] = qamw.train_codebook(7, 1 << 20, seed=0)[0]
     out[8] = qamw.train_codebook(8, 1 << 18, seed=0, max_iters=60)[0]
@@ -58,6 +58,7 @@ SHAPES = [
     (25, 6, 3072, 11, 256, "f32"),
     (26, 13, 4096, 7, 128, "bf16"),
     (27, 4, 3072, 7, 1024, "f32"),
+    (28, 10, 2304, 6, 256, "bf16"),        # K = 64: the smallest codebook the matrix-core shortlist takes
 ]
 
 
@@ -139,6 +140,40 @@ def test_exact_ties_take_lowest_index(orc, kernel_path):
     assert np.all(got < 16)
     diff = got != ref["idx"]
     assert np.all((ref_half["d2"][diff] - ref_half["d1"][diff]) < 1e-6 * ref_half["d2"][diff])
+
+
+@pytest.mark.parametrize("kind", ["far_codebook", "clustered", "duplicates_across_chunks", "wild_sigma"])
+def test_shortlist_stress(orc, codebooks, kernel_path, kind):
+    """Inputs that strain the encoder's shortlist-then-exact-recheck decision (the approximate scores
+    must never decide an index): a codebook far larger than the data, codewords packed closer than the
+    score error, exact ties between codewords that sit in different chunks, and per-pair gains spread
+    over six orders of magnitude.  The indices must still be the oracle's."""
+    say(f"[shortlist] {kind} path={kernel_path}")
+    rng = np.random.default_rng(77)
+    bits, d_out, d_in, block = 8, 24, 2048, 128
+    cb = np.array(codebooks[8], dtype=np.float32)
+    sigma = "calibrated"
+    if kind == "far_codebook":
+        cb = cb * np.float32(64.0)
+    elif kind == "clustered":
+        cb[64:] = (np.float32(0.5) + np.float32(1e-4) * rng.standard_normal((192, 2))).astype(np.float32)
+    elif kind == "duplicates_across_chunks":
+        cb[128:] = cb[:128]                                  # entry i equals entry i + 128: another chunk
+    else:
+        sigma = (10.0 ** rng.uniform(-4.5, 1.5, d_in // 2) / np.sqrt(d_in)).astype(np.float32)
+    case = Case(orc, 61, d_out, d_in, bits, block, dtype="bf16", codebook=cb, sigma=sigma)
+    ref = case.oracle_encode(orc)
+    packed, norms = case.gpu_encode()
+    got = orc.unpack(packed, d_in, bits)
+    if kind == "duplicates_across_chunks":
+        assert np.all(ref["idx"] < 128) and np.all(got < 128)
+        half = Case(orc, 61, d_out, d_in, 7, block, dtype="bf16", codebook=cb[:128], sigma=sigma).oracle_encode(orc)
+        diff = got != half["idx"]
+        assert np.all((half["d2"][diff] - half["d1"][diff]) < 1e-6 * half["d2"][diff])
+    else:
+        rep = {}
+        check_encode(orc, case, packed, norms, ref, report=rep)
+        say("   ", rep)
 
 
 def test_config0_full_matrix(orc, codebooks):
