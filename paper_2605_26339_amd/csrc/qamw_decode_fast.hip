@@ -7,18 +7,29 @@
 // across the wave (qamw_wave_fwht.hpp), applies row and column factors and stores 16 bf16.
 // Column constants (1/s_j with the sign mask and the transform's lane sign folded in, sigma_k)
 // are loaded once per slab and reused for every row.
+#include <type_traits>
+
 #include "qamw_common.hpp"
 #include "qamw_internal.hpp"
 #include "qamw_wave_fwht.hpp"
 
 namespace qamw {
 
-constexpr int DF_THREADS = 256;
+#ifndef QAMW_DF_THREADS
+#define QAMW_DF_THREADS 256
+#endif
+#ifndef QAMW_DF_ROWS
+#define QAMW_DF_ROWS 2
+#endif
+#ifndef QAMW_DF_UNIT_ROWS
+#define QAMW_DF_UNIT_ROWS 16
+#endif
+constexpr int DF_THREADS = QAMW_DF_THREADS;
 constexpr int DF_WAVES = DF_THREADS / WAVE;
 constexpr int SLAB = 1024;
 constexpr int DF_MAX_BATCH = QAMW_DECODE_MAX_BATCH;
-constexpr int DF_ROWS = 2;            // rows a wave has in flight at a time
-constexpr int DF_UNIT_ROWS = 16;      // rows of one unit of work (a multiple of DF_ROWS)
+constexpr int DF_ROWS = QAMW_DF_ROWS;            // rows a wave has in flight at a time
+constexpr int DF_UNIT_ROWS = QAMW_DF_UNIT_ROWS;  // rows of one unit of work (a multiple of DF_ROWS)
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float floatx2_t __attribute__((ext_vector_type(2)));
@@ -37,17 +48,6 @@ __device__ __forceinline__ float fast_recip(float s) {
     float q = __builtin_amdgcn_rcpf(s);
     float e = __builtin_fmaf(-s, q, 1.0f);
     return __builtin_fmaf(q, e, q);
-}
-
-__device__ __forceinline__ void load_group(uint32_t (&d)[4], const uint32_t *pk32, int64_t b0, int64_t total_dw) {
-    const int64_t d0 = b0 >> 2;
-    if (d0 + 3 < total_dw) {
-#pragma unroll
-        for (int t = 0; t < 4; ++t) d[t] = pk32[d0 + t];
-    } else {
-#pragma unroll
-        for (int t = 0; t < 4; ++t) d[t] = pk32[min(d0 + t, total_dw - 1)];
-    }
 }
 
 // Per-lane column constants of 16 consecutive columns starting at c (a multiple of 16):
@@ -103,8 +103,8 @@ struct DecodeMat {
     int d_out, d_in, n_slabs, n_groups;
 };
 
-// Work list of one launch.  A unit is (matrix, group of R rows, slab), numbered matrix-major, then
-// row-group-major, slab fastest: unit numbers follow memory order.
+// Work list of one launch.  A unit is (matrix, group of DF_UNIT_ROWS rows, slab), numbered matrix-major,
+// then row-group-major, slab fastest: unit numbers follow memory order.
 struct DecodeBatch {
     DecodeMat m[DF_MAX_BATCH];
     int unit_begin[DF_MAX_BATCH + 1];     // first unit of each matrix; unit_begin[n] = total
@@ -115,13 +115,16 @@ struct DecodeBatch {
 };
 
 // Decode kernel over a batch of matrices.  A block (4 waves) stages the codebook into LDS once; wave w
-// of the grid takes unit w: DF_UNIT_ROWS rows of one 1024-column slab, R rows in flight at a time, with
-// the slab's column constants loaded once.  Units are numbered in memory order and blocks are dispatched
-// in that order, which keeps the reads and writes in flight close together in HBM.  (The loop also
-// supports a grid smaller than the work, n_waves < units, each wave then striding through the units.)
+// of the grid takes unit w: DF_UNIT_ROWS rows of one 1024-column slab, with the slab's column constants
+// loaded once.  Units are numbered in memory order and blocks are dispatched in that order, which
+// keeps the reads and writes in flight close together in HBM.  The row loop is software pipelined:
+// the packed words of the next R rows are requested before the current R rows are computed and
+// stored, so a wave never waits for its own stores to drain before its next loads are under way
+// (loads and stores retire through one in-order counter on this chip).
 template <int BITS, int B, bool OUT_BF16, int R>
 __global__ __launch_bounds__(DF_THREADS) void k_decode_fast(DecodeBatch bt, int n_waves) {
     extern __shared__ float2 cb_lds[];                          // K codewords
+    typedef u32x4_t u32x4_a4_t __attribute__((aligned(4)));     // a 16-byte load that is only 4-byte aligned
     const int lane = threadIdx.x & (WAVE - 1);
     const int wid = threadIdx.x >> 6;
     const int wave = __builtin_amdgcn_readfirstlane(blockIdx.x * DF_WAVES + wid);
@@ -129,120 +132,141 @@ __global__ __launch_bounds__(DF_THREADS) void k_decode_fast(DecodeBatch bt, int 
     const int pos = slab_pos(lane);
     // after the half exchange: whose sub-block this lane stores in the first / second store instruction, and which half
     const int pos_a = slab_pos(lane & 31), pos_b = slab_pos((lane & 31) + 32), half = lane >> 5;
-    const int total_units = bt.unit_begin[bt.n];
-
-    struct Unit {
-        int mi, slab, row0;
-    };
-    auto locate = [&](int u, Unit &q) {
-        int mi = 0;
-        while (mi + 1 < bt.n && u >= bt.unit_begin[mi + 1]) ++mi;
-        const int local = u - bt.unit_begin[mi];
-        const int ns = bt.m[mi].n_slabs;
-        // the division runs on the vector ALU; readfirstlane returns the (uniform) results to scalar registers
-        q.mi = mi;
-        q.slab = __builtin_amdgcn_readfirstlane(local % ns);
-        q.row0 = __builtin_amdgcn_readfirstlane((local / ns) * DF_UNIT_ROWS);
-    };
-    auto lane_col = [&](const Unit &q) {                        // first of the lane's 16 columns (0 for idle lanes)
-        const int col0 = q.slab * SLAB + 16 * pos;
-        return (col0 < bt.m[q.mi].d_in) ? col0 : 0;
-    };
-    auto fetch = [&](const Unit &q, int sub, uint32_t (&d)[R][4], float (&rn)[R]) {
-        const DecodeMat &M = bt.m[q.mi];
-        const int64_t byte_off = (int64_t)(lane_col(q) >> 4) * BITS;   // 8 fields of BITS bits = BITS bytes per lane
-        const uint32_t *pk32 = reinterpret_cast<const uint32_t *>(M.packed);
-        const int64_t total_dw = (int64_t)M.d_out * (M.row_bytes >> 2);
-#pragma unroll
-        for (int t = 0; t < R; ++t) {
-            const int row = min(q.row0 + sub + t, M.d_out - 1); // rows past the end re-read the last row
-            load_group(d[t], pk32, (int64_t)row * M.row_bytes + byte_off, total_dw);
-            rn[t] = M.norms[row];
-        }
-    };
 
     const float2 *cbk = reinterpret_cast<const float2 *>(bt.codebook);
     for (int i = threadIdx.x; i < bt.K; i += DF_THREADS) cb_lds[i] = cbk[i];
     __syncthreads();
+    if (wave >= n_waves) return;                                // n_waves = number of units; surplus waves of the last block
+
+    // which matrix, slab and rows (all uniform over the wave)
+    int mi = 0;
+    while (mi + 1 < bt.n && wave >= bt.unit_begin[mi + 1]) ++mi;
+    const DecodeMat &M = bt.m[mi];
+    const int local = wave - bt.unit_begin[mi];
+    const int n_slabs = M.n_slabs;
+    // the division runs on the vector ALU; readfirstlane returns the (uniform) results to scalar registers
+    const int slab = __builtin_amdgcn_readfirstlane(local % n_slabs);
+    const int row0 = __builtin_amdgcn_readfirstlane((local / n_slabs) * DF_UNIT_ROWS);
+    const int d_in = M.d_in, last_row = M.d_out - 1;
+    const int64_t row_bytes = M.row_bytes, ldo = M.ldo;
+    const uint8_t *packed = M.packed;
+    const float *norms = M.norms;
+    void *out = M.out;
+
+    const int col0 = slab * SLAB + 16 * pos;
+    const int c = (col0 < d_in) ? col0 : 0;                     // first of the lane's 16 columns (0 for idle lanes)
+    const int slab_cols = min(SLAB, d_in - slab * SLAB);        // valid columns of this slab
+    // The lane's 8 fields are BITS bytes at byte (c/16)*BITS of the row: rows are multiples of 4 bytes, so the
+    // position inside a dword is the same in every row.
+    const unsigned lane_off = (unsigned)(c >> 4) * BITS;
+    const unsigned lane_b0 = lane_off & ~3u;
+    const int sh = (int)(lane_off & 3u) * 8;
+    const unsigned row_dw = (unsigned)(row_bytes >> 2);
 
     float qs[16], sig[8];
-    int have_mi = -1, have_slab = -1;
-    for (int u = (wave < n_waves) ? wave : total_units; u < total_units; u += n_waves) {   // surplus waves idle
-        Unit cur;
-        locate(u, cur);
-        const DecodeMat &M = bt.m[cur.mi];
-        const int c = lane_col(cur);
-        if (cur.mi != have_mi || cur.slab != have_slab) {       // uniform over the wave
-            Problem pc;
-            pc.chan_scale = M.chan_scale;
-            pc.signs = M.signs;
-            pc.pair_sigma = M.pair_sigma;
-            pc.sigma_default = bt.sigma_default;
-            load_column_constants(qs, sig, pc, c, ls.parity);
-            have_mi = cur.mi;
-            have_slab = cur.slab;
-        }
-        const int slab_cols = min(SLAB, M.d_in - cur.slab * SLAB);   // valid columns of this slab
-        const int64_t byte_off = (int64_t)(c >> 4) * BITS;
-        const int last_row = M.d_out - 1;
-        for (int sub = 0; sub < DF_UNIT_ROWS && cur.row0 + sub <= last_row; sub += R) {
-        uint32_t d[R][4];
-        float rn[R];
-        fetch(cur, sub, d, rn);                                 // latency is hidden by the other waves of the SIMD
-#pragma unroll
-        for (int t = 0; t < R; ++t) {
-            const int row = cur.row0 + sub + t;
-            const int sh = (int)(((int64_t)min(row, last_row) * M.row_bytes + byte_off) & 3) * 8;
-            uint32_t w[4];
-            w[0] = __builtin_amdgcn_alignbit(d[t][1], d[t][0], sh);
-            w[1] = __builtin_amdgcn_alignbit(d[t][2], d[t][1], sh);
-            w[2] = __builtin_amdgcn_alignbit(d[t][3], d[t][2], sh);
-            w[3] = d[t][3] >> sh;
-            float x[16];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                float2 cw = cb_lds[field<BITS>(w, k)];
-                x[2 * k] = sig[k] * cw.x;
-                x[2 * k + 1] = sig[k] * cw.y;
-            }
-            fwht_wave<B>(x, ls);
-            const float a = rn[t] * bt.inv_sqrt_block;          // row factor r * block^-1/2
-            if (OUT_BF16) {
-                uint32_t o[8];
-#pragma unroll
-                for (int e = 0; e < 16; e += 2) {
-                    floatx2_t v = {(x[e] * a) * qs[e], (x[e + 1] * a) * qs[e + 1]};
-                    o[e >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
-                }
-                // A lane's 16 bf16 are 32 consecutive bytes.  Storing them as they are would make each store
-                // instruction write every other 16 bytes; instead lanes i and i+32 trade one half each
-                // (v_permlane32_swap), after which lanes 0-31 hold the first halves and lanes 32-63 the second
-                // halves of 32 neighbouring sub-blocks: each store instruction then covers 1 KB without holes.
-                uint32_t lo[4] = {o[0], o[1], o[2], o[3]}, hi[4] = {o[4], o[5], o[6], o[7]};
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    auto r = __builtin_amdgcn_permlane32_swap(lo[q], hi[q], false, false);   // upper lanes' lo <-> lower lanes' hi
-                    lo[q] = r[0];
-                    hi[q] = r[1];
-                }
-                if (row <= last_row) {
-                    u32x4_t *dst = reinterpret_cast<u32x4_t *>(reinterpret_cast<uint16_t *>(M.out) + (int64_t)row * M.ldo + cur.slab * SLAB);
-                    // instruction A: sub-blocks of lanes 0-31; instruction B: sub-blocks of lanes 32-63.
-                    // The output is written once and not read again by this kernel: streaming stores.
-                    const u32x4_t va = {lo[0], lo[1], lo[2], lo[3]}, vb = {hi[0], hi[1], hi[2], hi[3]};
-                    if (16 * pos_a < slab_cols) __builtin_nontemporal_store(va, dst + 2 * pos_a + half);
-                    if (16 * pos_b < slab_cols) __builtin_nontemporal_store(vb, dst + 2 * pos_b + half);
-                }
-            } else if (row <= last_row && 16 * pos < slab_cols) {   // fp32 output (accuracy checks): plain per-lane stores
-                float4 *dst = reinterpret_cast<float4 *>(reinterpret_cast<float *>(M.out) + (int64_t)row * M.ldo + cur.slab * SLAB + 16 * pos);
-#pragma unroll
-                for (int e = 0; e < 16; e += 4)
-                    dst[e >> 2] = make_float4((x[e] * a) * qs[e], (x[e + 1] * a) * qs[e + 1], (x[e + 2] * a) * qs[e + 2],
-                                              (x[e + 3] * a) * qs[e + 3]);
-            }
-        }
-        }
+    {
+        Problem pc;
+        pc.chan_scale = M.chan_scale;
+        pc.signs = M.signs;
+        pc.pair_sigma = M.pair_sigma;
+        pc.sigma_default = bt.sigma_default;
+        load_column_constants(qs, sig, pc, c, ls.parity);
     }
+
+    // FULL: every row of the unit exists and is not the matrix's last row, and the slab has all 1024
+    // columns.  Then every load and store below is unconditional, which lets the compiler count them
+    // (s_waitcnt vmcnt(N) with N > 0) instead of draining the stores before each wait for loads.
+    auto run = [&](auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        auto fetch = [&](int sub, uint32_t (&d)[R][4], float (&rn)[R]) {
+#pragma unroll
+            for (int t = 0; t < R; ++t) {
+                const int row = FULL ? row0 + sub + t : min(row0 + sub + t, last_row);   // rows past the end re-read the last row
+                const uint8_t *rowp = packed + (int64_t)row * row_bytes;
+                if (FULL || row != last_row) {
+                    // 16 bytes from a 4-byte-aligned address; may run a few bytes into the next row
+                    const u32x4_t v = *reinterpret_cast<const u32x4_a4_t *>(rowp + lane_b0);
+                    d[t][0] = v[0]; d[t][1] = v[1]; d[t][2] = v[2]; d[t][3] = v[3];
+                } else {
+                    // last row of the matrix: stay inside it (the clamped words are beyond the lane's fields)
+                    const uint32_t *rw = reinterpret_cast<const uint32_t *>(rowp);
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) d[t][k] = rw[min((lane_b0 >> 2) + k, row_dw - 1u)];
+                }
+                rn[t] = norms[row];
+            }
+        };
+        auto rows = [&](int sub, const uint32_t (&d)[R][4], const float (&rn)[R]) {
+#pragma unroll
+            for (int t = 0; t < R; ++t) {
+                const int row = row0 + sub + t;
+                uint32_t w[4];
+                w[0] = __builtin_amdgcn_alignbit(d[t][1], d[t][0], sh);
+                w[1] = __builtin_amdgcn_alignbit(d[t][2], d[t][1], sh);
+                w[2] = __builtin_amdgcn_alignbit(d[t][3], d[t][2], sh);
+                w[3] = d[t][3] >> sh;
+                float x[16];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    float2 cw = cb_lds[field<BITS>(w, k)];
+                    x[2 * k] = sig[k] * cw.x;
+                    x[2 * k + 1] = sig[k] * cw.y;
+                }
+                fwht_wave<B>(x, ls);
+                const float a = rn[t] * bt.inv_sqrt_block;      // row factor r * block^-1/2
+                if (OUT_BF16) {
+                    uint32_t o[8];
+#pragma unroll
+                    for (int e = 0; e < 16; e += 2) {
+                        floatx2_t v = {(x[e] * a) * qs[e], (x[e + 1] * a) * qs[e + 1]};
+                        o[e >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+                    }
+                    // A lane's 16 bf16 are 32 consecutive bytes.  Storing them as they are would make each store
+                    // instruction write every other 16 bytes; instead lanes i and i+32 trade one half each
+                    // (v_permlane32_swap), after which lanes 0-31 hold the first halves and lanes 32-63 the second
+                    // halves of 32 neighbouring sub-blocks: each store instruction then covers 1 KB without holes.
+                    uint32_t lo[4] = {o[0], o[1], o[2], o[3]}, hi[4] = {o[4], o[5], o[6], o[7]};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        auto r = __builtin_amdgcn_permlane32_swap(lo[q], hi[q], false, false);   // upper lanes' lo <-> lower lanes' hi
+                        lo[q] = r[0];
+                        hi[q] = r[1];
+                    }
+                    if (FULL || row <= last_row) {
+                        u32x4_t *dst = reinterpret_cast<u32x4_t *>(reinterpret_cast<uint16_t *>(out) + (int64_t)row * ldo + slab * SLAB);
+                        // instruction A: sub-blocks of lanes 0-31; instruction B: sub-blocks of lanes 32-63.
+                        // The output is written once and not read again by this kernel: streaming stores.
+                        const u32x4_t va = {lo[0], lo[1], lo[2], lo[3]}, vb = {hi[0], hi[1], hi[2], hi[3]};
+                        if (FULL || 16 * pos_a < slab_cols) __builtin_nontemporal_store(va, dst + 2 * pos_a + half);
+                        if (FULL || 16 * pos_b < slab_cols) __builtin_nontemporal_store(vb, dst + 2 * pos_b + half);
+                    }
+                } else if (FULL || (row <= last_row && 16 * pos < slab_cols)) {   // fp32 output (accuracy checks): plain per-lane stores
+                    float4 *dst = reinterpret_cast<float4 *>(reinterpret_cast<float *>(out) + (int64_t)row * ldo + slab * SLAB + 16 * pos);
+#pragma unroll
+                    for (int e = 0; e < 16; e += 4)
+                        dst[e >> 2] = make_float4((x[e] * a) * qs[e], (x[e + 1] * a) * qs[e + 1], (x[e + 2] * a) * qs[e + 2],
+                                                  (x[e + 3] * a) * qs[e + 3]);
+                }
+            }
+        };
+        // two buffers, used alternately: rows sub .. sub+R-1 are computed while the next R rows are on their way
+        uint32_t d0[R][4], d1[R][4];
+        float rn0[R], rn1[R];
+        fetch(0, d0, rn0);
+        for (int sub = 0; sub < DF_UNIT_ROWS; sub += 2 * R) {
+            if (!FULL && row0 + sub > last_row) break;
+            if (FULL || row0 + sub + R <= last_row) fetch(sub + R, d1, rn1);
+            rows(sub, d0, rn0);
+            if (!FULL && row0 + sub + R > last_row) break;
+            if (sub + 2 * R < DF_UNIT_ROWS && (FULL || row0 + sub + 2 * R <= last_row)) fetch(sub + 2 * R, d0, rn0);
+            rows(sub + R, d1, rn1);
+        }
+    };
+    static_assert(DF_UNIT_ROWS % (2 * R) == 0, "the row loop handles two groups of R rows per trip");
+    if (slab_cols == SLAB && row0 + DF_UNIT_ROWS <= last_row)
+        run(std::true_type{});
+    else
+        run(std::false_type{});
 }
 
 bool fast_decode_supported(const Problem &p) {
