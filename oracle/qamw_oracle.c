@@ -17,7 +17,10 @@
  * Parity pins (tests/test_oracle_*.py): Hadamard orthogonality and symmetry in
  * integers, rotation isometry, brute-force argmin, hand-computed packed bytes,
  * printed bits-per-weight values, Rayleigh mean closed form, Lloyd fixed-point
- * conditions, library bf16 cast.  What cannot be pinned: agreement with the
+ * conditions, library bf16 cast; for the polar baseline: centroid conditions and
+ * C_LM by numerical quadrature, the one-level textbook values, brute-force
+ * amplitude/phase decisions, the pair distortion identity and the corollary's
+ * closed form on samples.  What cannot be pinned: agreement with the
  * authors' own bytes (their sign generator, packing layout and codebook are not
  * published) -- parity unpinned for that, by necessity.
  *
@@ -27,6 +30,10 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+
+#ifndef M_PI
+#define M_PI 3.14159265358979323846
+#endif
 
 #define ORC_OK 0
 #define ORC_ERR 1
@@ -662,5 +669,134 @@ void orc_assign(const double *samples, int64_t n, const double *codebook, int K,
         }
         assign[s] = bi;
         err[s] = best;
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* Polar baseline (Sec. 3 "Polar Baseline"; Thm. "Polar QAM pair distortion   */
+/* decomposition"; Cor. "Rayleigh-Lloyd polar distortion bound" and the       */
+/* remark after it).                                                          */
+/*                                                                            */
+/* Amplitude: an Na-level Lloyd-Max quantiser for the unit Rayleigh density   */
+/* f(r) = r exp(-r^2/2), integrated up to the cutoff rmax (the remark: 8).    */
+/* Lloyd-Max fixed point: thresholds at the midpoints of neighbouring levels, */
+/* levels at the centroids of their cells.  The three integrals needed have   */
+/* closed forms:                                                              */
+/*   int f      = -exp(-r^2/2)                                                */
+/*   int r f    = -r exp(-r^2/2) + sqrt(pi/2) erf(r/sqrt 2)                   */
+/*   int r^2 f  = -(r^2 + 2) exp(-r^2/2)                                      */
+/* Start: level i at the (i+0.5)/Na quantile, sqrt(-2 ln(1 - q)).             */
+/* Returns the number of iterations; c_lm_out = E (U - Q(U))^2 of the final   */
+/* levels for the untruncated Rayleigh law (last cell runs to infinity).      */
+/* ------------------------------------------------------------------------- */
+static double ray_i0(double r) { return -exp(-0.5 * r * r); }
+static double ray_i1(double r) { return -r * exp(-0.5 * r * r) + sqrt(M_PI / 2.0) * erf(r / sqrt(2.0)); }
+static double ray_i2(double r) { return -(r * r + 2.0) * exp(-0.5 * r * r); }
+
+double orc_rayleigh_distortion(const double *levels, int Na)
+{
+    double D = 0.0;
+    for (int i = 0; i < Na; ++i) {
+        double lo = (i == 0) ? 0.0 : 0.5 * (levels[i - 1] + levels[i]);
+        double a = levels[i];
+        double m0, m1, m2;
+        if (i == Na - 1) { /* to infinity: i0 -> 0, i1 -> sqrt(pi/2), i2 -> 0 */
+            m0 = 0.0 - ray_i0(lo);
+            m1 = sqrt(M_PI / 2.0) - ray_i1(lo);
+            m2 = 0.0 - ray_i2(lo);
+        } else {
+            double hi = 0.5 * (levels[i] + levels[i + 1]);
+            m0 = ray_i0(hi) - ray_i0(lo);
+            m1 = ray_i1(hi) - ray_i1(lo);
+            m2 = ray_i2(hi) - ray_i2(lo);
+        }
+        D += m2 - 2.0 * a * m1 + a * a * m0;
+    }
+    return D;
+}
+
+int orc_rayleigh_lloyd_max(int Na, double rmax, int max_iters, double tol, double *levels,
+                           double *c_lm_out)
+{
+    for (int i = 0; i < Na; ++i)
+        levels[i] = sqrt(-2.0 * log(1.0 - ((double)i + 0.5) / (double)Na));
+    double *next = (double *)malloc(sizeof(double) * (size_t)Na);
+    int it;
+    for (it = 0; it < max_iters; ++it) {
+        double move = 0.0;
+        for (int i = 0; i < Na; ++i) {
+            double lo = (i == 0) ? 0.0 : 0.5 * (levels[i - 1] + levels[i]);
+            double hi = (i == Na - 1) ? rmax : 0.5 * (levels[i] + levels[i + 1]);
+            double mass = ray_i0(hi) - ray_i0(lo);
+            next[i] = (mass > 0.0) ? (ray_i1(hi) - ray_i1(lo)) / mass : levels[i];
+            if (fabs(next[i] - levels[i]) > move)
+                move = fabs(next[i] - levels[i]);
+        }
+        memcpy(levels, next, sizeof(double) * (size_t)Na);
+        if (move < tol)
+            break;
+    }
+    free(next);
+    if (c_lm_out)
+        *c_lm_out = orc_rayleigh_distortion(levels, Na);
+    return it;
+}
+
+/* The 2^B-entry table that makes the polar code a plain lookup: entry ia*Np + ip is the point with  */
+/* amplitude levels[ia] and phase (2 ip + 1) h, h = pi / Np (bin centres of Cor. 1).  The           */
+/* amplitude-major index order is this implementation's choice (the paper fixes none).              */
+void orc_polar_table(const float *levels, int Na, int Np, float *table)
+{
+    double h = M_PI / (double)Np;
+    for (int ia = 0; ia < Na; ++ia)
+        for (int ip = 0; ip < Np; ++ip) {
+            double ph = (2.0 * (double)ip + 1.0) * h;
+            table[2 * ((size_t)ia * Np + ip)] = (float)((double)levels[ia] * cos(ph));
+            table[2 * ((size_t)ia * Np + ip) + 1] = (float)((double)levels[ia] * sin(ph));
+        }
+}
+
+/* Polar quantisation of n points (x0, x1): amplitude |x| to the nearest level (lowest index on a    */
+/* tie), phase atan2(x1, x0), taken in [0, 2 pi), to the bin [2 k h, 2 (k+1) h) whose centre          */
+/* (2k+1) h is the nearest phase level.  The origin has phase 0.  Also returned, for the             */
+/* acceptance test of a lower-precision implementation: how close each decision was --               */
+/* amp_margin = |a - nearest threshold| / a (infinity with one level or a = 0),                      */
+/* phase_margin = angular distance to the nearest bin boundary in radians.                           */
+void orc_polar_quantize(const double *x, int64_t n, const float *levels, int Na, int Np,
+                        int32_t *idx, double *amp_margin, double *phase_margin)
+{
+    double two_h = 2.0 * M_PI / (double)Np;
+    for (int64_t s = 0; s < n; ++s) {
+        double x0 = x[2 * s], x1 = x[2 * s + 1];
+        double a = sqrt(x0 * x0 + x1 * x1);
+        int ia = 0;
+        double best = INFINITY;
+        for (int i = 0; i < Na; ++i) {
+            double d = fabs(a - (double)levels[i]);
+            if (d < best) {
+                best = d;
+                ia = i;
+            }
+        }
+        double am = INFINITY;
+        for (int i = 1; i < Na; ++i) {
+            double t = 0.5 * ((double)levels[i - 1] + (double)levels[i]);
+            double m = fabs(a - t);
+            if (m < am)
+                am = m;
+        }
+        double th = (a > 0.0) ? atan2(x1, x0) : 0.0;
+        if (th < 0.0)
+            th += 2.0 * M_PI;
+        int ip = (int)floor(th / two_h);
+        if (ip >= Np)
+            ip = Np - 1; /* th rounded up to 2 pi */
+        double off = th - (double)ip * two_h;
+        double pm = off < two_h - off ? off : two_h - off;
+        idx[s] = ia * Np + ip;
+        if (amp_margin)
+            amp_margin[s] = (a > 0.0) ? am / a : INFINITY;
+        if (phase_margin)
+            phase_margin[s] = (a > 0.0) ? pm : INFINITY;
     }
 }

@@ -299,3 +299,57 @@ def assign(samples, codebook, threads=1):
         with ThreadPoolExecutor(len(parts)) as ex:
             list(ex.map(run, parts))
     return a, e
+
+
+# ------------------------------------------------------------------------------ polar baseline
+def rayleigh_lloyd_max(Na: int, rmax: float = 8.0, max_iters: int = 10000, tol: float = 1e-13):
+    """Lloyd-Max levels of the unit Rayleigh density (Sec. 3 'Polar Baseline'), fp64; returns
+    (levels, C_LM, iterations)."""
+    levels = np.zeros(Na, dtype=np.float64)
+    c = C.c_double()
+    L = lib()
+    L.orc_rayleigh_lloyd_max.restype = C.c_int
+    it = L.orc_rayleigh_lloyd_max(C.c_int(Na), C.c_double(rmax), C.c_int(max_iters), C.c_double(tol),
+                                  _p(levels, C.c_double), C.byref(c))
+    return levels, float(c.value), int(it)
+
+
+def rayleigh_distortion(levels) -> float:
+    lv = np.ascontiguousarray(levels, dtype=np.float64)
+    L = lib()
+    L.orc_rayleigh_distortion.restype = C.c_double
+    return float(L.orc_rayleigh_distortion(_p(lv, C.c_double), C.c_int(lv.size)))
+
+
+def polar_table(levels, Np: int) -> np.ndarray:
+    lv = _f32(levels)
+    out = np.zeros((lv.size * Np, 2), dtype=np.float32)
+    lib().orc_polar_table(_p(lv, C.c_float), C.c_int(lv.size), C.c_int(Np), _p(out, C.c_float))
+    return out
+
+
+def polar_quantize(x, levels, Np: int):
+    """x: (..., 2) points.  Returns dict(idx, amp_margin, phase_margin) shaped like x[..., 0]."""
+    xs = np.ascontiguousarray(x, dtype=np.float64)
+    shape = xs.shape[:-1]
+    n = int(np.prod(shape)) if shape else 1
+    lv = _f32(levels)
+    idx = np.zeros(n, dtype=np.int32)
+    am = np.zeros(n, dtype=np.float64)
+    pm = np.zeros(n, dtype=np.float64)
+    lib().orc_polar_quantize(_p(xs, C.c_double), C.c_int64(n), _p(lv, C.c_float), C.c_int(lv.size), C.c_int(Np),
+                             _p(idx, C.c_int32), _p(am, C.c_double), _p(pm, C.c_double))
+    return dict(idx=idx.reshape(shape), amp_margin=am.reshape(shape), phase_margin=pm.reshape(shape))
+
+
+def encode_polar(W, levels, bits_p, block, chan_scale=None, signs=None, pair_sigma=None, mode=MODE_SPEC, threads=1):
+    """The encoder with the polar quantiser in place of the joint codebook: the same front half
+    (channel scale, row norm, rotation, pair gain), then amplitude level and phase bin per pair.
+    Index = amplitude_index * 2^bits_p + phase_index."""
+    dummy = np.array([[0.0, 0.0], [1.0, 1.0]], dtype=np.float32)          # the front half does not depend on it
+    front = encode(W, dummy, 1, block, chan_scale=chan_scale, signs=signs, pair_sigma=pair_sigma, mode=mode,
+                   want_gaps=False, want_x=True, threads=threads)
+    q = polar_quantize(front["x"], levels, 1 << bits_p)
+    q["norms"] = front["norms"]
+    q["x"] = front["x"]
+    return q
