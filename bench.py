@@ -145,6 +145,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="0 = the workload's own layer count")
     ap.add_argument("--decode-passes", type=int, default=10,
                     help="extra decode-only passes over the whole weight set after the timed steps (median and best reported)")
+    ap.add_argument("--polar", action="store_true", help="also time the polar-baseline encoder at the same bits per pair")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -206,6 +207,27 @@ def main():
         e1.synchronize()
         pass_ms.append(e0.elapsed_time(e1))
 
+    # the polar baseline at the same rate (amplitude bits + phase bits = B): one encode pass over the set
+    polar = None
+    if args.polar:
+        bits_a = wl.bits // 2
+        bits_p = wl.bits - bits_a
+        levels = torch.from_numpy(qamw.polar_codebook(bits_a, bits_p)[0]).to(dev)
+        for timed in (False, True):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for m in mats:
+                qamw.encode_polar(m["W"], levels, bits_a, bits_p, wl.block, chan_scale=m["s"], signs=m["sg"],
+                                  pair_sigma=m["sigma"], out=(m["packed"], m["norms"]))
+            e1.record()
+            e1.synchronize()
+        pol_ms = e0.elapsed_time(e1)
+        pairs_set = sum(m["d_out"] * m["d_in"] // 2 for m in mats)
+        in_bytes = pairs_set * ((8 if wl.dtype == "f32" else 4) * 2 + wl.bits / 8.0)      # W is read twice: norms, then encode
+        polar = {"bits_amplitude": bits_a, "bits_phase": bits_p, "encode_gpairs_per_s": pairs_set / (pol_ms * 1e-3) / 1e9,
+                 "encode_ms_per_pass": pol_ms, "encode_hbm_gb_per_s": in_bytes / (pol_ms * 1e-3) / 1e9,
+                 "note": "same decoder as the joint code (table lookup); packed buffers are overwritten by this pass"}
+
     cal_ms = sum(e[0].elapsed_time(e[1]) for e in all_enc)
     enc_ms = sum(e[1].elapsed_time(e[2]) for e in all_enc)
     dec_ms = sum(e[0].elapsed_time(e[1]) for e in all_dec)
@@ -259,6 +281,8 @@ def main():
                             "algorithmic_bytes_per_launch": dec_bytes / n_dec_launch},
         "wall_s_timed_region": wall,
     }
+    if polar:
+        result["polar_baseline"] = polar
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, mats, cb_host)
     print(json.dumps(result))

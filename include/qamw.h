@@ -138,6 +138,32 @@ int qamw_encode(const void *W, int dtype, int d_out, int d_in, int64_t ldw, cons
                 const int8_t *signs, const float *pair_sigma, const float *codebook, int bits,
                 int hadamard_block, uint8_t *packed_out, float *row_norms_out, void *stream);
 
+/* Polar baseline of Sec. 3 ("Polar Baseline"; distortion: the polar pair theorem and the
+ * Rayleigh-Lloyd corollary).
+ *
+ * qamw_polar_codebook (host): the 2^bits_a Lloyd-Max levels of the unit Rayleigh density
+ * f(r) = r exp(-r^2/2), by numerical integration up to the cutoff 8 (the remark after the corollary).
+ * levels_out: host, 2^bits_a floats, increasing.  table_out: host, 2^(bits_a+bits_p) x 2 floats or NULL:
+ * entry ia * 2^bits_p + ip = level ia at phase (2 ip + 1) pi / 2^bits_p (the bin centres of the corollary);
+ * with this table as `codebook`, qamw_decode / qamw_decode_batch decode a polar code.  c_lm_out (nullable):
+ * the levels' distortion E (U - Q(U))^2.
+ * Errors: bits_a outside [0, QAMW_MAX_POLAR_AMPLITUDE_BITS], bits_p outside [0,12], bits_a + bits_p outside
+ * [1,12], NULL levels_out.
+ *
+ * qamw_encode_polar (device): the encoder's front half unchanged, then per pair the nearest amplitude
+ * level (decided on squared amplitudes against squared midpoints; the lower level on a tie) and the
+ * phase bin [2k pi/Np, 2(k+1) pi/Np) containing atan2(x1, x0) in [0, 2 pi) (the origin: bin 0).
+ * Index = amplitude index * 2^bits_p + phase index, packed with bits_a + bits_p bits per pair as
+ * qamw_encode packs.  levels: device, 2^bits_a floats.
+ * Shapes: d_in a multiple of max(hadamard_block, 16), hadamard_block >= 64, W and the optional vectors
+ * 16-byte aligned, ldw a multiple of 4 (fp32) or 8 (bf16); anything else -> QAMW_ERR_UNSUPPORTED. */
+enum { QAMW_MAX_POLAR_AMPLITUDE_BITS = 6 };
+int qamw_polar_codebook(int bits_a, int bits_p, float *levels_out, float *table_out, double *c_lm_out);
+int qamw_encode_polar(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
+                      const int8_t *signs, const float *pair_sigma, const float *levels, int bits_a,
+                      int bits_p, int hadamard_block, uint8_t *packed_out, float *row_norms_out,
+                      void *stream);
+
 /* Decoder of Sec. 3.2 with D_s^-1 of Sec. B.2, bf16 output (uint16 bit patterns).
  * W_out: device, d_out rows of d_in bf16 with leading dimension ldo >= d_in (elements). */
 int qamw_decode(const uint8_t *packed, const float *row_norms, int d_out, int d_in,

@@ -302,7 +302,7 @@ def assign(samples, codebook, threads=1):
 
 
 # ------------------------------------------------------------------------------ polar baseline
-def rayleigh_lloyd_max(Na: int, rmax: float = 8.0, max_iters: int = 10000, tol: float = 1e-13):
+def rayleigh_lloyd_max(Na: int, rmax: float = 8.0, max_iters: int = 400000, tol: float = 1e-14):
     """Lloyd-Max levels of the unit Rayleigh density (Sec. 3 'Polar Baseline'), fp64; returns
     (levels, C_LM, iterations)."""
     levels = np.zeros(Na, dtype=np.float64)

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqamw.so")
 
 SOURCES = ["qamw_host.cpp", "qamw_api.hip", "qamw_general.hip", "qamw_decode_fast.hip", "qamw_encode_fast.hip",
-           "qamw_encode_mfma.hip", "qamw_calibrate_fast.hip"]
+           "qamw_encode_mfma.hip", "qamw_encode_polar.hip", "qamw_calibrate_fast.hip"]
 
 # -ffp-contract=off: the codec's fp32 steps are rounded one by one; fused multiply-adds appear only
 # where the source asks for them.  Packed fp32 instructions are disabled for the device pass.
@@ -34,6 +34,7 @@ def hipcc() -> str:
 # amdgpu-mfma-vgpr-form: matrix instructions read and write ordinary vector registers, so the
 # scores need no copies out of the accumulation register file.
 EXTRA_FLAGS = {"qamw_encode_fast.hip": ["-fno-honor-nans"],
+               "qamw_encode_polar.hip": ["-fno-honor-nans"],
                "qamw_encode_mfma.hip": ["-fno-honor-nans", "-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 

@@ -122,6 +122,24 @@ int qamw_encode(const void *W, int dtype, int d_out, int d_in, int64_t ldw, cons
     return e == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
 }
 
+int qamw_encode_polar(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
+                      const int8_t *signs, const float *pair_sigma, const float *levels, int bits_a, int bits_p,
+                      int hadamard_block, uint8_t *packed_out, float *row_norms_out, void *stream) {
+    if (!W || !levels || !packed_out || !row_norms_out) return QAMW_ERR_INVALID_ARG;
+    if (dtype != QAMW_DTYPE_F32 && dtype != QAMW_DTYPE_BF16) return QAMW_ERR_INVALID_ARG;
+    if (bits_a < 0 || bits_a > QAMW_MAX_POLAR_AMPLITUDE_BITS || bits_p < 0 || bits_p > 12) return QAMW_ERR_INVALID_ARG;
+    int rc = check_common(d_out, d_in, bits_a + bits_p, hadamard_block);
+    if (rc != QAMW_OK) return rc;
+    if (ldw < d_in) return QAMW_ERR_SHAPE;
+    qamw::Problem p = make_problem(d_out, d_in, chan_scale, signs, pair_sigma, nullptr, bits_a + bits_p, hadamard_block,
+                                   stream);
+    // nothing is launched for a shape outside the kernel's range
+    if (!qamw::polar_encode_launchable(W, dtype, ldw, p, bits_a, bits_p)) return QAMW_ERR_UNSUPPORTED;
+    if (launch_norms(W, dtype, ldw, d_out, p, row_norms_out) != hipSuccess) return QAMW_ERR_DEVICE;
+    hipError_t e = qamw::launch_encode_polar(W, dtype, ldw, p, levels, bits_a, bits_p, row_norms_out, packed_out);
+    return e == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
+}
+
 int qamw_decode(const uint8_t *packed, const float *row_norms, int d_out, int d_in, const float *chan_scale,
                 const int8_t *signs, const float *pair_sigma, const float *codebook, int bits, int hadamard_block,
                 uint16_t *W_out, int64_t ldo, void *stream) {

@@ -276,3 +276,77 @@ int qamw_train_codebook(int bits, uint64_t n_samples, uint64_t seed, int max_ite
 }
 
 }  // extern "C"
+
+namespace {
+
+// Running integrals of f(r) = r exp(-r^2/2) times 1, r, r^2 from 0 to r on a uniform grid over
+// [0, rmax] (Simpson's rule per grid interval), read back between grid points by cubic Hermite
+// interpolation (the derivative of a running integral is its integrand).
+struct RayleighTables {
+    static constexpr int N = 1 << 15;
+    double rmax, h;
+    std::vector<double> m[3];
+    static double integrand(int k, double r) {
+        const double f = r * std::exp(-0.5 * r * r);
+        return k == 0 ? f : (k == 1 ? f * r : f * r * r);
+    }
+    explicit RayleighTables(double rmax_) : rmax(rmax_), h(rmax_ / N) {
+        for (int k = 0; k < 3; ++k) {
+            m[k].assign(N + 1, 0.0);
+            for (int i = 0; i < N; ++i) {
+                const double a = h * i, b = a + h;
+                m[k][i + 1] = m[k][i] + h / 6.0 * (integrand(k, a) + 4.0 * integrand(k, 0.5 * (a + b)) + integrand(k, b));
+            }
+        }
+    }
+    double upto(int k, double r) const {
+        if (r <= 0.0) return 0.0;
+        if (r >= rmax) return m[k][N];
+        const int i = std::min((int)(r / h), N - 1);
+        const double a = h * i, t = (r - a) / h;
+        const double y0 = m[k][i], y1 = m[k][i + 1], d0 = h * integrand(k, a), d1 = h * integrand(k, a + h);
+        const double t2 = t * t, t3 = t2 * t;
+        return (2 * t3 - 3 * t2 + 1) * y0 + (t3 - 2 * t2 + t) * d0 + (-2 * t3 + 3 * t2) * y1 + (t3 - t2) * d1;
+    }
+};
+
+}  // namespace
+
+extern "C" int qamw_polar_codebook(int bits_a, int bits_p, float *levels_out, float *table_out, double *c_lm_out) {
+    if (!levels_out || bits_a < 0 || bits_a > QAMW_MAX_POLAR_AMPLITUDE_BITS || bits_p < 0 || bits_p > 12 ||
+        bits_a + bits_p < 1 || bits_a + bits_p > QAMW_MAX_BITS)
+        return QAMW_ERR_INVALID_ARG;
+    const int Na = 1 << bits_a, Np = 1 << bits_p;
+    const RayleighTables T(8.0);
+    std::vector<double> lv(Na), nx(Na);
+    for (int i = 0; i < Na; ++i) lv[i] = 4.0 * (i + 0.5) / Na;   // any increasing start converges; this one is uniform on [0, 4]
+    double D = 0.0;
+    // the fixed-point iteration contracts slowly when there are many levels (about Na^2 log(1/tol) steps)
+    for (int it = 0; it < 1000000; ++it) {
+        double move = 0.0;
+        D = 0.0;
+        for (int i = 0; i < Na; ++i) {
+            const double lo = i == 0 ? 0.0 : 0.5 * (lv[i - 1] + lv[i]);
+            const double hi = i == Na - 1 ? T.rmax : 0.5 * (lv[i] + lv[i + 1]);
+            const double m0 = T.upto(0, hi) - T.upto(0, lo), m1 = T.upto(1, hi) - T.upto(1, lo),
+                         m2 = T.upto(2, hi) - T.upto(2, lo);
+            nx[i] = m0 > 0.0 ? m1 / m0 : lv[i];
+            D += m2 - 2.0 * lv[i] * m1 + lv[i] * lv[i] * m0;     // distortion of the levels before the move
+            move = std::max(move, std::fabs(nx[i] - lv[i]));
+        }
+        lv = nx;
+        if (move < 1e-14) break;
+    }
+    for (int i = 0; i < Na; ++i) levels_out[i] = (float)lv[i];
+    if (table_out) {
+        const double h = 3.14159265358979323846 / Np;
+        for (int ia = 0; ia < Na; ++ia)
+            for (int ip = 0; ip < Np; ++ip) {
+                const double ph = (2.0 * ip + 1.0) * h;
+                table_out[2 * ((size_t)ia * Np + ip)] = (float)((double)levels_out[ia] * std::cos(ph));
+                table_out[2 * ((size_t)ia * Np + ip) + 1] = (float)((double)levels_out[ia] * std::sin(ph));
+            }
+    }
+    if (c_lm_out) *c_lm_out = D;
+    return QAMW_OK;
+}

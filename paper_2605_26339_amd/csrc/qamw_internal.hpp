@@ -61,6 +61,9 @@ hipError_t launch_decode_fast(const uint8_t *packed, const float *norms, const P
 bool fast_encode_supported(const Problem &p);
 hipError_t launch_encode_fast(const void *W, int dtype, int64_t ldw, const Problem &p, const float *norms,
                               uint8_t *packed);
+bool polar_encode_launchable(const void *W, int dtype, int64_t ldw, const Problem &p, int bits_a, int bits_p);
+hipError_t launch_encode_polar(const void *W, int dtype, int64_t ldw, const Problem &p, const float *levels, int bits_a,
+                               int bits_p, const float *norms, uint8_t *packed);
 bool mfma_encode_supported(const Problem &p);
 hipError_t launch_encode_mfma(const void *W, int dtype, int64_t ldw, const Problem &p, const float *norms,
                               uint8_t *packed);

@@ -19,7 +19,7 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
 EXPORTS = [
     "qamw_status_string", "qamw_packed_row_bytes", "qamw_paper_block_size", "qamw_bpw", "qamw_sign_mask",
     "qamw_channel_scales", "qamw_train_codebook", "qamw_calibrate_workspace_bytes", "qamw_calibrate_sigma", "qamw_encode", "qamw_decode",
-    "qamw_decode_f32", "qamw_decode_batch", "qamw_set_kernel_path",
+    "qamw_decode_f32", "qamw_decode_batch", "qamw_set_kernel_path", "qamw_polar_codebook", "qamw_encode_polar",
 ]
 
 
@@ -69,6 +69,8 @@ def lib() -> C.CDLL:
         L.qamw_decode_f32.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, i64, vp]
         L.qamw_decode_batch.argtypes = [C.POINTER(DecodeItem), i32, vp, i32, i32, vp]
         L.qamw_set_kernel_path.argtypes = [i32]
+        L.qamw_polar_codebook.argtypes = [i32, i32, vp, vp, C.POINTER(C.c_double)]
+        L.qamw_encode_polar.argtypes = [vp, i32, i32, i32, i64, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp]
         for name in EXPORTS:
             if name != "qamw_status_string":
                 getattr(L, name).restype = C.c_int
@@ -124,6 +126,18 @@ def train_codebook(bits: int, n_samples: int = 1 << 20, seed: int = 0, max_iters
     _check(lib().qamw_train_codebook(bits, n_samples, seed & (2**64 - 1), max_iters, tol, out.ctypes.data,
                                      C.byref(mse), C.byref(it)), "qamw_train_codebook")
     return out, float(mse.value), int(it.value)
+
+
+def polar_codebook(bits_a: int, bits_p: int):
+    """Rayleigh Lloyd-Max amplitude levels and the lookup table of the polar baseline.
+    Returns (levels float32 [2^bits_a], table float32 [2^(bits_a+bits_p)][2], C_LM)."""
+    ok = 0 <= bits_a <= 6 and 0 <= bits_p <= 12 and 1 <= bits_a + bits_p <= 12
+    levels = np.empty(1 << bits_a if ok else 1, dtype=np.float32)
+    table = np.empty((1 << (bits_a + bits_p) if ok else 1, 2), dtype=np.float32)
+    c_lm = C.c_double()
+    _check(lib().qamw_polar_codebook(bits_a, bits_p, levels.ctypes.data_as(C.c_void_p), table.ctypes.data_as(C.c_void_p),
+                                     C.byref(c_lm)), "qamw_polar_codebook")
+    return levels, table, float(c_lm.value)
 
 
 def set_kernel_path(path: int) -> int:
@@ -200,6 +214,28 @@ def encode(W, codebook, bits: int, block: int, chan_scale=None, signs=None, pair
     _check(lib().qamw_encode(_ptr(W), _dtype_code(W), d_out, d_in, W.stride(0), _ptr(chan_scale), _ptr(signs),
                              _ptr(pair_sigma), _ptr(codebook), bits, block, _ptr(packed), _ptr(norms),
                              _stream(stream)), "qamw_encode")
+    return packed, norms
+
+
+def encode_polar(W, levels, bits_a: int, bits_p: int, block: int, chan_scale=None, signs=None, pair_sigma=None, out=None,
+                 stream=None):
+    """Polar-baseline encode of W: index = amplitude level * 2^bits_p + phase bin, bits_a + bits_p bits per pair.
+    Returns (packed uint8 [d_out][row_bytes], row_norms float32 [d_out])."""
+    import torch
+
+    _require_cuda(W, levels, chan_scale, signs, pair_sigma)
+    if W.dim() != 2 or W.stride(1) != 1:
+        raise ValueError("W must be 2-D with unit column stride")
+    d_out, d_in = W.shape
+    rb = packed_row_bytes(d_in, bits_a + bits_p)
+    if out is None:
+        packed = torch.empty((d_out, rb), dtype=torch.uint8, device=W.device)
+        norms = torch.empty(d_out, dtype=torch.float32, device=W.device)
+    else:
+        packed, norms = out
+    _check(lib().qamw_encode_polar(_ptr(W), _dtype_code(W), d_out, d_in, W.stride(0), _ptr(chan_scale), _ptr(signs),
+                                   _ptr(pair_sigma), _ptr(levels), bits_a, bits_p, block, _ptr(packed), _ptr(norms),
+                                   _stream(stream)), "qamw_encode_polar")
     return packed, norms
 
 

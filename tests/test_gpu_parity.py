@@ -176,6 +176,84 @@ def test_shortlist_stress(orc, codebooks, kernel_path, kind):
         say("   ", rep)
 
 
+POLAR_CASES = [
+    # seed d_out d_in bits_a bits_p block dtype
+    (71, 21, 2048, 5, 6, 128, "bf16"),     # the 5+6 configuration the paper compares with at 11 bits
+    (72, 9, 5632, 3, 5, 512, "f32"),
+    (73, 5, 11008, 4, 4, 256, "bf16"),
+    (74, 33, 1280, 0, 7, 256, "f32"),      # phase only
+    (75, 17, 1024, 6, 0, 64, "f32"),       # amplitude only
+    (76, 12, 3072, 1, 1, 1024, "f32"),
+    (77, 6, 4096, 6, 6, 128, "bf16"),
+]
+
+
+@pytest.mark.parametrize("seed,d_out,d_in,bits_a,bits_p,block,dtype", POLAR_CASES)
+def test_polar_encode_and_decode_match_oracle(orc, seed, d_out, d_in, bits_a, bits_p, block, dtype):
+    """Polar baseline: amplitude level and phase bin of every pair equal the oracle's, except where the
+    oracle's own decision was within 1e-6 of a boundary (then that component may move by one step);
+    decoding the polar code through the lookup table meets the decoder's bars."""
+    say(f"[polar] seed={seed} {d_out}x{d_in} Ba={bits_a} Bp={bits_p} b={block} {dtype}")
+    bits, Np = bits_a + bits_p, 1 << bits_p
+    levels, table, _ = qamw.polar_codebook(bits_a, bits_p)
+    W = synth.weight_host(seed, d_out, d_in, 0.5)
+    W[2] = 0.0                                               # a zero row: amplitude level 0, phase bin 0
+    case = Case(orc, seed, d_out, d_in, bits, block, dtype=dtype, codebook=table, W=W)
+    ref = orc.encode_polar(case.W, levels, bits_p, block, chan_scale=case.s, signs=case.sg, pair_sigma=case.sigma)
+    packed, norms = qamw.encode_polar(case.W_dev, torch.from_numpy(levels).cuda(), bits_a, bits_p, block, chan_scale=case.s_dev,
+                                      signs=case.sg_dev, pair_sigma=case.sigma_dev)
+    torch.cuda.synchronize()
+    packed, norms = packed.cpu().numpy(), norms.cpu().numpy()
+    ref_norms = ref["norms"].astype(np.float32)
+    assert np.abs(norms.view(np.int32).astype(np.int64) - ref_norms.view(np.int32).astype(np.int64)).max() <= 1
+    got = orc.unpack(packed, d_in, bits)
+    assert np.array_equal(orc.pack(got, bits), packed)       # layout and zero padding
+    assert np.all(got[2] == 0)
+    same_norm = (norms == ref_norms)[:, None]
+    ga, gp, ra, rp = got // Np, got % Np, ref["idx"] // Np, ref["idx"] % Np
+    bad_a = (ga != ra) & same_norm
+    bad_p = (gp != rp) & same_norm
+    assert np.all(ref["amp_margin"][bad_a] < 1e-6) and np.all(np.abs(ga - ra)[bad_a] == 1)
+    step = np.minimum((gp - rp) % Np, (rp - gp) % Np)
+    assert np.all(ref["phase_margin"][bad_p] < 1e-6) and np.all(step[bad_p] == 1)
+    near = int((ref["amp_margin"] < 1e-6).sum() + (ref["phase_margin"] < 1e-6).sum())
+    say(f"    pairs {got.size}, amplitude mismatches {int(bad_a.sum())}, phase mismatches {int(bad_p.sum())}, near a boundary {near}")
+    # decode of the oracle's polar indices through the table
+    nr = ref["norms"].astype(np.float32)
+    pk = orc.pack(ref["idx"], bits)
+    f32 = case.gpu_decode(pk, nr, f32=True)
+    b16 = case.gpu_decode(pk, nr)
+    say("   ", check_decode(orc, case, ref["idx"], nr, got_f32=f32, got_bf16=b16))
+
+
+@pytest.mark.parametrize("bits_a,bits_p", [(5, 6), (3, 5)])
+def test_joint_code_beats_polar_at_equal_bits(orc, codebooks, bits_a, bits_p):
+    """Encode + decode one synthetic matrix with both codes at the same bits per pair, all on the device:
+    the polar error follows the Rayleigh-Lloyd corollary (relative Frobenius error^2 = D_polar / 2, the pairs
+    having E|x|^2 = 2), and the joint 2-D codebook does better (the paper's fixed-rate claim)."""
+    bits = bits_a + bits_p
+    say(f"[joint vs polar] B={bits} = {bits_a}+{bits_p}")
+    levels, table, c_lm = qamw.polar_codebook(bits_a, bits_p)
+    case = Case(orc, 81, 256, 4096, bits, 128, codebook=codebooks[bits])
+    Ws = (case.W * case.s[None, :]).astype(np.float64)
+
+    def rel_err(dec):
+        D = dec.astype(np.float64) * case.s[None, :]          # compare in the scaled domain the codec quantises
+        return np.linalg.norm(D - Ws) / np.linalg.norm(Ws)
+
+    pj, nj = case.gpu_encode()
+    joint = rel_err(case.gpu_decode(pj, nj, f32=True))
+    pp, npn = qamw.encode_polar(case.W_dev, torch.from_numpy(levels).cuda(), bits_a, bits_p, 128, chan_scale=case.s_dev,
+                                signs=case.sg_dev, pair_sigma=case.sigma_dev)
+    polar_case = Case(orc, 81, 256, 4096, bits, 128, codebook=table)
+    polar = rel_err(polar_case.gpu_decode(pp.cpu().numpy(), npn.cpu().numpy(), f32=True))
+    h = np.pi / (1 << bits_p)
+    predicted = np.sqrt(0.5 * (c_lm + 2 * (2 - c_lm) * (1 - np.sin(h) / h)))
+    say(f"    relative Frobenius error: joint {joint:.5f}, polar {polar:.5f} (corollary: {predicted:.5f})")
+    assert abs(polar - predicted) < 0.03 * predicted
+    assert joint < polar
+
+
 def test_config0_full_matrix(orc, codebooks):
     """BASELINE config 0: 2048 x 2048 fp32, b = 128, K = 2048, every pair checked."""
     say("[config0] 2048x2048 B=11 b=128")

@@ -149,6 +149,45 @@ def test_decode_batch_rejects_bad_arguments():
         assert L.qamw_decode_batch(arr2, 2, cb, 11, 256 if bad.d_in == 384 else 128, None) == want
 
 
+def test_polar_codebook_matches_oracle_and_rejects_bad_arguments(orc):
+    """The library integrates the Rayleigh density numerically, the oracle in closed form: same levels."""
+    for ba, bp in [(0, 4), (1, 1), (3, 5), (5, 6), (6, 4)]:
+        lv, table, c_lm = qamw.polar_codebook(ba, bp)
+        olv, oc, _ = orc.rayleigh_lloyd_max(1 << ba)
+        assert np.abs(lv - olv).max() < 3e-7 and abs(c_lm - oc) < 1e-9
+        assert np.array_equal(table, orc.polar_table(lv, 1 << bp))
+    L = qamw.lib()
+    buf = np.zeros(8192, dtype=np.float32)
+    ptr = buf.ctypes.data_as(C.c_void_p)
+    assert L.qamw_polar_codebook(7, 2, ptr, None, None) == qamw.ERR_INVALID_ARG
+    assert L.qamw_polar_codebook(-1, 2, ptr, None, None) == qamw.ERR_INVALID_ARG
+    assert L.qamw_polar_codebook(0, 0, ptr, None, None) == qamw.ERR_INVALID_ARG
+    assert L.qamw_polar_codebook(6, 7, ptr, None, None) == qamw.ERR_INVALID_ARG          # 13 bits in all
+    assert L.qamw_polar_codebook(3, 3, None, None, None) == qamw.ERR_INVALID_ARG
+    p = C.c_void_p(0x1000)
+
+    def enc(**kw):
+        a = dict(W=p, dtype=0, d_out=8, d_in=256, ldw=256, lv=p, ba=5, bp=6, block=128, packed=p, norms=p)
+        a.update(kw)
+        return L.qamw_encode_polar(a["W"], a["dtype"], a["d_out"], a["d_in"], a["ldw"], None, None, None, a["lv"], a["ba"],
+                                   a["bp"], a["block"], a["packed"], a["norms"], None)
+
+    assert enc(W=None) == qamw.ERR_INVALID_ARG
+    assert enc(lv=None) == qamw.ERR_INVALID_ARG
+    assert enc(packed=None) == qamw.ERR_INVALID_ARG
+    assert enc(ba=7) == qamw.ERR_INVALID_ARG
+    assert enc(ba=6, bp=7) == qamw.ERR_INVALID_ARG           # 13 bits
+    assert enc(ba=0, bp=0) == qamw.ERR_INVALID_ARG
+    assert enc(dtype=3) == qamw.ERR_INVALID_ARG
+    assert enc(d_in=255, ldw=255) == qamw.ERR_SHAPE
+    assert enc(block=96) == qamw.ERR_SHAPE
+    assert enc(ldw=100) == qamw.ERR_SHAPE
+    # valid arguments outside the kernel's range: reported as unsupported, nothing launched
+    assert enc(d_in=64, ldw=64, block=32) == qamw.ERR_UNSUPPORTED
+    assert enc(d_in=72, ldw=72, block=8) == qamw.ERR_UNSUPPORTED
+    assert enc(W=C.c_void_p(0x1004)) == qamw.ERR_UNSUPPORTED  # W not 16-byte aligned
+
+
 def test_kernel_path_switch():
     prev = qamw.set_kernel_path(1)
     assert qamw.set_kernel_path(0) == 1
