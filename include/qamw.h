@@ -199,6 +199,27 @@ enum { QAMW_MAX_BATCH = 16 };
 int qamw_decode_batch(const qamw_decode_item *items, int n_items, const float *codebook, int bits,
                       int hadamard_block, void *stream);
 
+/* Fused dequantise-and-multiply (the follow-up named in the paper's Limitations, "No fused
+ * dequantization-matmul kernel"): Y = X W^T for m <= QAMW_MATMUL_MAX_ROWS activation rows, W = the matrix
+ * that qamw_decode_f32 would produce from (packed, row_norms, ...), without materialising W.
+ * By the linearity of the decoder (Sec. 3.2, Sec. B.2) and the symmetry of F (Lemma 1),
+ *     <w_i, x> = r_i * sum_k < c[idx_ik], z_k >,   z = the pairs of sigma (.) F S (x / s):
+ * the activations are rotated once, then every packed index costs one lookup and two multiply-adds per
+ * activation row; the matrix is read once, packed.
+ * X: device, m rows of d_in elements (fp32 or bf16), leading dimension ldx.  Y: device, m rows of d_out
+ * floats, leading dimension ldy.  workspace: device, at least qamw_matmul_workspace_bytes() bytes, 16-byte
+ * aligned, owned by the caller (rotated activations and per-slab partial sums; contents unspecified afterwards).
+ * Accumulation is fp32 in a fixed order (deterministic).
+ * Errors: m outside [1, QAMW_MATMUL_MAX_ROWS], NULL pointers, workspace too small or misaligned ->
+ * INVALID_ARG; ldx < d_in, ldy < d_out -> SHAPE.  Shapes: bits in {7, 8, 11}, hadamard_block >= 64, d_in a
+ * multiple of max(hadamard_block, 16), packed 4-byte aligned; anything else -> QAMW_ERR_UNSUPPORTED. */
+enum { QAMW_MATMUL_MAX_ROWS = 8 };
+int qamw_matmul_workspace_bytes(int d_in, int d_out, int m, size_t *bytes_out);
+int qamw_matmul(const void *X, int x_dtype, int m, int64_t ldx, const uint8_t *packed, const float *row_norms,
+                int d_out, int d_in, const float *chan_scale, const int8_t *signs, const float *pair_sigma,
+                const float *codebook, int bits, int hadamard_block, void *workspace, size_t workspace_bytes,
+                float *Y, int64_t ldy, void *stream);
+
 /* Which implementation the device entry points use: 0 = automatic (fast kernels when the shape
  * allows, otherwise the general ones), 1 = always the general kernels, 2 = as 0 but the encoder's
  * shortlist runs on the vector ALU instead of the matrix cores.  All three give the same indices.

@@ -176,6 +176,31 @@ int qamw_decode_batch(const qamw_decode_item *items, int n_items, const float *c
     return QAMW_OK;
 }
 
+int qamw_matmul_workspace_bytes(int d_in, int d_out, int m, size_t *bytes_out) {
+    if (!bytes_out || d_out <= 0 || m < 1 || m > QAMW_MATMUL_MAX_ROWS) return QAMW_ERR_INVALID_ARG;
+    if (d_in <= 0 || (d_in & 1)) return QAMW_ERR_SHAPE;
+    *bytes_out = qamw::matmul_workspace_bytes(d_in, d_out, m);
+    return QAMW_OK;
+}
+
+int qamw_matmul(const void *X, int x_dtype, int m, int64_t ldx, const uint8_t *packed, const float *row_norms, int d_out,
+                int d_in, const float *chan_scale, const int8_t *signs, const float *pair_sigma, const float *codebook,
+                int bits, int hadamard_block, void *workspace, size_t workspace_bytes, float *Y, int64_t ldy,
+                void *stream) {
+    if (!X || !packed || !row_norms || !codebook || !workspace || !Y) return QAMW_ERR_INVALID_ARG;
+    if (x_dtype != QAMW_DTYPE_F32 && x_dtype != QAMW_DTYPE_BF16) return QAMW_ERR_INVALID_ARG;
+    if (m < 1 || m > QAMW_MATMUL_MAX_ROWS) return QAMW_ERR_INVALID_ARG;
+    int rc = check_common(d_out, d_in, bits, hadamard_block);
+    if (rc != QAMW_OK) return rc;
+    if (ldx < d_in || ldy < d_out) return QAMW_ERR_SHAPE;
+    if (workspace_bytes < qamw::matmul_workspace_bytes(d_in, d_out, m) || (reinterpret_cast<uintptr_t>(workspace) & 15))
+        return QAMW_ERR_INVALID_ARG;
+    qamw::Problem p = make_problem(d_out, d_in, chan_scale, signs, pair_sigma, codebook, bits, hadamard_block, stream);
+    if (!qamw::matmul_supported(p, m) || (reinterpret_cast<uintptr_t>(packed) & 3)) return QAMW_ERR_UNSUPPORTED;
+    hipError_t e = qamw::launch_matmul(X, x_dtype, m, ldx, packed, row_norms, p, workspace, Y, ldy);
+    return e == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
+}
+
 int qamw_decode_f32(const uint8_t *packed, const float *row_norms, int d_out, int d_in, const float *chan_scale,
                     const int8_t *signs, const float *pair_sigma, const float *codebook, int bits,
                     int hadamard_block, float *W_out, int64_t ldo, void *stream) {

@@ -64,6 +64,10 @@ hipError_t launch_encode_fast(const void *W, int dtype, int64_t ldw, const Probl
 bool polar_encode_launchable(const void *W, int dtype, int64_t ldw, const Problem &p, int bits_a, int bits_p);
 hipError_t launch_encode_polar(const void *W, int dtype, int64_t ldw, const Problem &p, const float *levels, int bits_a,
                                int bits_p, const float *norms, uint8_t *packed);
+bool matmul_supported(const Problem &p, int m);
+size_t matmul_workspace_bytes(int d_in, int d_out, int m);
+hipError_t launch_matmul(const void *X, int xdtype, int m, int64_t ldx, const uint8_t *packed, const float *norms,
+                         const Problem &p, void *workspace, float *Y, int64_t ldy);
 bool mfma_encode_supported(const Problem &p);
 hipError_t launch_encode_mfma(const void *W, int dtype, int64_t ldw, const Problem &p, const float *norms,
                               uint8_t *packed);

@@ -1,0 +1,268 @@
+// Fused dequantise-and-multiply for a few activation rows, Y = X W^T with W the decoded matrix
+// (the follow-up the paper names in its Limitations: a fused dequantization-matmul kernel).
+//
+// The decoder is linear in the codewords (Sec. 3.2, Sec. B.2):
+//     w_i = r_i * D_s^-1 S F yhat_i,        yhat_i,k = sigma_k * c[idx_ik]   (pair k of row i)
+// and F is symmetric, S and D_s diagonal, so for an activation row x
+//     <w_i, x> = r_i * < yhat_i, F S D_s^-1 x > = r_i * sum_k < c[idx_ik], z_k >,
+//     z = the pairs of  sigma (.) F S (x / s).
+// The weights are never rotated back: the ACTIVATIONS are rotated once (m rows, d_in log b adds
+// each), and each packed index then costs one codeword lookup and two multiply-adds per
+// activation row.  HBM traffic is the packed matrix, B/8 bytes per pair, against 4 bytes per pair
+// for a bf16 matrix.
+//
+// Kernels: k_rotate_x (one wave per activation row and 1024-column slab, the encoder's register
+// transform), k_qgemv (one wave per 16 rows x slab: packed words -> indices -> LDS codebook ->
+// multiply-add against the slab's z held in registers -> one wave reduction per row; partial sums
+// per slab go to the workspace), k_gemv_finish (sums the slabs in a fixed order, times r_i).
+#include <type_traits>
+
+#include "qamw_common.hpp"
+#include "qamw_internal.hpp"
+#include "qamw_wave_fwht.hpp"
+
+namespace qamw {
+
+constexpr int GV_THREADS = 256;
+constexpr int GV_WAVES = GV_THREADS / WAVE;
+constexpr int GV_SLAB = 1024;
+constexpr int GV_UNIT_ROWS = 16;       // rows of one unit of work; lane r keeps the result of row r
+constexpr int GV_ROWS = 2;             // rows requested together
+constexpr int GV_MAX_M = 8;
+
+typedef uint32_t gv_u32x4_t __attribute__((ext_vector_type(4)));
+
+// z = sigma (.) F S (x / s) for every activation row, fp32, row-major [m][d_in].
+template <int XDTYPE, int B>
+__global__ __launch_bounds__(GV_THREADS) void k_rotate_x(const void *__restrict__ X, int64_t ldx, int m, Problem p,
+                                                         float *__restrict__ Z, int n_slabs) {
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int wid = threadIdx.x >> 6;
+    const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * GV_WAVES + wid);
+    if (item >= m * n_slabs) return;
+    const int tok = item / n_slabs, slab = item - tok * n_slabs;
+    const LaneSigns<B> ls(lane);
+    const int pos = slab_pos(lane);
+    const int col0 = slab * GV_SLAB + 16 * pos;
+    const bool active = col0 < p.d_in;
+    const int c = active ? col0 : 0;
+    float y[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = Elem<XDTYPE>::load(X, (int64_t)tok * ldx + c + e);
+    if (p.chan_scale) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) y[e] = y[e] * (1.0f / p.chan_scale[c + e]);   // times fl32(1/s_j), as the decoder does
+    }
+    if (p.signs) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) y[e] = (p.signs[c + e] < 0) ? -y[e] : y[e];
+    }
+    fwht_wave<B>(y, ls);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const float sg = p.pair_sigma ? p.pair_sigma[(c + e) >> 1] : p.sigma_default;
+        y[e] = ((y[e] * ls.parity) * p.inv_sqrt_block) * sg;
+    }
+    if (active) {
+        float4 *dst = reinterpret_cast<float4 *>(Z + (int64_t)tok * p.d_in + c);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) dst[t] = make_float4(y[4 * t], y[4 * t + 1], y[4 * t + 2], y[4 * t + 3]);
+    }
+}
+
+template <int BITS> __device__ __forceinline__ uint32_t gv_field(const uint32_t (&w)[4], int i) {
+    const int bit = i * BITS, word = bit >> 5, off = bit & 31;
+    uint32_t v = (off + BITS <= 32) ? (w[word] >> off) : __builtin_amdgcn_alignbit(w[word + 1], w[word], off);
+    return v & ((1u << BITS) - 1u);
+}
+
+// partial[(slab * MT + t) * d_out + i] = sum over the slab's pairs of <c[idx_ik], z_t,k>
+template <int BITS, int MT>
+__global__ __launch_bounds__(GV_THREADS) void k_qgemv(const uint8_t *__restrict__ packed, int64_t row_bytes, int d_out,
+                                                      int d_in, const float *__restrict__ Z, int m,
+                                                      const float *__restrict__ codebook, int K,
+                                                      float *__restrict__ partial, int n_slabs, int n_units) {
+    extern __shared__ float2 cb_lds[];
+    typedef gv_u32x4_t u32x4_a4_t __attribute__((aligned(4)));
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int wid = threadIdx.x >> 6;
+    const float2 *cbk = reinterpret_cast<const float2 *>(codebook);
+    for (int i = threadIdx.x; i < K; i += GV_THREADS) cb_lds[i] = cbk[i];
+    __syncthreads();
+    const int unit = __builtin_amdgcn_readfirstlane(blockIdx.x * GV_WAVES + wid);
+    if (unit >= n_units) return;
+    const int slab = __builtin_amdgcn_readfirstlane(unit % n_slabs);
+    const int row0 = __builtin_amdgcn_readfirstlane((unit / n_slabs) * GV_UNIT_ROWS);
+    const int last_row = d_out - 1;
+
+    const int col0 = slab * GV_SLAB + 16 * lane;               // no transform here: lanes in natural column order
+    const bool active = col0 < d_in;
+    const int c = active ? col0 : 0;
+    const unsigned lane_off = (unsigned)(c >> 4) * BITS;       // the lane's 8 fields: BITS bytes, same place in every row
+    const unsigned lane_b0 = lane_off & ~3u;
+    const int sh = (int)(lane_off & 3u) * 8;
+    const unsigned row_dw = (unsigned)(row_bytes >> 2);
+
+    // the slab's rotated activations, zero for missing tokens and idle lanes
+    float z[MT][16];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+        const bool have = active && t < m;
+        const float4 *src = reinterpret_cast<const float4 *>(Z + (int64_t)(t < m ? t : 0) * d_in + c);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 v = src[q];
+            z[t][4 * q] = have ? v.x : 0.0f;
+            z[t][4 * q + 1] = have ? v.y : 0.0f;
+            z[t][4 * q + 2] = have ? v.z : 0.0f;
+            z[t][4 * q + 3] = have ? v.w : 0.0f;
+        }
+    }
+
+    float keep[MT];                                             // lane r: the sums of row row0 + r
+#pragma unroll
+    for (int t = 0; t < MT; ++t) keep[t] = 0.0f;
+
+    auto run = [&](auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;        // every row exists and none is the matrix's last row
+        auto fetch = [&](int sub, uint32_t (&d)[GV_ROWS][4]) {
+#pragma unroll
+            for (int r = 0; r < GV_ROWS; ++r) {
+                const int row = FULL ? row0 + sub + r : min(row0 + sub + r, last_row);
+                const uint8_t *rowp = packed + (int64_t)row * row_bytes;
+                if (FULL || row != last_row) {
+                    // 16 bytes from a 4-byte-aligned address; may run a few bytes into the next row
+                    const gv_u32x4_t v = *reinterpret_cast<const u32x4_a4_t *>(rowp + lane_b0);
+                    d[r][0] = v[0]; d[r][1] = v[1]; d[r][2] = v[2]; d[r][3] = v[3];
+                } else {
+                    // last row of the matrix: stay inside it (the clamped words are beyond the lane's fields)
+                    const uint32_t *rw = reinterpret_cast<const uint32_t *>(rowp);
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) d[r][k] = rw[min((lane_b0 >> 2) + k, row_dw - 1u)];
+                }
+            }
+        };
+        auto rows = [&](int sub, const uint32_t (&d)[GV_ROWS][4]) {
+#pragma unroll
+            for (int r = 0; r < GV_ROWS; ++r) {
+                uint32_t w[4];
+                w[0] = __builtin_amdgcn_alignbit(d[r][1], d[r][0], sh);
+                w[1] = __builtin_amdgcn_alignbit(d[r][2], d[r][1], sh);
+                w[2] = __builtin_amdgcn_alignbit(d[r][3], d[r][2], sh);
+                w[3] = d[r][3] >> sh;
+                float acc[MT];
+#pragma unroll
+                for (int t = 0; t < MT; ++t) acc[t] = 0.0f;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const float2 cw = cb_lds[gv_field<BITS>(w, k)];
+#pragma unroll
+                    for (int t = 0; t < MT; ++t) acc[t] = __builtin_fmaf(cw.y, z[t][2 * k + 1], __builtin_fmaf(cw.x, z[t][2 * k], acc[t]));
+                }
+#pragma unroll
+                for (int t = 0; t < MT; ++t) {
+                    float v = acc[t];
+#pragma unroll
+                    for (int s = 1; s < WAVE; s <<= 1) v += __shfl_xor(v, s, WAVE);     // every lane ends with the row's sum
+                    keep[t] = (lane == sub + r) ? v : keep[t];
+                }
+            }
+        };
+        uint32_t d0[GV_ROWS][4], d1[GV_ROWS][4];
+        fetch(0, d0);
+        for (int sub = 0; sub < GV_UNIT_ROWS; sub += 2 * GV_ROWS) {
+            if (!FULL && row0 + sub > last_row) break;
+            if (FULL || row0 + sub + GV_ROWS <= last_row) fetch(sub + GV_ROWS, d1);
+            rows(sub, d0);
+            if (!FULL && row0 + sub + GV_ROWS > last_row) break;
+            if (sub + 2 * GV_ROWS < GV_UNIT_ROWS && (FULL || row0 + sub + 2 * GV_ROWS <= last_row)) fetch(sub + 2 * GV_ROWS, d0);
+            rows(sub + GV_ROWS, d1);
+        }
+    };
+    static_assert(GV_UNIT_ROWS % (2 * GV_ROWS) == 0 && GV_UNIT_ROWS <= WAVE, "row loop shape");
+    if (row0 + GV_UNIT_ROWS <= last_row)
+        run(std::true_type{});
+    else
+        run(std::false_type{});
+
+    if (lane < GV_UNIT_ROWS && row0 + lane <= last_row) {
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+            if (t < m) partial[((int64_t)slab * m + t) * d_out + row0 + lane] = keep[t];
+    }
+}
+
+// Y[t][i] = r_i * sum over slabs of partial[slab][t][i], slabs in ascending order
+__global__ __launch_bounds__(256) void k_gemv_finish(const float *__restrict__ partial, int n_slabs, int m, int d_out,
+                                                     const float *__restrict__ norms, float *__restrict__ Y, int64_t ldy) {
+    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (g >= (int64_t)m * d_out) return;
+    const int t = (int)(g / d_out), i = (int)(g - (int64_t)t * d_out);
+    float s = 0.0f;
+    for (int sl = 0; sl < n_slabs; ++sl) s += partial[((int64_t)sl * m + t) * d_out + i];
+    Y[(int64_t)t * ldy + i] = norms[i] * s;
+}
+
+bool matmul_supported(const Problem &p, int m) {
+    const int unit = p.block > 16 ? p.block : 16;
+    if (p.d_in % unit || p.block < 64) return false;
+    if (p.bits != 7 && p.bits != 8 && p.bits != 11) return false;
+    return m >= 1 && m <= GV_MAX_M;
+}
+
+size_t matmul_workspace_bytes(int d_in, int d_out, int m) {
+    const size_t n_slabs = (size_t)(d_in + GV_SLAB - 1) / GV_SLAB;
+    return ((size_t)m * d_in + n_slabs * (size_t)m * d_out) * sizeof(float);
+}
+
+template <int XDTYPE>
+static hipError_t launch_rotate(const void *X, int64_t ldx, int m, const Problem &p, float *Z, int n_slabs) {
+    const unsigned blocks = (unsigned)((m * n_slabs + GV_WAVES - 1) / GV_WAVES);
+#define QAMW_ROT(BB) \
+    case BB: hipLaunchKernelGGL((k_rotate_x<XDTYPE, BB>), dim3(blocks), dim3(GV_THREADS), 0, p.stream, X, ldx, m, p, Z, n_slabs); break;
+    switch (p.block) {
+        QAMW_ROT(64) QAMW_ROT(128) QAMW_ROT(256) QAMW_ROT(512) QAMW_ROT(1024)
+        default: return hipErrorNotSupported;
+    }
+#undef QAMW_ROT
+    return hipGetLastError();
+}
+
+template <int BITS>
+static hipError_t launch_qgemv(const uint8_t *packed, const Problem &p, const float *Z, int m, float *partial, int n_slabs) {
+    const int64_t n_units = (int64_t)n_slabs * ((p.d_out + GV_UNIT_ROWS - 1) / GV_UNIT_ROWS);
+    if (n_units > 0x3fffffff) return hipErrorNotSupported;
+    const unsigned blocks = (unsigned)((n_units + GV_WAVES - 1) / GV_WAVES);
+    const size_t lds = (size_t)p.K * sizeof(float2);
+#define QAMW_GV(MM) \
+    hipLaunchKernelGGL((k_qgemv<BITS, MM>), dim3(blocks), dim3(GV_THREADS), lds, p.stream, packed, p.row_bytes, p.d_out, p.d_in, \
+                       Z, m, p.codebook, p.K, partial, n_slabs, (int)n_units)
+    if (m == 1) QAMW_GV(1);
+    else if (m == 2) QAMW_GV(2);
+    else if (m <= 4) QAMW_GV(4);
+    else QAMW_GV(8);
+#undef QAMW_GV
+    return hipGetLastError();
+}
+
+// Y = X W^T for m <= 8 activation rows.  workspace: matmul_workspace_bytes(), 16-byte aligned.
+// Returns hipErrorNotSupported (nothing launched) outside the supported shapes.
+hipError_t launch_matmul(const void *X, int xdtype, int m, int64_t ldx, const uint8_t *packed, const float *norms,
+                         const Problem &p, void *workspace, float *Y, int64_t ldy) {
+    if (!matmul_supported(p, m)) return hipErrorNotSupported;
+    const int n_slabs = (p.d_in + GV_SLAB - 1) / GV_SLAB;
+    float *Z = static_cast<float *>(workspace);
+    float *partial = Z + (size_t)m * p.d_in;
+    hipError_t e = xdtype == 0 ? launch_rotate<0>(X, ldx, m, p, Z, n_slabs) : launch_rotate<1>(X, ldx, m, p, Z, n_slabs);
+    if (e != hipSuccess) return e;
+    if (p.bits == 11) e = launch_qgemv<11>(packed, p, Z, m, partial, n_slabs);
+    else if (p.bits == 8) e = launch_qgemv<8>(packed, p, Z, m, partial, n_slabs);
+    else e = launch_qgemv<7>(packed, p, Z, m, partial, n_slabs);
+    if (e != hipSuccess) return e;
+    const int64_t total = (int64_t)m * p.d_out;
+    hipLaunchKernelGGL(k_gemv_finish, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, p.stream, partial, n_slabs, m,
+                       p.d_out, norms, Y, ldy);
+    return hipGetLastError();
+}
+
+}  // namespace qamw

@@ -20,6 +20,7 @@ EXPORTS = [
     "qamw_status_string", "qamw_packed_row_bytes", "qamw_paper_block_size", "qamw_bpw", "qamw_sign_mask",
     "qamw_channel_scales", "qamw_train_codebook", "qamw_calibrate_workspace_bytes", "qamw_calibrate_sigma", "qamw_encode", "qamw_decode",
     "qamw_decode_f32", "qamw_decode_batch", "qamw_set_kernel_path", "qamw_polar_codebook", "qamw_encode_polar",
+    "qamw_matmul_workspace_bytes", "qamw_matmul",
 ]
 
 
@@ -69,6 +70,8 @@ def lib() -> C.CDLL:
         L.qamw_decode_f32.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, i64, vp]
         L.qamw_decode_batch.argtypes = [C.POINTER(DecodeItem), i32, vp, i32, i32, vp]
         L.qamw_set_kernel_path.argtypes = [i32]
+        L.qamw_matmul_workspace_bytes.argtypes = [i32, i32, i32, C.POINTER(C.c_size_t)]
+        L.qamw_matmul.argtypes = [vp, i32, i32, i64, vp, vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, C.c_size_t, vp, i64, vp]
         L.qamw_polar_codebook.argtypes = [i32, i32, vp, vp, C.POINTER(C.c_double)]
         L.qamw_encode_polar.argtypes = [vp, i32, i32, i32, i64, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp]
         for name in EXPORTS:
@@ -252,6 +255,36 @@ def decode(packed, row_norms, d_in: int, codebook, bits: int, block: int, chan_s
     _check(fn(_ptr(packed), _ptr(row_norms), d_out, d_in, _ptr(chan_scale), _ptr(signs), _ptr(pair_sigma),
               _ptr(codebook), bits, block, _ptr(out), out.stride(0), _stream(stream)),
            "qamw_decode_f32" if f32 else "qamw_decode")
+    return out
+
+
+MATMUL_MAX_ROWS = 8
+
+
+def matmul_workspace_bytes(d_in: int, d_out: int, m: int) -> int:
+    out = C.c_size_t()
+    _check(lib().qamw_matmul_workspace_bytes(d_in, d_out, m, C.byref(out)), "qamw_matmul_workspace_bytes")
+    return int(out.value)
+
+
+def matmul(X, packed, row_norms, codebook, bits: int, block: int, chan_scale=None, signs=None, pair_sigma=None,
+           workspace=None, out=None, stream=None):
+    """Y = X W^T (fp32 [m][d_out]) for m <= 8 rows of X (fp32 or bf16 [m][d_in]) against the packed matrix."""
+    import torch
+
+    _require_cuda(X, packed, row_norms, codebook, chan_scale, signs, pair_sigma)
+    if X.dim() != 2 or X.stride(1) != 1:
+        raise ValueError("X must be 2-D with unit column stride")
+    m, d_in = X.shape
+    d_out = row_norms.shape[0]
+    if workspace is None:
+        workspace = torch.empty(matmul_workspace_bytes(d_in, d_out, m), dtype=torch.uint8, device=X.device)
+    if out is None:
+        out = torch.empty((m, d_out), dtype=torch.float32, device=X.device)
+    _check(lib().qamw_matmul(_ptr(X), _dtype_code(X), m, X.stride(0), _ptr(packed), _ptr(row_norms), d_out, d_in,
+                             _ptr(chan_scale), _ptr(signs), _ptr(pair_sigma), _ptr(codebook), bits, block,
+                             _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(out), out.stride(0),
+                             _stream(stream)), "qamw_matmul")
     return out
 
 

@@ -188,6 +188,40 @@ def test_polar_codebook_matches_oracle_and_rejects_bad_arguments(orc):
     assert enc(W=C.c_void_p(0x1004)) == qamw.ERR_UNSUPPORTED  # W not 16-byte aligned
 
 
+def test_matmul_rejects_bad_arguments():
+    L = qamw.lib()
+    p = C.c_void_p(0x1000)
+    need = qamw.matmul_workspace_bytes(256, 8, 2)
+    assert need == (2 * 256 + 1 * 2 * 8) * 4
+    assert qamw.matmul_workspace_bytes(11008, 4096, 8) == (8 * 11008 + 11 * 8 * 4096) * 4
+
+    def mm(**kw):
+        a = dict(X=p, xd=0, m=2, ldx=256, packed=p, norms=p, d_out=8, d_in=256, cb=p, bits=11, block=128, ws=p,
+                 ws_bytes=need, Y=p, ldy=8)
+        a.update(kw)
+        return L.qamw_matmul(a["X"], a["xd"], a["m"], a["ldx"], a["packed"], a["norms"], a["d_out"], a["d_in"], None, None,
+                             None, a["cb"], a["bits"], a["block"], a["ws"], a["ws_bytes"], a["Y"], a["ldy"], None)
+
+    for k in ("X", "packed", "norms", "cb", "ws", "Y"):
+        assert mm(**{k: None}) == qamw.ERR_INVALID_ARG
+    assert mm(m=0) == qamw.ERR_INVALID_ARG
+    assert mm(m=9) == qamw.ERR_INVALID_ARG
+    assert mm(xd=5) == qamw.ERR_INVALID_ARG
+    assert mm(bits=0) == qamw.ERR_INVALID_ARG
+    assert mm(ws_bytes=need - 1) == qamw.ERR_INVALID_ARG
+    assert mm(ws=C.c_void_p(0x1008)) == qamw.ERR_INVALID_ARG
+    assert mm(ldx=100) == qamw.ERR_SHAPE
+    assert mm(ldy=4) == qamw.ERR_SHAPE
+    assert mm(block=96) == qamw.ERR_SHAPE
+    assert mm(bits=9) == qamw.ERR_UNSUPPORTED                 # only 7, 8 and 11 bits
+    assert mm(d_in=64, ldx=64, block=32) == qamw.ERR_UNSUPPORTED
+    assert mm(packed=C.c_void_p(0x1002)) == qamw.ERR_UNSUPPORTED
+    out = C.c_size_t()
+    assert L.qamw_matmul_workspace_bytes(256, 8, 9, C.byref(out)) == qamw.ERR_INVALID_ARG
+    assert L.qamw_matmul_workspace_bytes(255, 8, 1, C.byref(out)) == qamw.ERR_SHAPE
+    assert L.qamw_matmul_workspace_bytes(256, 8, 1, None) == qamw.ERR_INVALID_ARG
+
+
 def test_kernel_path_switch():
     prev = qamw.set_kernel_path(1)
     assert qamw.set_kernel_path(0) == 1

@@ -348,3 +348,27 @@ def test_bf16_input_is_widened_exactly(orc, small_codebook):
     Wb = orc.bf16_bits_to_f32(bits16)
     assert np.array_equal(Wb, torch.from_numpy(W).to(torch.bfloat16).to(torch.float32).numpy())
     assert np.array_equal(orc.bf16_rne(Wb), bits16)
+
+
+def test_product_with_decoded_rows_equals_product_in_the_rotated_domain(orc):
+    """The decoder is linear and F is symmetric (Lemma 1), so <w_i, x> = r_i <yhat_i, F S (x / s)>: a
+    product with the decoded matrix can rotate the activation instead of the weights.  Checked on the
+    oracle's own fp64 decode; the right-hand side is assembled here from the rotation alone."""
+    rng = np.random.default_rng(17)
+    d_out, d_in, bits, block = 12, 512, 6, 128
+    P = d_in // 2
+    cb = rng.standard_normal((1 << bits, 2)).astype(np.float32)
+    idx = rng.integers(0, 1 << bits, (d_out, P)).astype(np.int32)
+    norms = rng.uniform(0.5, 2.0, d_out).astype(np.float32)
+    s = rng.uniform(0.25, 4.0, d_in).astype(np.float32)
+    sg = orc.sign_mask(3, d_in)
+    sigma = rng.uniform(0.02, 0.08, P).astype(np.float32)
+    W = orc.decode(idx, norms, cb, bits, block, chan_scale=s, signs=sg, pair_sigma=sigma, mode=orc.MODE_TRUTH)["w"]
+    X = rng.standard_normal((3, d_in))
+    direct = X @ W.T
+    inv_s = 1.0 / s.astype(np.float64)                             # the fp64 decoder divides by s_j
+    Z = np.stack([orc.rotate_fwd_truth(x * inv_s, block, signs=sg) for x in X])        # F S (x / s)
+    Zp = Z.reshape(3, P, 2) * sigma.astype(np.float64)[None, :, None]
+    C2 = cb.astype(np.float64)[idx]                                # [d_out][P][2]
+    rotated = np.einsum("ipe,tpe->ti", C2, Zp) * norms.astype(np.float64)[None, :]
+    assert np.allclose(direct, rotated, rtol=1e-10, atol=1e-12)
