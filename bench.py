@@ -145,6 +145,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="0 = the workload's own layer count")
     ap.add_argument("--decode-passes", type=int, default=10,
                     help="extra decode-only passes over the whole weight set after the timed steps (median and best reported)")
+    ap.add_argument("--matmul", type=int, default=0, metavar="M",
+                    help="also time the fused dequantise-and-multiply with M activation rows (1..8) over the whole set")
     ap.add_argument("--polar", action="store_true", help="also time the polar-baseline encoder at the same bits per pair")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -206,6 +208,45 @@ def main():
         e1.record()
         e1.synchronize()
         pass_ms.append(e0.elapsed_time(e1))
+
+    # fused dequantise-and-multiply: one pass = Y = X W^T for every matrix of the set (what generating
+    # one token batch reads), next to the same products with the decoded bf16 matrices through torch
+    fused = None
+    if args.matmul:
+        mm = args.matmul
+        xs = {d: torch.randn((mm, d), device=dev, dtype=torch.float32).to(torch.bfloat16) for d in {m["d_in"] for m in mats}}
+        ys = [torch.empty((mm, m["d_out"]), device=dev, dtype=torch.float32) for m in mats[:per_layer]]
+        # one call per layer: its projections as independent products (a kernel benchmark; in a model some of
+        # them depend on each other and would go in separate calls)
+        mm_batches = [qamw.make_matmul_items([(xs[m["d_in"]], m["packed"], m["norms"], m["s"], m["sg"], m["sigma"], y)
+                                              for m, y in zip(mats[i:i + per_layer], ys)]) for i in range(0, len(mats), per_layer)]
+        ws_mm = torch.empty(max(b[4] for b in mm_batches), dtype=torch.uint8, device=dev)
+        times = {}
+        for kind in ("fused", "bf16"):
+            best = []
+            for rep in range(1 + 5):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                if kind == "fused":
+                    for b in mm_batches:
+                        qamw.matmul_batch(b, cb, wl.bits, wl.block, ws_mm)
+                else:
+                    for m in mats:
+                        torch.matmul(xs[m["d_in"]], m["out"].t())
+                e1.record()
+                e1.synchronize()
+                if rep:
+                    best.append(e0.elapsed_time(e1))
+            times[kind] = sorted(best)[len(best) // 2]
+        pairs_set = sum(m["d_out"] * m["d_in"] // 2 for m in mats)
+        fused_bytes = pairs_set * wl.bits / 8.0 + sum(4 * m["d_out"] + mm * (2 * m["d_in"] + 4 * m["d_out"]) for m in mats)
+        bf16_bytes = pairs_set * 4.0 + sum(mm * 2 * (m["d_in"] + m["d_out"]) for m in mats)
+        fused = {"rows": mm, "ms_per_pass": times["fused"], "gb_per_s": fused_bytes / (times["fused"] * 1e-3) / 1e9,
+                 "frac_of_hbm_peak": fused_bytes / (times["fused"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                 "algorithmic_bytes_per_pass": fused_bytes,
+                 "bf16_matmul_ms_per_pass": times["bf16"], "bf16_matmul_gb_per_s": bf16_bytes / (times["bf16"] * 1e-3) / 1e9,
+                 "speedup_vs_bf16_matmul": times["bf16"] / times["fused"],
+                 "note": "median of 5 passes over the whole set, one qamw_matmul_batch call per layer; the bf16 leg is torch.matmul on the decoded matrices, one call per matrix"}
 
     # the polar baseline at the same rate (amplitude bits + phase bits = B): one encode pass over the set
     polar = None
@@ -281,6 +322,8 @@ def main():
                             "algorithmic_bytes_per_launch": dec_bytes / n_dec_launch},
         "wall_s_timed_region": wall,
     }
+    if fused:
+        result["fused_matmul"] = fused
     if polar:
         result["polar_baseline"] = polar
     if not args.no_cpu_baseline:

@@ -213,12 +213,32 @@ int qamw_decode_batch(const qamw_decode_item *items, int n_items, const float *c
  * Errors: m outside [1, QAMW_MATMUL_MAX_ROWS], NULL pointers, workspace too small or misaligned ->
  * INVALID_ARG; ldx < d_in, ldy < d_out -> SHAPE.  Shapes: bits in {7, 8, 11}, hadamard_block >= 64, d_in a
  * multiple of max(hadamard_block, 16), packed 4-byte aligned; anything else -> QAMW_ERR_UNSUPPORTED. */
-enum { QAMW_MATMUL_MAX_ROWS = 8 };
+enum { QAMW_MATMUL_MAX_ROWS = 8, QAMW_MATMUL_MAX_BATCH = 16 };
 int qamw_matmul_workspace_bytes(int d_in, int d_out, int m, size_t *bytes_out);
 int qamw_matmul(const void *X, int x_dtype, int m, int64_t ldx, const uint8_t *packed, const float *row_norms,
                 int d_out, int d_in, const float *chan_scale, const int8_t *signs, const float *pair_sigma,
                 const float *codebook, int bits, int hadamard_block, void *workspace, size_t workspace_bytes,
                 float *Y, int64_t ldy, void *stream);
+
+/* The same for up to QAMW_MATMUL_MAX_BATCH independent products Y_i = X_i W_i^T that share the codebook, bits,
+ * hadamard_block, m and the element type of X (for instance the projections of one layer applied to their
+ * inputs): three launches in all instead of three per matrix.  items: host array, read during the call only;
+ * every pointer in it is a device pointer.  workspace: at least the sum of qamw_matmul_workspace_bytes() over
+ * the items, 16-byte aligned.  Errors as qamw_matmul, per item; nothing is launched if any item is rejected. */
+typedef struct qamw_matmul_item {
+    const void *X;               /* m rows of d_in elements, leading dimension ldx                */
+    int64_t ldx;
+    const uint8_t *packed;       /* d_out rows of qamw_packed_row_bytes(d_in, bits) bytes        */
+    const float *row_norms;      /* d_out floats                                                */
+    const float *chan_scale;     /* d_in floats or NULL                                         */
+    const int8_t *signs;         /* d_in int8 or NULL                                           */
+    const float *pair_sigma;     /* d_in/2 floats or NULL                                       */
+    float *Y;                    /* m rows of d_out floats, leading dimension ldy               */
+    int64_t ldy;
+    int32_t d_out, d_in;
+} qamw_matmul_item;
+int qamw_matmul_batch(const qamw_matmul_item *items, int n_items, int x_dtype, int m, const float *codebook,
+                      int bits, int hadamard_block, void *workspace, size_t workspace_bytes, void *stream);
 
 /* Which implementation the device entry points use: 0 = automatic (fast kernels when the shape
  * allows, otherwise the general ones), 1 = always the general kernels, 2 = as 0 but the encoder's

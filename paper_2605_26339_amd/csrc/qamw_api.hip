@@ -183,22 +183,56 @@ int qamw_matmul_workspace_bytes(int d_in, int d_out, int m, size_t *bytes_out) {
     return QAMW_OK;
 }
 
+static int matmul_batch_impl(const qamw_matmul_item *items, int n_items, int x_dtype, int m, const float *codebook, int bits,
+                             int hadamard_block, void *workspace, size_t workspace_bytes, void *stream) {
+    static_assert(QAMW_MATMUL_MAX_BATCH == qamw::QAMW_MATMUL_MAX_BATCH, "batch limits differ");
+    if (!items || !codebook || !workspace || n_items < 1 || n_items > QAMW_MATMUL_MAX_BATCH) return QAMW_ERR_INVALID_ARG;
+    if (x_dtype != QAMW_DTYPE_F32 && x_dtype != QAMW_DTYPE_BF16) return QAMW_ERR_INVALID_ARG;
+    if (m < 1 || m > QAMW_MATMUL_MAX_ROWS) return QAMW_ERR_INVALID_ARG;
+    qamw::MatmulItem its[QAMW_MATMUL_MAX_BATCH];
+    size_t need = 0;
+    bool supported = true;
+    for (int i = 0; i < n_items; ++i) {
+        const qamw_matmul_item &q = items[i];
+        if (!q.X || !q.packed || !q.row_norms || !q.Y) return QAMW_ERR_INVALID_ARG;
+        int rc = check_common(q.d_out, q.d_in, bits, hadamard_block);
+        if (rc != QAMW_OK) return rc;
+        if (q.ldx < q.d_in || q.ldy < q.d_out) return QAMW_ERR_SHAPE;
+        qamw::Problem pi = make_problem(q.d_out, q.d_in, nullptr, nullptr, nullptr, codebook, bits, hadamard_block, stream);
+        if (!qamw::matmul_supported(pi, m) || (reinterpret_cast<uintptr_t>(q.packed) & 3)) supported = false;
+        need += qamw::matmul_workspace_bytes(q.d_in, q.d_out, m);
+        its[i] = qamw::MatmulItem{q.X, q.ldx, q.packed, q.row_norms, q.chan_scale, q.signs, q.pair_sigma, q.Y, q.ldy, q.d_out, q.d_in};
+    }
+    if (workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15)) return QAMW_ERR_INVALID_ARG;
+    if (!supported) return QAMW_ERR_UNSUPPORTED;
+    qamw::Problem p = make_problem(items[0].d_out, items[0].d_in, nullptr, nullptr, nullptr, codebook, bits, hadamard_block, stream);
+    hipError_t e = qamw::launch_matmul_batch(its, n_items, x_dtype, m, p, workspace);
+    if (e == hipErrorNotSupported) return QAMW_ERR_UNSUPPORTED;
+    return e == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
+}
+
+int qamw_matmul_batch(const qamw_matmul_item *items, int n_items, int x_dtype, int m, const float *codebook, int bits,
+                      int hadamard_block, void *workspace, size_t workspace_bytes, void *stream) {
+    return matmul_batch_impl(items, n_items, x_dtype, m, codebook, bits, hadamard_block, workspace, workspace_bytes, stream);
+}
+
 int qamw_matmul(const void *X, int x_dtype, int m, int64_t ldx, const uint8_t *packed, const float *row_norms, int d_out,
                 int d_in, const float *chan_scale, const int8_t *signs, const float *pair_sigma, const float *codebook,
                 int bits, int hadamard_block, void *workspace, size_t workspace_bytes, float *Y, int64_t ldy,
                 void *stream) {
-    if (!X || !packed || !row_norms || !codebook || !workspace || !Y) return QAMW_ERR_INVALID_ARG;
-    if (x_dtype != QAMW_DTYPE_F32 && x_dtype != QAMW_DTYPE_BF16) return QAMW_ERR_INVALID_ARG;
-    if (m < 1 || m > QAMW_MATMUL_MAX_ROWS) return QAMW_ERR_INVALID_ARG;
-    int rc = check_common(d_out, d_in, bits, hadamard_block);
-    if (rc != QAMW_OK) return rc;
-    if (ldx < d_in || ldy < d_out) return QAMW_ERR_SHAPE;
-    if (workspace_bytes < qamw::matmul_workspace_bytes(d_in, d_out, m) || (reinterpret_cast<uintptr_t>(workspace) & 15))
-        return QAMW_ERR_INVALID_ARG;
-    qamw::Problem p = make_problem(d_out, d_in, chan_scale, signs, pair_sigma, codebook, bits, hadamard_block, stream);
-    if (!qamw::matmul_supported(p, m) || (reinterpret_cast<uintptr_t>(packed) & 3)) return QAMW_ERR_UNSUPPORTED;
-    hipError_t e = qamw::launch_matmul(X, x_dtype, m, ldx, packed, row_norms, p, workspace, Y, ldy);
-    return e == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
+    qamw_matmul_item it;
+    it.X = X;
+    it.ldx = ldx;
+    it.packed = packed;
+    it.row_norms = row_norms;
+    it.chan_scale = chan_scale;
+    it.signs = signs;
+    it.pair_sigma = pair_sigma;
+    it.Y = Y;
+    it.ldy = ldy;
+    it.d_out = d_out;
+    it.d_in = d_in;
+    return matmul_batch_impl(&it, 1, x_dtype, m, codebook, bits, hadamard_block, workspace, workspace_bytes, stream);
 }
 
 int qamw_decode_f32(const uint8_t *packed, const float *row_norms, int d_out, int d_in, const float *chan_scale,

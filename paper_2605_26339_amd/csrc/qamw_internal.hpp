@@ -66,8 +66,19 @@ hipError_t launch_encode_polar(const void *W, int dtype, int64_t ldw, const Prob
                                int bits_p, const float *norms, uint8_t *packed);
 bool matmul_supported(const Problem &p, int m);
 size_t matmul_workspace_bytes(int d_in, int d_out, int m);
-hipError_t launch_matmul(const void *X, int xdtype, int m, int64_t ldx, const uint8_t *packed, const float *norms,
-                         const Problem &p, void *workspace, float *Y, int64_t ldy);
+constexpr int QAMW_MATMUL_MAX_BATCH = 16;
+struct MatmulItem {
+    const void *X;
+    int64_t ldx;
+    const uint8_t *packed;
+    const float *norms, *chan_scale;
+    const int8_t *signs;
+    const float *pair_sigma;
+    float *Y;
+    int64_t ldy;
+    int d_out, d_in;
+};
+hipError_t launch_matmul_batch(const MatmulItem *items, int n, int xdtype, int m, const Problem &p, void *workspace);
 bool mfma_encode_supported(const Problem &p);
 hipError_t launch_encode_mfma(const void *W, int dtype, int64_t ldw, const Problem &p, const float *norms,
                               uint8_t *packed);

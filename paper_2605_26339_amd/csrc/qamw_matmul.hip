@@ -32,39 +32,73 @@ constexpr int GV_MAX_M = 8;
 
 typedef uint32_t gv_u32x4_t __attribute__((ext_vector_type(4)));
 
+// One product of a batch, as the kernels see it.  Z and partial point into the caller's workspace.
+struct GemvMat {
+    const void *X;
+    const uint8_t *packed;
+    const float *norms, *chan_scale, *pair_sigma;
+    const int8_t *signs;
+    float *Z, *partial, *Y;
+    int64_t ldx, ldy, row_bytes;
+    int d_out, d_in, n_slabs;
+};
+// Work lists of one launch: rotation items (activation row, slab), product units (16 rows, slab) and output
+// elements, each numbered matrix-major.
+struct GemvBatch {
+    GemvMat mat[QAMW_MATMUL_MAX_BATCH];
+    int rot_begin[QAMW_MATMUL_MAX_BATCH + 1];
+    int unit_begin[QAMW_MATMUL_MAX_BATCH + 1];
+    int out_begin[QAMW_MATMUL_MAX_BATCH + 1];
+    int n, m, K;
+    float inv_sqrt_block;
+    const float *codebook;
+};
+__device__ __forceinline__ int gv_find(const int *begin, int n, int u) {
+    int i = 0;
+    while (i + 1 < n && u >= begin[i + 1]) ++i;
+    return i;
+}
+
 // z = sigma (.) F S (x / s) for every activation row, fp32, row-major [m][d_in].
 template <int XDTYPE, int B>
-__global__ __launch_bounds__(GV_THREADS) void k_rotate_x(const void *__restrict__ X, int64_t ldx, int m, Problem p,
-                                                         float *__restrict__ Z, int n_slabs) {
+__global__ __launch_bounds__(GV_THREADS) void k_rotate_x(GemvBatch bt) {
     const int lane = threadIdx.x & (WAVE - 1);
     const int wid = threadIdx.x >> 6;
     const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * GV_WAVES + wid);
-    if (item >= m * n_slabs) return;
-    const int tok = item / n_slabs, slab = item - tok * n_slabs;
+    if (item >= bt.rot_begin[bt.n]) return;
+    const int mi = gv_find(bt.rot_begin, bt.n, item);
+    const GemvMat &M = bt.mat[mi];
+    const int local = item - bt.rot_begin[mi];
+    const int n_slabs = M.n_slabs;
+    const int tok = __builtin_amdgcn_readfirstlane(local / n_slabs), slab = __builtin_amdgcn_readfirstlane(local % n_slabs);
+    const int d_in = M.d_in;
+    const float *chan_scale = M.chan_scale, *pair_sigma = M.pair_sigma;
+    const int8_t *signs = M.signs;
     const LaneSigns<B> ls(lane);
     const int pos = slab_pos(lane);
     const int col0 = slab * GV_SLAB + 16 * pos;
-    const bool active = col0 < p.d_in;
+    const bool active = col0 < d_in;
     const int c = active ? col0 : 0;
     float y[16];
 #pragma unroll
-    for (int e = 0; e < 16; ++e) y[e] = Elem<XDTYPE>::load(X, (int64_t)tok * ldx + c + e);
-    if (p.chan_scale) {
+    for (int e = 0; e < 16; ++e) y[e] = Elem<XDTYPE>::load(M.X, (int64_t)tok * M.ldx + c + e);
+    if (chan_scale) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) y[e] = y[e] * (1.0f / p.chan_scale[c + e]);   // times fl32(1/s_j), as the decoder does
+        for (int e = 0; e < 16; ++e) y[e] = y[e] * (1.0f / chan_scale[c + e]);    // times fl32(1/s_j), as the decoder does
     }
-    if (p.signs) {
+    if (signs) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) y[e] = (p.signs[c + e] < 0) ? -y[e] : y[e];
+        for (int e = 0; e < 16; ++e) y[e] = (signs[c + e] < 0) ? -y[e] : y[e];
     }
     fwht_wave<B>(y, ls);
+    const float sigma_default = 1.0f / sqrtf((float)d_in);
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-        const float sg = p.pair_sigma ? p.pair_sigma[(c + e) >> 1] : p.sigma_default;
-        y[e] = ((y[e] * ls.parity) * p.inv_sqrt_block) * sg;
+        const float sg = pair_sigma ? pair_sigma[(c + e) >> 1] : sigma_default;
+        y[e] = ((y[e] * ls.parity) * bt.inv_sqrt_block) * sg;
     }
     if (active) {
-        float4 *dst = reinterpret_cast<float4 *>(Z + (int64_t)tok * p.d_in + c);
+        float4 *dst = reinterpret_cast<float4 *>(M.Z + (int64_t)tok * d_in + c);
 #pragma unroll
         for (int t = 0; t < 4; ++t) dst[t] = make_float4(y[4 * t], y[4 * t + 1], y[4 * t + 2], y[4 * t + 3]);
     }
@@ -78,22 +112,27 @@ template <int BITS> __device__ __forceinline__ uint32_t gv_field(const uint32_t 
 
 // partial[(slab * MT + t) * d_out + i] = sum over the slab's pairs of <c[idx_ik], z_t,k>
 template <int BITS, int MT>
-__global__ __launch_bounds__(GV_THREADS) void k_qgemv(const uint8_t *__restrict__ packed, int64_t row_bytes, int d_out,
-                                                      int d_in, const float *__restrict__ Z, int m,
-                                                      const float *__restrict__ codebook, int K,
-                                                      float *__restrict__ partial, int n_slabs, int n_units) {
+__global__ __launch_bounds__(GV_THREADS) void k_qgemv(GemvBatch bt) {
     extern __shared__ float2 cb_lds[];
     typedef gv_u32x4_t u32x4_a4_t __attribute__((aligned(4)));
     const int lane = threadIdx.x & (WAVE - 1);
     const int wid = threadIdx.x >> 6;
-    const float2 *cbk = reinterpret_cast<const float2 *>(codebook);
-    for (int i = threadIdx.x; i < K; i += GV_THREADS) cb_lds[i] = cbk[i];
+    const float2 *cbk = reinterpret_cast<const float2 *>(bt.codebook);
+    for (int i = threadIdx.x; i < bt.K; i += GV_THREADS) cb_lds[i] = cbk[i];
     __syncthreads();
     const int unit = __builtin_amdgcn_readfirstlane(blockIdx.x * GV_WAVES + wid);
-    if (unit >= n_units) return;
-    const int slab = __builtin_amdgcn_readfirstlane(unit % n_slabs);
-    const int row0 = __builtin_amdgcn_readfirstlane((unit / n_slabs) * GV_UNIT_ROWS);
-    const int last_row = d_out - 1;
+    if (unit >= bt.unit_begin[bt.n]) return;
+    const int mi = gv_find(bt.unit_begin, bt.n, unit);
+    const GemvMat &M = bt.mat[mi];
+    const int local = unit - bt.unit_begin[mi];
+    const int n_slabs = M.n_slabs, m = bt.m;
+    const int slab = __builtin_amdgcn_readfirstlane(local % n_slabs);
+    const int row0 = __builtin_amdgcn_readfirstlane((local / n_slabs) * GV_UNIT_ROWS);
+    const int d_out = M.d_out, d_in = M.d_in, last_row = M.d_out - 1;
+    const int64_t row_bytes = M.row_bytes;
+    const uint8_t *packed = M.packed;
+    const float *Z = M.Z;
+    float *partial = M.partial;
 
     const int col0 = slab * GV_SLAB + 16 * lane;               // no transform here: lanes in natural column order
     const bool active = col0 < d_in;
@@ -193,14 +232,17 @@ __global__ __launch_bounds__(GV_THREADS) void k_qgemv(const uint8_t *__restrict_
 }
 
 // Y[t][i] = r_i * sum over slabs of partial[slab][t][i], slabs in ascending order
-__global__ __launch_bounds__(256) void k_gemv_finish(const float *__restrict__ partial, int n_slabs, int m, int d_out,
-                                                     const float *__restrict__ norms, float *__restrict__ Y, int64_t ldy) {
-    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (g >= (int64_t)m * d_out) return;
-    const int t = (int)(g / d_out), i = (int)(g - (int64_t)t * d_out);
+__global__ __launch_bounds__(256) void k_gemv_finish(GemvBatch bt) {
+    const int g = blockIdx.x * 256 + threadIdx.x;
+    if (g >= bt.out_begin[bt.n]) return;
+    const int mi = gv_find(bt.out_begin, bt.n, g);
+    const GemvMat &M = bt.mat[mi];
+    const int local = g - bt.out_begin[mi];
+    const int d_out = M.d_out, m = bt.m;
+    const int t = local / d_out, i = local - t * d_out;
     float s = 0.0f;
-    for (int sl = 0; sl < n_slabs; ++sl) s += partial[((int64_t)sl * m + t) * d_out + i];
-    Y[(int64_t)t * ldy + i] = norms[i] * s;
+    for (int sl = 0; sl < M.n_slabs; ++sl) s += M.partial[((int64_t)sl * m + t) * d_out + i];
+    M.Y[(int64_t)t * M.ldy + i] = M.norms[i] * s;
 }
 
 bool matmul_supported(const Problem &p, int m) {
@@ -212,15 +254,16 @@ bool matmul_supported(const Problem &p, int m) {
 
 size_t matmul_workspace_bytes(int d_in, int d_out, int m) {
     const size_t n_slabs = (size_t)(d_in + GV_SLAB - 1) / GV_SLAB;
-    return ((size_t)m * d_in + n_slabs * (size_t)m * d_out) * sizeof(float);
+    const size_t bytes = ((size_t)m * d_in + n_slabs * (size_t)m * d_out) * sizeof(float);
+    return (bytes + 15) / 16 * 16;
 }
 
 template <int XDTYPE>
-static hipError_t launch_rotate(const void *X, int64_t ldx, int m, const Problem &p, float *Z, int n_slabs) {
-    const unsigned blocks = (unsigned)((m * n_slabs + GV_WAVES - 1) / GV_WAVES);
+static hipError_t launch_rotate(const GemvBatch &bt, int block, hipStream_t stream) {
+    const unsigned blocks = (unsigned)((bt.rot_begin[bt.n] + GV_WAVES - 1) / GV_WAVES);
 #define QAMW_ROT(BB) \
-    case BB: hipLaunchKernelGGL((k_rotate_x<XDTYPE, BB>), dim3(blocks), dim3(GV_THREADS), 0, p.stream, X, ldx, m, p, Z, n_slabs); break;
-    switch (p.block) {
+    case BB: hipLaunchKernelGGL((k_rotate_x<XDTYPE, BB>), dim3(blocks), dim3(GV_THREADS), 0, stream, bt); break;
+    switch (block) {
         QAMW_ROT(64) QAMW_ROT(128) QAMW_ROT(256) QAMW_ROT(512) QAMW_ROT(1024)
         default: return hipErrorNotSupported;
     }
@@ -229,39 +272,74 @@ static hipError_t launch_rotate(const void *X, int64_t ldx, int m, const Problem
 }
 
 template <int BITS>
-static hipError_t launch_qgemv(const uint8_t *packed, const Problem &p, const float *Z, int m, float *partial, int n_slabs) {
-    const int64_t n_units = (int64_t)n_slabs * ((p.d_out + GV_UNIT_ROWS - 1) / GV_UNIT_ROWS);
-    if (n_units > 0x3fffffff) return hipErrorNotSupported;
-    const unsigned blocks = (unsigned)((n_units + GV_WAVES - 1) / GV_WAVES);
-    const size_t lds = (size_t)p.K * sizeof(float2);
-#define QAMW_GV(MM) \
-    hipLaunchKernelGGL((k_qgemv<BITS, MM>), dim3(blocks), dim3(GV_THREADS), lds, p.stream, packed, p.row_bytes, p.d_out, p.d_in, \
-                       Z, m, p.codebook, p.K, partial, n_slabs, (int)n_units)
-    if (m == 1) QAMW_GV(1);
-    else if (m == 2) QAMW_GV(2);
-    else if (m <= 4) QAMW_GV(4);
+static hipError_t launch_qgemv(const GemvBatch &bt, hipStream_t stream) {
+    const unsigned blocks = (unsigned)((bt.unit_begin[bt.n] + GV_WAVES - 1) / GV_WAVES);
+    const size_t lds = (size_t)bt.K * sizeof(float2);
+#define QAMW_GV(MM) hipLaunchKernelGGL((k_qgemv<BITS, MM>), dim3(blocks), dim3(GV_THREADS), lds, stream, bt)
+    if (bt.m == 1) QAMW_GV(1);
+    else if (bt.m == 2) QAMW_GV(2);
+    else if (bt.m <= 4) QAMW_GV(4);
     else QAMW_GV(8);
 #undef QAMW_GV
     return hipGetLastError();
 }
 
-// Y = X W^T for m <= 8 activation rows.  workspace: matmul_workspace_bytes(), 16-byte aligned.
+// Y_i = X_i W_i^T for n <= QAMW_MATMUL_MAX_BATCH matrices that share codebook, bits, block, m and the element type
+// of X.  workspace: the sum of matmul_workspace_bytes() over the items, 16-byte aligned.
 // Returns hipErrorNotSupported (nothing launched) outside the supported shapes.
-hipError_t launch_matmul(const void *X, int xdtype, int m, int64_t ldx, const uint8_t *packed, const float *norms,
-                         const Problem &p, void *workspace, float *Y, int64_t ldy) {
-    if (!matmul_supported(p, m)) return hipErrorNotSupported;
-    const int n_slabs = (p.d_in + GV_SLAB - 1) / GV_SLAB;
-    float *Z = static_cast<float *>(workspace);
-    float *partial = Z + (size_t)m * p.d_in;
-    hipError_t e = xdtype == 0 ? launch_rotate<0>(X, ldx, m, p, Z, n_slabs) : launch_rotate<1>(X, ldx, m, p, Z, n_slabs);
+hipError_t launch_matmul_batch(const MatmulItem *items, int n, int xdtype, int m, const Problem &p, void *workspace) {
+    if (n < 1 || n > QAMW_MATMUL_MAX_BATCH) return hipErrorNotSupported;
+    GemvBatch bt;
+    int64_t rot = 0, units = 0, outs = 0;
+    char *ws = static_cast<char *>(workspace);
+    for (int i = 0; i < n; ++i) {
+        Problem q = p;
+        q.d_in = items[i].d_in;
+        q.d_out = items[i].d_out;
+        if (!matmul_supported(q, m) || (reinterpret_cast<uintptr_t>(items[i].packed) & 3)) return hipErrorNotSupported;
+        GemvMat &M = bt.mat[i];
+        M.X = items[i].X;
+        M.packed = items[i].packed;
+        M.norms = items[i].norms;
+        M.chan_scale = items[i].chan_scale;
+        M.pair_sigma = items[i].pair_sigma;
+        M.signs = items[i].signs;
+        M.Y = items[i].Y;
+        M.ldx = items[i].ldx;
+        M.ldy = items[i].ldy;
+        M.d_out = items[i].d_out;
+        M.d_in = items[i].d_in;
+        M.n_slabs = (M.d_in + GV_SLAB - 1) / GV_SLAB;
+        M.row_bytes = (((int64_t)(M.d_in / 2) * p.bits + 31) / 32) * 4;
+        M.Z = reinterpret_cast<float *>(ws);
+        M.partial = M.Z + (size_t)m * M.d_in;
+        ws += matmul_workspace_bytes(M.d_in, M.d_out, m);
+        bt.rot_begin[i] = (int)rot;
+        bt.unit_begin[i] = (int)units;
+        bt.out_begin[i] = (int)outs;
+        rot += (int64_t)m * M.n_slabs;
+        units += (int64_t)M.n_slabs * ((M.d_out + GV_UNIT_ROWS - 1) / GV_UNIT_ROWS);
+        outs += (int64_t)m * M.d_out;
+        if (units > 0x3fffffff || outs > 0x3fffffff) return hipErrorNotSupported;
+    }
+    for (int i = n; i <= QAMW_MATMUL_MAX_BATCH; ++i) {
+        bt.rot_begin[i] = (int)rot;
+        bt.unit_begin[i] = (int)units;
+        bt.out_begin[i] = (int)outs;
+    }
+    for (int i = n; i < QAMW_MATMUL_MAX_BATCH; ++i) bt.mat[i] = bt.mat[0];
+    bt.n = n;
+    bt.m = m;
+    bt.K = p.K;
+    bt.inv_sqrt_block = p.inv_sqrt_block;
+    bt.codebook = p.codebook;
+    hipError_t e = xdtype == 0 ? launch_rotate<0>(bt, p.block, p.stream) : launch_rotate<1>(bt, p.block, p.stream);
     if (e != hipSuccess) return e;
-    if (p.bits == 11) e = launch_qgemv<11>(packed, p, Z, m, partial, n_slabs);
-    else if (p.bits == 8) e = launch_qgemv<8>(packed, p, Z, m, partial, n_slabs);
-    else e = launch_qgemv<7>(packed, p, Z, m, partial, n_slabs);
+    if (p.bits == 11) e = launch_qgemv<11>(bt, p.stream);
+    else if (p.bits == 8) e = launch_qgemv<8>(bt, p.stream);
+    else e = launch_qgemv<7>(bt, p.stream);
     if (e != hipSuccess) return e;
-    const int64_t total = (int64_t)m * p.d_out;
-    hipLaunchKernelGGL(k_gemv_finish, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, p.stream, partial, n_slabs, m,
-                       p.d_out, norms, Y, ldy);
+    hipLaunchKernelGGL(k_gemv_finish, dim3((unsigned)((outs + 255) / 256)), dim3(256), 0, p.stream, bt);
     return hipGetLastError();
 }
 

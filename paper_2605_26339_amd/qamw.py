@@ -20,11 +20,18 @@ EXPORTS = [
     "qamw_status_string", "qamw_packed_row_bytes", "qamw_paper_block_size", "qamw_bpw", "qamw_sign_mask",
     "qamw_channel_scales", "qamw_train_codebook", "qamw_calibrate_workspace_bytes", "qamw_calibrate_sigma", "qamw_encode", "qamw_decode",
     "qamw_decode_f32", "qamw_decode_batch", "qamw_set_kernel_path", "qamw_polar_codebook", "qamw_encode_polar",
-    "qamw_matmul_workspace_bytes", "qamw_matmul",
+    "qamw_matmul_workspace_bytes", "qamw_matmul", "qamw_matmul_batch",
 ]
 
 
 MAX_BATCH = 16
+
+
+class MatmulItem(C.Structure):
+    """qamw_matmul_item of include/qamw.h."""
+    _fields_ = [("X", C.c_void_p), ("ldx", C.c_int64), ("packed", C.c_void_p), ("row_norms", C.c_void_p),
+                ("chan_scale", C.c_void_p), ("signs", C.c_void_p), ("pair_sigma", C.c_void_p), ("Y", C.c_void_p),
+                ("ldy", C.c_int64), ("d_out", C.c_int32), ("d_in", C.c_int32)]
 
 
 class DecodeItem(C.Structure):
@@ -72,6 +79,7 @@ def lib() -> C.CDLL:
         L.qamw_set_kernel_path.argtypes = [i32]
         L.qamw_matmul_workspace_bytes.argtypes = [i32, i32, i32, C.POINTER(C.c_size_t)]
         L.qamw_matmul.argtypes = [vp, i32, i32, i64, vp, vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, C.c_size_t, vp, i64, vp]
+        L.qamw_matmul_batch.argtypes = [C.POINTER(MatmulItem), i32, i32, i32, vp, i32, i32, vp, C.c_size_t, vp]
         L.qamw_polar_codebook.argtypes = [i32, i32, vp, vp, C.POINTER(C.c_double)]
         L.qamw_encode_polar.argtypes = [vp, i32, i32, i32, i64, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp]
         for name in EXPORTS:
@@ -286,6 +294,33 @@ def matmul(X, packed, row_norms, codebook, bits: int, block: int, chan_scale=Non
                              _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(out), out.stride(0),
                              _stream(stream)), "qamw_matmul")
     return out
+
+
+def make_matmul_items(entries):
+    """Host descriptor array for matmul_batch: each entry = (X, packed, row_norms, chan_scale, signs, pair_sigma, Y).
+    Returns (array, keepalive, m, x dtype code, workspace bytes)."""
+    arr = (MatmulItem * len(entries))()
+    need, m, code = 0, None, None
+    for i, (X, packed, norms, s, sg, sigma, Y) in enumerate(entries):
+        _require_cuda(X, packed, norms, s, sg, sigma, Y)
+        if X.dim() != 2 or X.stride(1) != 1 or Y.stride(1) != 1:
+            raise ValueError("X and Y must be 2-D with unit column stride")
+        if m is None:
+            m, code = X.shape[0], _dtype_code(X)
+        if X.shape[0] != m or _dtype_code(X) != code:
+            raise ValueError("all items of a batch share the number of rows and the element type of X")
+        d_in, d_out = X.shape[1], norms.shape[0]
+        arr[i] = MatmulItem(X.data_ptr(), X.stride(0), packed.data_ptr(), norms.data_ptr(), None if s is None else s.data_ptr(),
+                            None if sg is None else sg.data_ptr(), None if sigma is None else sigma.data_ptr(), Y.data_ptr(),
+                            Y.stride(0), d_out, d_in)
+        need += matmul_workspace_bytes(d_in, d_out, m)
+    return arr, list(entries), m, code, need
+
+
+def matmul_batch(items, codebook, bits: int, block: int, workspace, stream=None):
+    arr, _keep, m, code, need = items
+    _check(lib().qamw_matmul_batch(arr, len(arr), code, m, _ptr(codebook), bits, block, _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream(stream)), "qamw_matmul_batch")
 
 
 def make_decode_items(entries):

@@ -300,6 +300,29 @@ def test_fused_matmul_matches_oracle(orc, codebooks, seed, d_out, d_in, bits, bl
     assert np.array_equal(Y2.cpu().numpy(), Y) and bool((out2[:, d_out:] == -3.0).all())
 
 
+def test_fused_matmul_batch_equals_single_calls(orc, codebooks):
+    """Several independent products in one call give, bit for bit, what one call per matrix gives."""
+    say("[matmul batch]")
+    bits, block, m = 11, 128, 3
+    shapes = [(40, 2048), (17, 5632), (64, 1024), (33, 2048)]
+    entries, singles = [], []
+    for i, (d_out, d_in) in enumerate(shapes):
+        case = Case(orc, 100 + i, d_out, d_in, bits, block, codebook=codebooks[bits])
+        pk, nr = qamw.encode(case.W_dev, case.cb_dev, bits, block, chan_scale=case.s_dev, signs=case.sg_dev, pair_sigma=case.sigma_dev)
+        X = torch.randn((m, d_in), device="cuda", generator=torch.Generator("cuda").manual_seed(i)).to(torch.bfloat16)
+        Y = torch.full((m, d_out), -1.0, device="cuda")
+        entries.append((X, pk, nr, case.s_dev, case.sg_dev, case.sigma_dev, Y))
+        singles.append(qamw.matmul(X, pk, nr, case.cb_dev, bits, block, chan_scale=case.s_dev, signs=case.sg_dev,
+                                   pair_sigma=case.sigma_dev))
+        cb = case.cb_dev
+    items = qamw.make_matmul_items(entries)
+    ws = torch.empty(items[4], dtype=torch.uint8, device="cuda")
+    qamw.matmul_batch(items, cb, bits, block, ws)
+    torch.cuda.synchronize()
+    for e, ref in zip(entries, singles):
+        assert torch.equal(e[6], ref)
+
+
 def test_config0_full_matrix(orc, codebooks):
     """BASELINE config 0: 2048 x 2048 fp32, b = 128, K = 2048, every pair checked."""
     say("[config0] 2048x2048 B=11 b=128")
