@@ -208,7 +208,7 @@ int qamw_decode_batch(const qamw_decode_item *items, int n_items, const float *c
  * activation row; the matrix is read once, packed.
  * X: device, m rows of d_in elements (fp32 or bf16), leading dimension ldx.  Y: device, m rows of d_out
  * floats, leading dimension ldy.  workspace: device, at least qamw_matmul_workspace_bytes() bytes, 16-byte
- * aligned, owned by the caller (rotated activations and per-slab partial sums; contents unspecified afterwards).
+ * aligned, owned by the caller (the rotated activations; contents unspecified afterwards).
  * Accumulation is fp32 in a fixed order (deterministic).
  * Errors: m outside [1, QAMW_MATMUL_MAX_ROWS], NULL pointers, workspace too small or misaligned ->
  * INVALID_ARG; ldx < d_in, ldy < d_out -> SHAPE.  Shapes: bits in {7, 8, 11}, hadamard_block >= 64, d_in a

@@ -12,9 +12,13 @@
 // for a bf16 matrix.
 //
 // Kernels: k_rotate_x (one wave per activation row and 1024-column slab, the encoder's register
-// transform), k_qgemv (one wave per 16 rows x slab: packed words -> indices -> LDS codebook ->
-// multiply-add against the slab's z held in registers -> one wave reduction per row; partial sums
-// per slab go to the workspace), k_gemv_finish (sums the slabs in a fixed order, times r_i).
+// transform) and k_qgemv: a workgroup of 4 waves owns 16 rows of one matrix; wave w takes the
+// 1024-column slabs w, w+4, ...; per slab it holds the slab's z in registers, requests the packed
+// words of a group of rows at once, and per row unpacks 8 indices, gathers 8 codewords from the
+// LDS codebook and multiply-adds them into per-row, per-lane accumulators.  Nothing crosses lanes
+// until the wave has finished its slabs: then one transposing reduction (two half-swaps that halve
+// the number of live sums, a butterfly over the remaining 16 lanes), a sum over the 4 waves in
+// LDS in a fixed order, times r_i, and the store of 16 x m outputs.
 #include <type_traits>
 
 #include "qamw_common.hpp"
@@ -27,7 +31,6 @@ constexpr int GV_THREADS = 256;
 constexpr int GV_WAVES = GV_THREADS / WAVE;
 constexpr int GV_SLAB = 1024;
 constexpr int GV_UNIT_ROWS = 16;       // rows of one unit of work; lane r keeps the result of row r
-constexpr int GV_ROWS = 2;             // rows requested together
 constexpr int GV_MAX_M = 8;
 
 typedef uint32_t gv_u32x4_t __attribute__((ext_vector_type(4)));
@@ -38,17 +41,16 @@ struct GemvMat {
     const uint8_t *packed;
     const float *norms, *chan_scale, *pair_sigma;
     const int8_t *signs;
-    float *Z, *partial, *Y;
+    float *Z, *Y;
     int64_t ldx, ldy, row_bytes;
     int d_out, d_in, n_slabs;
 };
-// Work lists of one launch: rotation items (activation row, slab), product units (16 rows, slab) and output
-// elements, each numbered matrix-major.
+// Work lists of one launch: rotation items (activation row, slab) and row groups (16 rows), each numbered
+// matrix-major.
 struct GemvBatch {
     GemvMat mat[QAMW_MATMUL_MAX_BATCH];
     int rot_begin[QAMW_MATMUL_MAX_BATCH + 1];
-    int unit_begin[QAMW_MATMUL_MAX_BATCH + 1];
-    int out_begin[QAMW_MATMUL_MAX_BATCH + 1];
+    int grp_begin[QAMW_MATMUL_MAX_BATCH + 1];
     int n, m, K;
     float inv_sqrt_block;
     const float *codebook;
@@ -110,66 +112,72 @@ template <int BITS> __device__ __forceinline__ uint32_t gv_field(const uint32_t 
     return v & ((1u << BITS) - 1u);
 }
 
-// partial[(slab * MT + t) * d_out + i] = sum over the slab's pairs of <c[idx_ik], z_t,k>
-template <int BITS, int MT>
+// Sums over the 64 lanes of RG per-lane values a[0..RG): two half-swaps leave RG/4 values per lane (lane bits
+// 5 and 4 select which), a butterfly over lane bits 0-3 finishes them.  On return a[0 .. RG/4) hold the totals
+// of rows  (lane>>5) * RG/2 + ((lane>>4)&1) * RG/4 + j  (the same in all 16 lanes of a row of lanes).
+template <int RG> __device__ __forceinline__ void gv_reduce_rows(float (&a)[RG]) {
+    static_assert(RG == 4 || RG == 8 || RG == 16, "rows per reduction");
+#pragma unroll
+    for (int r = 0; r < RG / 2; ++r) {
+        auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(a[r]), __float_as_uint(a[r + RG / 2]), false, false);
+        a[r] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+    }
+#pragma unroll
+    for (int r = 0; r < RG / 4; ++r) {
+        auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(a[r]), __float_as_uint(a[r + RG / 4]), false, false);
+        a[r] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+    }
+#pragma unroll
+    for (int r = 0; r < RG / 4; ++r) {
+#pragma unroll
+        for (int s = 1; s < 16; s <<= 1) a[r] += __shfl_xor(a[r], s, WAVE);
+    }
+}
+
+// Y[t][row] = r_row * sum over the row's pairs of <c[idx], z_t>, 16 rows per workgroup
+template <int BITS, int MT, int RG>
 __global__ __launch_bounds__(GV_THREADS) void k_qgemv(GemvBatch bt) {
-    extern __shared__ float2 cb_lds[];
+    extern __shared__ __align__(16) float gv_lds[];
     typedef gv_u32x4_t u32x4_a4_t __attribute__((aligned(4)));
+    float2 *cb_lds = reinterpret_cast<float2 *>(gv_lds);        // K codewords
+    float *red = gv_lds + 2 * bt.K;                             // [waves][16 rows][MT]
     const int lane = threadIdx.x & (WAVE - 1);
     const int wid = threadIdx.x >> 6;
     const float2 *cbk = reinterpret_cast<const float2 *>(bt.codebook);
     for (int i = threadIdx.x; i < bt.K; i += GV_THREADS) cb_lds[i] = cbk[i];
     __syncthreads();
-    const int unit = __builtin_amdgcn_readfirstlane(blockIdx.x * GV_WAVES + wid);
-    if (unit >= bt.unit_begin[bt.n]) return;
-    const int mi = gv_find(bt.unit_begin, bt.n, unit);
+
+    const int grp = blockIdx.x;                                 // the grid is exactly the number of row groups
+    const int mi = gv_find(bt.grp_begin, bt.n, grp);
     const GemvMat &M = bt.mat[mi];
-    const int local = unit - bt.unit_begin[mi];
+    const int row0 = (grp - bt.grp_begin[mi]) * GV_UNIT_ROWS;
     const int n_slabs = M.n_slabs, m = bt.m;
-    const int slab = __builtin_amdgcn_readfirstlane(local % n_slabs);
-    const int row0 = __builtin_amdgcn_readfirstlane((local / n_slabs) * GV_UNIT_ROWS);
     const int d_out = M.d_out, d_in = M.d_in, last_row = M.d_out - 1;
     const int64_t row_bytes = M.row_bytes;
     const uint8_t *packed = M.packed;
     const float *Z = M.Z;
-    float *partial = M.partial;
-
-    const int col0 = slab * GV_SLAB + 16 * lane;               // no transform here: lanes in natural column order
-    const bool active = col0 < d_in;
-    const int c = active ? col0 : 0;
-    const unsigned lane_off = (unsigned)(c >> 4) * BITS;       // the lane's 8 fields: BITS bytes, same place in every row
-    const unsigned lane_b0 = lane_off & ~3u;
-    const int sh = (int)(lane_off & 3u) * 8;
     const unsigned row_dw = (unsigned)(row_bytes >> 2);
 
-    // the slab's rotated activations, zero for missing tokens and idle lanes
-    float z[MT][16];
+    for (int rg = 0; rg < GV_UNIT_ROWS / RG; ++rg) {
+        float a[MT][RG];                                        // per-lane sums of this group's rows
 #pragma unroll
-    for (int t = 0; t < MT; ++t) {
-        const bool have = active && t < m;
-        const float4 *src = reinterpret_cast<const float4 *>(Z + (int64_t)(t < m ? t : 0) * d_in + c);
+        for (int t = 0; t < MT; ++t)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const float4 v = src[q];
-            z[t][4 * q] = have ? v.x : 0.0f;
-            z[t][4 * q + 1] = have ? v.y : 0.0f;
-            z[t][4 * q + 2] = have ? v.z : 0.0f;
-            z[t][4 * q + 3] = have ? v.w : 0.0f;
-        }
-    }
-
-    float keep[MT];                                             // lane r: the sums of row row0 + r
+            for (int r = 0; r < RG; ++r) a[t][r] = 0.0f;
+        for (int slab = wid; slab < n_slabs; slab += GV_WAVES) {
+            const int col0 = slab * GV_SLAB + 16 * lane;       // no transform here: lanes in natural column order
+            const bool active = col0 < d_in;
+            const int c = active ? col0 : 0;
+            const unsigned lane_off = (unsigned)(c >> 4) * BITS;   // the lane's 8 fields: BITS bytes, same place in every row
+            const unsigned lane_b0 = lane_off & ~3u;
+            const int sh = (int)(lane_off & 3u) * 8;
+            // packed words of the group's rows, all requested before any is used
+            uint32_t d[RG][4];
 #pragma unroll
-    for (int t = 0; t < MT; ++t) keep[t] = 0.0f;
-
-    auto run = [&](auto full_tag) {
-        constexpr bool FULL = decltype(full_tag)::value;        // every row exists and none is the matrix's last row
-        auto fetch = [&](int sub, uint32_t (&d)[GV_ROWS][4]) {
-#pragma unroll
-            for (int r = 0; r < GV_ROWS; ++r) {
-                const int row = FULL ? row0 + sub + r : min(row0 + sub + r, last_row);
+            for (int r = 0; r < RG; ++r) {
+                const int row = min(row0 + rg * RG + r, last_row);  // rows past the end re-read the last row
                 const uint8_t *rowp = packed + (int64_t)row * row_bytes;
-                if (FULL || row != last_row) {
+                if (row != last_row) {
                     // 16 bytes from a 4-byte-aligned address; may run a few bytes into the next row
                     const gv_u32x4_t v = *reinterpret_cast<const u32x4_a4_t *>(rowp + lane_b0);
                     d[r][0] = v[0]; d[r][1] = v[1]; d[r][2] = v[2]; d[r][3] = v[3];
@@ -180,69 +188,60 @@ __global__ __launch_bounds__(GV_THREADS) void k_qgemv(GemvBatch bt) {
                     for (int k = 0; k < 4; ++k) d[r][k] = rw[min((lane_b0 >> 2) + k, row_dw - 1u)];
                 }
             }
-        };
-        auto rows = [&](int sub, const uint32_t (&d)[GV_ROWS][4]) {
+            // the slab's rotated activations, zero for missing tokens and idle lanes
+            float z[MT][16];
 #pragma unroll
-            for (int r = 0; r < GV_ROWS; ++r) {
+            for (int t = 0; t < MT; ++t) {
+                const bool have = active && t < m;
+                const float4 *src = reinterpret_cast<const float4 *>(Z + (int64_t)(t < m ? t : 0) * d_in + c);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 v = src[q];
+                    z[t][4 * q] = have ? v.x : 0.0f;
+                    z[t][4 * q + 1] = have ? v.y : 0.0f;
+                    z[t][4 * q + 2] = have ? v.z : 0.0f;
+                    z[t][4 * q + 3] = have ? v.w : 0.0f;
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < RG; ++r) {
                 uint32_t w[4];
                 w[0] = __builtin_amdgcn_alignbit(d[r][1], d[r][0], sh);
                 w[1] = __builtin_amdgcn_alignbit(d[r][2], d[r][1], sh);
                 w[2] = __builtin_amdgcn_alignbit(d[r][3], d[r][2], sh);
                 w[3] = d[r][3] >> sh;
-                float acc[MT];
-#pragma unroll
-                for (int t = 0; t < MT; ++t) acc[t] = 0.0f;
 #pragma unroll
                 for (int k = 0; k < 8; ++k) {
                     const float2 cw = cb_lds[gv_field<BITS>(w, k)];
 #pragma unroll
-                    for (int t = 0; t < MT; ++t) acc[t] = __builtin_fmaf(cw.y, z[t][2 * k + 1], __builtin_fmaf(cw.x, z[t][2 * k], acc[t]));
-                }
-#pragma unroll
-                for (int t = 0; t < MT; ++t) {
-                    float v = acc[t];
-#pragma unroll
-                    for (int s = 1; s < WAVE; s <<= 1) v += __shfl_xor(v, s, WAVE);     // every lane ends with the row's sum
-                    keep[t] = (lane == sub + r) ? v : keep[t];
+                    for (int t = 0; t < MT; ++t)
+                        a[t][r] = __builtin_fmaf(cw.y, z[t][2 * k + 1], __builtin_fmaf(cw.x, z[t][2 * k], a[t][r]));
                 }
             }
-        };
-        uint32_t d0[GV_ROWS][4], d1[GV_ROWS][4];
-        fetch(0, d0);
-        for (int sub = 0; sub < GV_UNIT_ROWS; sub += 2 * GV_ROWS) {
-            if (!FULL && row0 + sub > last_row) break;
-            if (FULL || row0 + sub + GV_ROWS <= last_row) fetch(sub + GV_ROWS, d1);
-            rows(sub, d0);
-            if (!FULL && row0 + sub + GV_ROWS > last_row) break;
-            if (sub + 2 * GV_ROWS < GV_UNIT_ROWS && (FULL || row0 + sub + 2 * GV_ROWS <= last_row)) fetch(sub + 2 * GV_ROWS, d0);
-            rows(sub + GV_ROWS, d1);
         }
-    };
-    static_assert(GV_UNIT_ROWS % (2 * GV_ROWS) == 0 && GV_UNIT_ROWS <= WAVE, "row loop shape");
-    if (row0 + GV_UNIT_ROWS <= last_row)
-        run(std::true_type{});
-    else
-        run(std::false_type{});
-
-    if (lane < GV_UNIT_ROWS && row0 + lane <= last_row) {
+        // totals over the lanes; one lane of each 16-lane row stores its RG/4 rows
+        const int first = rg * RG + (lane >> 5) * (RG / 2) + ((lane >> 4) & 1) * (RG / 4);
 #pragma unroll
-        for (int t = 0; t < MT; ++t)
-            if (t < m) partial[((int64_t)slab * m + t) * d_out + row0 + lane] = keep[t];
+        for (int t = 0; t < MT; ++t) {
+            gv_reduce_rows<RG>(a[t]);
+            if ((lane & 15) == 0) {
+#pragma unroll
+                for (int j = 0; j < RG / 4; ++j) red[(wid * GV_UNIT_ROWS + first + j) * MT + t] = a[t][j];
+            }
+        }
     }
-}
-
-// Y[t][i] = r_i * sum over slabs of partial[slab][t][i], slabs in ascending order
-__global__ __launch_bounds__(256) void k_gemv_finish(GemvBatch bt) {
-    const int g = blockIdx.x * 256 + threadIdx.x;
-    if (g >= bt.out_begin[bt.n]) return;
-    const int mi = gv_find(bt.out_begin, bt.n, g);
-    const GemvMat &M = bt.mat[mi];
-    const int local = g - bt.out_begin[mi];
-    const int d_out = M.d_out, m = bt.m;
-    const int t = local / d_out, i = local - t * d_out;
-    float s = 0.0f;
-    for (int sl = 0; sl < M.n_slabs; ++sl) s += M.partial[((int64_t)sl * m + t) * d_out + i];
-    M.Y[(int64_t)t * M.ldy + i] = M.norms[i] * s;
+    __syncthreads();
+    // the 4 waves' sums in wave order, times the row norm
+    const int o = threadIdx.x;
+    if (o < GV_UNIT_ROWS * MT) {
+        const int row = o / MT, t = o - row * MT;
+        if (t < m && row0 + row <= last_row) {
+            float s = 0.0f;
+#pragma unroll
+            for (int w = 0; w < GV_WAVES; ++w) s += red[(w * GV_UNIT_ROWS + row) * MT + t];
+            M.Y[(int64_t)t * M.ldy + row0 + row] = M.norms[row0 + row] * s;
+        }
+    }
 }
 
 bool matmul_supported(const Problem &p, int m) {
@@ -253,8 +252,8 @@ bool matmul_supported(const Problem &p, int m) {
 }
 
 size_t matmul_workspace_bytes(int d_in, int d_out, int m) {
-    const size_t n_slabs = (size_t)(d_in + GV_SLAB - 1) / GV_SLAB;
-    const size_t bytes = ((size_t)m * d_in + n_slabs * (size_t)m * d_out) * sizeof(float);
+    (void)d_out;
+    const size_t bytes = (size_t)m * d_in * sizeof(float);     // the rotated activations
     return (bytes + 15) / 16 * 16;
 }
 
@@ -273,13 +272,14 @@ static hipError_t launch_rotate(const GemvBatch &bt, int block, hipStream_t stre
 
 template <int BITS>
 static hipError_t launch_qgemv(const GemvBatch &bt, hipStream_t stream) {
-    const unsigned blocks = (unsigned)((bt.unit_begin[bt.n] + GV_WAVES - 1) / GV_WAVES);
-    const size_t lds = (size_t)bt.K * sizeof(float2);
-#define QAMW_GV(MM) hipLaunchKernelGGL((k_qgemv<BITS, MM>), dim3(blocks), dim3(GV_THREADS), lds, stream, bt)
-    if (bt.m == 1) QAMW_GV(1);
-    else if (bt.m == 2) QAMW_GV(2);
-    else if (bt.m <= 4) QAMW_GV(4);
-    else QAMW_GV(8);
+    const unsigned blocks = (unsigned)bt.grp_begin[bt.n];
+#define QAMW_GV(MM, RR)                                                                                              \
+    hipLaunchKernelGGL((k_qgemv<BITS, MM, RR>), dim3(blocks), dim3(GV_THREADS),                                        \
+                       ((size_t)bt.K * 2 + (size_t)GV_WAVES * GV_UNIT_ROWS * MM) * sizeof(float), stream, bt)
+    if (bt.m == 1) QAMW_GV(1, 8);
+    else if (bt.m == 2) QAMW_GV(2, 8);
+    else if (bt.m <= 4) QAMW_GV(4, 8);
+    else QAMW_GV(8, 4);
 #undef QAMW_GV
     return hipGetLastError();
 }
@@ -290,7 +290,7 @@ static hipError_t launch_qgemv(const GemvBatch &bt, hipStream_t stream) {
 hipError_t launch_matmul_batch(const MatmulItem *items, int n, int xdtype, int m, const Problem &p, void *workspace) {
     if (n < 1 || n > QAMW_MATMUL_MAX_BATCH) return hipErrorNotSupported;
     GemvBatch bt;
-    int64_t rot = 0, units = 0, outs = 0;
+    int64_t rot = 0, groups = 0;
     char *ws = static_cast<char *>(workspace);
     for (int i = 0; i < n; ++i) {
         Problem q = p;
@@ -312,20 +312,16 @@ hipError_t launch_matmul_batch(const MatmulItem *items, int n, int xdtype, int m
         M.n_slabs = (M.d_in + GV_SLAB - 1) / GV_SLAB;
         M.row_bytes = (((int64_t)(M.d_in / 2) * p.bits + 31) / 32) * 4;
         M.Z = reinterpret_cast<float *>(ws);
-        M.partial = M.Z + (size_t)m * M.d_in;
         ws += matmul_workspace_bytes(M.d_in, M.d_out, m);
         bt.rot_begin[i] = (int)rot;
-        bt.unit_begin[i] = (int)units;
-        bt.out_begin[i] = (int)outs;
+        bt.grp_begin[i] = (int)groups;
         rot += (int64_t)m * M.n_slabs;
-        units += (int64_t)M.n_slabs * ((M.d_out + GV_UNIT_ROWS - 1) / GV_UNIT_ROWS);
-        outs += (int64_t)m * M.d_out;
-        if (units > 0x3fffffff || outs > 0x3fffffff) return hipErrorNotSupported;
+        groups += (M.d_out + GV_UNIT_ROWS - 1) / GV_UNIT_ROWS;
+        if (groups > 0x3fffffff || rot > 0x3fffffff) return hipErrorNotSupported;
     }
     for (int i = n; i <= QAMW_MATMUL_MAX_BATCH; ++i) {
         bt.rot_begin[i] = (int)rot;
-        bt.unit_begin[i] = (int)units;
-        bt.out_begin[i] = (int)outs;
+        bt.grp_begin[i] = (int)groups;
     }
     for (int i = n; i < QAMW_MATMUL_MAX_BATCH; ++i) bt.mat[i] = bt.mat[0];
     bt.n = n;
@@ -338,9 +334,7 @@ hipError_t launch_matmul_batch(const MatmulItem *items, int n, int xdtype, int m
     if (p.bits == 11) e = launch_qgemv<11>(bt, p.stream);
     else if (p.bits == 8) e = launch_qgemv<8>(bt, p.stream);
     else e = launch_qgemv<7>(bt, p.stream);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_gemv_finish, dim3((unsigned)((outs + 255) / 256)), dim3(256), 0, p.stream, bt);
-    return hipGetLastError();
+    return e;
 }
 
 }  // namespace qamw
