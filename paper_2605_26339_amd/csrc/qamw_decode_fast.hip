@@ -7,6 +7,7 @@
 // across the wave (qamw_wave_fwht.hpp), applies row and column factors and stores 16 bf16.
 // Column constants (1/s_j with the sign mask and the transform's lane sign folded in, sigma_k)
 // are loaded once per slab and reused for every row.
+#include <cmath>
 #include <type_traits>
 
 #include "qamw_common.hpp"
@@ -100,7 +101,8 @@ struct DecodeMat {
     void *out;
     int64_t ldo;
     int64_t row_bytes;
-    int d_out, d_in, n_slabs, n_groups;
+    int d_out, d_in, n_slabs;
+    float sigma_default;                  // 1/sqrt(d_in), used when pair_sigma is NULL
 };
 
 // Work list of one launch.  A unit is (matrix, group of DF_UNIT_ROWS rows, slab), numbered matrix-major,
@@ -110,7 +112,7 @@ struct DecodeBatch {
     int unit_begin[DF_MAX_BATCH + 1];     // first unit of each matrix; unit_begin[n] = total
     int n;
     int K;
-    float inv_sqrt_block, sigma_default;
+    float inv_sqrt_block;
     const float *codebook;
 };
 
@@ -169,7 +171,7 @@ __global__ __launch_bounds__(DF_THREADS) void k_decode_fast(DecodeBatch bt, int 
         pc.chan_scale = M.chan_scale;
         pc.signs = M.signs;
         pc.pair_sigma = M.pair_sigma;
-        pc.sigma_default = bt.sigma_default;
+        pc.sigma_default = M.sigma_default;
         load_column_constants(qs, sig, pc, c, ls.parity);
     }
 
@@ -286,13 +288,10 @@ static bool decode_alignment_ok(const DecodeItem &it, bool out_bf16) {
     return (reinterpret_cast<uintptr_t>(it.packed) & 3) == 0;
 }
 
-static int gcd_int(int a, int b) { return b ? gcd_int(b, a % b) : a; }
-
 template <int BITS, int B>
 static hipError_t launch_bb(const DecodeItem *items, int n, const Problem &p, bool out_bf16) {
     DecodeBatch bt;
     int64_t units = 0;
-    int64_t lcm = 1;
     for (int i = 0; i < n; ++i) {
         DecodeMat &M = bt.m[i];
         M.packed = items[i].packed;
@@ -306,22 +305,19 @@ static hipError_t launch_bb(const DecodeItem *items, int n, const Problem &p, bo
         M.d_in = items[i].d_in;
         M.row_bytes = (((int64_t)(M.d_in / 2) * BITS + 31) / 32) * 4;
         M.n_slabs = (M.d_in + SLAB - 1) / SLAB;
-        M.n_groups = (M.d_out + DF_UNIT_ROWS - 1) / DF_UNIT_ROWS;
+        M.sigma_default = (float)(1.0 / std::sqrt((double)M.d_in));
         bt.unit_begin[i] = (int)units;
-        units += (int64_t)M.n_slabs * M.n_groups;
+        units += (int64_t)M.n_slabs * ((M.d_out + DF_UNIT_ROWS - 1) / DF_UNIT_ROWS);
         if (units > 0x3fffffff) return hipErrorNotSupported;
-        lcm = lcm / gcd_int((int)lcm, M.n_slabs) * M.n_slabs;
     }
     for (int i = n; i <= DF_MAX_BATCH; ++i) bt.unit_begin[i] = (int)units;
     for (int i = n; i < DF_MAX_BATCH; ++i) bt.m[i] = bt.m[0];
     bt.n = n;
     bt.K = p.K;
     bt.inv_sqrt_block = p.inv_sqrt_block;
-    bt.sigma_default = p.sigma_default;
     bt.codebook = p.codebook;
     // One unit per wave, blocks dispatched in unit (= memory) order.  (A machine-sized persistent grid with a
     // stride was measured slower on HBM-bound sizes: its waves move in lockstep through read and write phases.)
-    (void)lcm;
     const int64_t n_waves = units;
     const unsigned blocks = (unsigned)((n_waves + DF_WAVES - 1) / DF_WAVES);
     const size_t lds = (size_t)p.K * sizeof(float2);

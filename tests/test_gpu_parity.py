@@ -357,13 +357,15 @@ def test_config0_full_matrix(orc, codebooks):
     assert 0.02 < rel < 0.05
 
 
-def test_decode_batch_equals_single_calls(orc, codebooks, kernel_path):
+@pytest.mark.parametrize("sigma", ["calibrated", None])
+def test_decode_batch_equals_single_calls(orc, codebooks, kernel_path, sigma):
     """One launch for several matrices of different shapes (ragged slabs, odd row counts) gives exactly
-    what the per-matrix entry point gives, and both match the oracle."""
-    say(f"[batch] path={kernel_path}")
+    what the per-matrix entry point gives, and both match the oracle.  Without pair scales every matrix
+    falls back to its own 1/sqrt(d_in)."""
+    say(f"[batch] path={kernel_path} sigma={sigma}")
     bits, block = 11, 128
     shapes = [(71, 33, 4096), (72, 18, 11008), (73, 7, 1152), (74, 41, 5632), (75, 1, 128), (76, 9, 13824), (77, 5, 2048)]
-    cases = [Case(orc, sd, do, di, bits, block, dtype="bf16", codebook=codebooks[bits]) for sd, do, di in shapes]
+    cases = [Case(orc, sd, do, di, bits, block, dtype="bf16", codebook=codebooks[bits], sigma=sigma) for sd, do, di in shapes]
     entries, singles, refs = [], [], []
     for cs in cases:
         ref = cs.oracle_encode(orc)
