@@ -19,7 +19,7 @@
 // until the wave has finished its slabs: then one transposing reduction (two half-swaps that halve
 // the number of live sums, a butterfly over the remaining 16 lanes), a sum over the 4 waves in
 // LDS in a fixed order, times r_i, and the store of 16 x m outputs.
-#include <type_traits>
+#include <cmath>
 
 #include "qamw_common.hpp"
 #include "qamw_internal.hpp"
@@ -44,6 +44,7 @@ struct GemvMat {
     float *Z, *Y;
     int64_t ldx, ldy, row_bytes;
     int d_out, d_in, n_slabs;
+    float sigma_default;                   // 1/sqrt(d_in), used when pair_sigma is NULL
 };
 // Work lists of one launch: rotation items (activation row, slab) and row groups (16 rows), each numbered
 // matrix-major.
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(GV_THREADS) void k_rotate_x(GemvBatch bt) {
         for (int e = 0; e < 16; ++e) y[e] = (signs[c + e] < 0) ? -y[e] : y[e];
     }
     fwht_wave<B>(y, ls);
-    const float sigma_default = 1.0f / sqrtf((float)d_in);
+    const float sigma_default = M.sigma_default;
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
         const float sg = pair_sigma ? pair_sigma[(c + e) >> 1] : sigma_default;
@@ -310,6 +311,7 @@ hipError_t launch_matmul_batch(const MatmulItem *items, int n, int xdtype, int m
         M.d_out = items[i].d_out;
         M.d_in = items[i].d_in;
         M.n_slabs = (M.d_in + GV_SLAB - 1) / GV_SLAB;
+        M.sigma_default = (float)(1.0 / std::sqrt((double)M.d_in));
         M.row_bytes = (((int64_t)(M.d_in / 2) * p.bits + 31) / 32) * 4;
         M.Z = reinterpret_cast<float *>(ws);
         ws += matmul_workspace_bytes(M.d_in, M.d_out, m);

@@ -262,6 +262,7 @@ MATMUL_CASES = [
     (94, 129, 1280, 8, 256, 2, "f32"),
     (95, 5, 4096, 7, 1024, 4, "f32"),
     (96, 48, 4096, 11, 128, 5, "bf16"),
+    (97, 21, 3072, 11, 256, 2, "plain"),       # no channel scale, no sign mask, default pair scale; fp32 X
 ]
 
 
@@ -270,7 +271,9 @@ def test_fused_matmul_matches_oracle(orc, codebooks, seed, d_out, d_in, bits, bl
     """Y = X W^T without materialising W, against the definition: the oracle's fp64 decode of the same
     indices times X in fp64.  Error bar per output: 1e-6 ||x|| ||w_i|| (fp32 accumulation of d_in terms; observed about 1e-8)."""
     say(f"[matmul] seed={seed} {d_out}x{d_in} B={bits} b={block} m={m} x={xdtype}")
-    case = Case(orc, seed, d_out, d_in, bits, block, codebook=codebooks[bits])
+    plain = xdtype == "plain"
+    case = Case(orc, seed, d_out, d_in, bits, block, codebook=codebooks[bits], scale=not plain, signs=not plain,
+                sigma=None if plain else "calibrated")
     ref = case.oracle_encode(orc)
     idx, norms = ref["idx"], ref["norms"].astype(np.float32)
     norms[min(3, d_out - 1)] = 0.0                               # a zero row gives exact zeros
