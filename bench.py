@@ -209,6 +209,13 @@ def main():
         e1.synchronize()
         pass_ms.append(e0.elapsed_time(e1))
 
+    # how often the encoder's shortlist could not decide and the whole codebook was scanned (first layer)
+    scans = torch.zeros(1, dtype=torch.int64, device=dev)
+    for m in mats[:per_layer]:
+        qamw.encode(m["W"], cb, wl.bits, wl.block, chan_scale=m["s"], signs=m["sg"], pair_sigma=m["sigma"],
+                    out=(m["packed"], m["norms"]), full_scans=scans)
+    full_scan_fraction = float(scans.item()) / sum(m["d_out"] * m["d_in"] // 2 for m in mats[:per_layer])
+
     # fused dequantise-and-multiply: one pass = Y = X W^T for every matrix of the set (what generating
     # one token batch reads), next to the same products with the decoded bf16 matrices through torch
     fused = None
@@ -301,7 +308,8 @@ def main():
         "encode": {"gpairs_per_s_kernels_only": pairs / (enc_ms * 1e-3) / 1e9,
                    "gpairs_per_s_with_calibration": pairs / ((enc_ms + cal_ms) * 1e-3) / 1e9,
                    "ms_per_step": enc_ms / args.steps, "calibration_ms_per_step": cal_ms / args.steps,
-                   "hbm_gb_per_s": enc_in_bytes / (enc_ms * 1e-3) / 1e9},
+                   "hbm_gb_per_s": enc_in_bytes / (enc_ms * 1e-3) / 1e9,
+                   "full_scan_fraction": full_scan_fraction},
         "decode": {"value": dec_gbs, "unit": "GB/s", "ms_per_step": dec_ms / args.steps,
                    "gpairs_per_s": pairs / (dec_ms * 1e-3) / 1e9,
                    "whole_set_passes": len(pass_ms),

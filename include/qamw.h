@@ -138,6 +138,17 @@ int qamw_encode(const void *W, int dtype, int d_out, int d_in, int64_t ldw, cons
                 const int8_t *signs, const float *pair_sigma, const float *codebook, int bits,
                 int hadamard_block, uint8_t *packed_out, float *row_norms_out, void *stream);
 
+/* qamw_encode that also counts how the indices were decided.  The fast encoders shortlist with approximate
+ * scores and decide every index by exact fp32 squared distances, inside the best chunk of codewords when the
+ * shortlist separates it provably from the rest, otherwise by an exact scan of the whole codebook.
+ * full_scans: device, one 64-bit counter; the number of pairs that took the whole-codebook scan is ADDED to
+ * it (the caller zeroes it); the general kernels, which scan everything for every pair, do not count.
+ * The packed output is identical to qamw_encode's. */
+int qamw_encode_stats(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
+                      const int8_t *signs, const float *pair_sigma, const float *codebook, int bits,
+                      int hadamard_block, uint8_t *packed_out, float *row_norms_out,
+                      unsigned long long *full_scans, void *stream);
+
 /* Polar baseline of Sec. 3 ("Polar Baseline"; distortion: the polar pair theorem and the
  * Rayleigh-Lloyd corollary).
  *

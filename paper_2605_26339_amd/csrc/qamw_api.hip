@@ -103,15 +103,16 @@ int qamw_calibrate_sigma(const void *W, int dtype, int d_out, int d_in, int64_t 
     return e == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
 }
 
-int qamw_encode(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
-                const int8_t *signs, const float *pair_sigma, const float *codebook, int bits, int hadamard_block,
-                uint8_t *packed_out, float *row_norms_out, void *stream) {
+static int encode_impl(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
+                       const int8_t *signs, const float *pair_sigma, const float *codebook, int bits, int hadamard_block,
+                       uint8_t *packed_out, float *row_norms_out, unsigned long long *full_scans, void *stream) {
     if (!W || !codebook || !packed_out || !row_norms_out) return QAMW_ERR_INVALID_ARG;
     if (dtype != QAMW_DTYPE_F32 && dtype != QAMW_DTYPE_BF16) return QAMW_ERR_INVALID_ARG;
     int rc = check_common(d_out, d_in, bits, hadamard_block);
     if (rc != QAMW_OK) return rc;
     if (ldw < d_in) return QAMW_ERR_SHAPE;
     qamw::Problem p = make_problem(d_out, d_in, chan_scale, signs, pair_sigma, codebook, bits, hadamard_block, stream);
+    p.full_scans = full_scans;
     if (launch_norms(W, dtype, ldw, d_out, p, row_norms_out) != hipSuccess) return QAMW_ERR_DEVICE;
     const int path = g_kernel_path.load();
     hipError_t e = hipErrorNotSupported;                        // "not supported" = nothing launched yet
@@ -120,6 +121,21 @@ int qamw_encode(const void *W, int dtype, int d_out, int d_in, int64_t ldw, cons
         e = qamw::launch_encode_fast(W, dtype, ldw, p, row_norms_out, packed_out);
     if (e == hipErrorNotSupported) e = qamw::launch_encode_general(W, dtype, ldw, p, row_norms_out, packed_out);
     return e == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
+}
+
+int qamw_encode(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
+                const int8_t *signs, const float *pair_sigma, const float *codebook, int bits, int hadamard_block,
+                uint8_t *packed_out, float *row_norms_out, void *stream) {
+    return encode_impl(W, dtype, d_out, d_in, ldw, chan_scale, signs, pair_sigma, codebook, bits, hadamard_block, packed_out,
+                       row_norms_out, nullptr, stream);
+}
+
+int qamw_encode_stats(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
+                      const int8_t *signs, const float *pair_sigma, const float *codebook, int bits, int hadamard_block,
+                      uint8_t *packed_out, float *row_norms_out, unsigned long long *full_scans, void *stream) {
+    if (!full_scans) return QAMW_ERR_INVALID_ARG;
+    return encode_impl(W, dtype, d_out, d_in, ldw, chan_scale, signs, pair_sigma, codebook, bits, hadamard_block, packed_out,
+                       row_norms_out, full_scans, stream);
 }
 
 int qamw_encode_polar(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,

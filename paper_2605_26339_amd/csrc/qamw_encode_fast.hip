@@ -164,6 +164,7 @@ __global__ __launch_bounds__(EF_THREADS) void k_encode_fast(const void *__restri
 #pragma unroll
     for (int j = 0; j < NPT; ++j) {
         unsigned long long mask = __ballot((flagged >> j) & 1u);
+        if (p.full_scans && mask && lane == 0) atomicAdd(p.full_scans, (unsigned long long)__popcll(mask));
         while (mask) {
             const int src = __ffsll((long long)mask) - 1;
             mask &= mask - 1;

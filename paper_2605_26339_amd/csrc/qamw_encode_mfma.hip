@@ -223,6 +223,7 @@ __global__ __launch_bounds__(MF_THREADS) void k_encode_mfma(const void *__restri
         for (int pb = 0; pb < NPB; ++pb) {
             const int pbg = pass * NPB + pb;
             unsigned long long mask = __ballot((flagged >> pb) & 1u);
+            if (p.full_scans && mask && lane == 0) atomicAdd(p.full_scans, (unsigned long long)__popcll(mask));
             while (mask) {
                 const int src = __ffsll((long long)mask) - 1;      // a lane below 32: point src of block pbg
                 mask &= mask - 1;

@@ -18,6 +18,7 @@ struct Problem {
     float g_default = 0.f;               // fp32(sqrt(d_in)): pair gain when no sigma is given
     float sigma_default = 0.f;           // fp32(d_in^-1/2)
     int64_t row_bytes = 0;               // packed row stride
+    unsigned long long *full_scans = nullptr;   // device counter of pairs decided by the exact whole-codebook scan, nullable
     hipStream_t stream = nullptr;
 };
 

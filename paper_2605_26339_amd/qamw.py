@@ -20,7 +20,7 @@ EXPORTS = [
     "qamw_status_string", "qamw_packed_row_bytes", "qamw_paper_block_size", "qamw_bpw", "qamw_sign_mask",
     "qamw_channel_scales", "qamw_train_codebook", "qamw_calibrate_workspace_bytes", "qamw_calibrate_sigma", "qamw_encode", "qamw_decode",
     "qamw_decode_f32", "qamw_decode_batch", "qamw_set_kernel_path", "qamw_polar_codebook", "qamw_encode_polar",
-    "qamw_matmul_workspace_bytes", "qamw_matmul", "qamw_matmul_batch",
+    "qamw_matmul_workspace_bytes", "qamw_matmul", "qamw_matmul_batch", "qamw_encode_stats",
 ]
 
 
@@ -73,6 +73,7 @@ def lib() -> C.CDLL:
         L.qamw_calibrate_workspace_bytes.argtypes = [i32, i32, i32, C.POINTER(C.c_size_t)]
         L.qamw_calibrate_sigma.argtypes = [vp, i32, i32, i32, i64, vp, vp, i32, i32, vp, C.c_size_t, vp, vp]
         L.qamw_encode.argtypes = [vp, i32, i32, i32, i64, vp, vp, vp, vp, i32, i32, vp, vp, vp]
+        L.qamw_encode_stats.argtypes = [vp, i32, i32, i32, i64, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
         L.qamw_decode.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, i64, vp]
         L.qamw_decode_f32.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, i64, vp]
         L.qamw_decode_batch.argtypes = [C.POINTER(DecodeItem), i32, vp, i32, i32, vp]
@@ -207,9 +208,11 @@ def calibrate_sigma(W, block: int, chan_scale=None, signs=None, max_rows: int = 
     return out
 
 
-def encode(W, codebook, bits: int, block: int, chan_scale=None, signs=None, pair_sigma=None, out=None, stream=None):
+def encode(W, codebook, bits: int, block: int, chan_scale=None, signs=None, pair_sigma=None, out=None, stream=None,
+           full_scans=None):
     """Encode W (torch CUDA tensor, fp32 or bf16, row-major, stride(1) == 1).
-    Returns (packed uint8 [d_out][row_bytes], row_norms float32 [d_out])."""
+    Returns (packed uint8 [d_out][row_bytes], row_norms float32 [d_out]).  full_scans: optional int64 CUDA tensor of
+    one element to which the number of pairs decided by the whole-codebook scan is added."""
     import torch
 
     _require_cuda(W, codebook, chan_scale, signs, pair_sigma)
@@ -222,6 +225,12 @@ def encode(W, codebook, bits: int, block: int, chan_scale=None, signs=None, pair
         norms = torch.empty(d_out, dtype=torch.float32, device=W.device)
     else:
         packed, norms = out
+    if full_scans is not None:
+        _require_cuda(full_scans)
+        _check(lib().qamw_encode_stats(_ptr(W), _dtype_code(W), d_out, d_in, W.stride(0), _ptr(chan_scale), _ptr(signs),
+                                       _ptr(pair_sigma), _ptr(codebook), bits, block, _ptr(packed), _ptr(norms),
+                                       _ptr(full_scans), _stream(stream)), "qamw_encode_stats")
+        return packed, norms
     _check(lib().qamw_encode(_ptr(W), _dtype_code(W), d_out, d_in, W.stride(0), _ptr(chan_scale), _ptr(signs),
                              _ptr(pair_sigma), _ptr(codebook), bits, block, _ptr(packed), _ptr(norms),
                              _stream(stream)), "qamw_encode")

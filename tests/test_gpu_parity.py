@@ -165,6 +165,20 @@ def test_shortlist_stress(orc, codebooks, kernel_path, kind):
     ref = case.oracle_encode(orc)
     packed, norms = case.gpu_encode()
     got = orc.unpack(packed, d_in, bits)
+    # the counting entry point gives the same bytes; how many pairs needed the whole-codebook scan
+    scans = torch.zeros(1, dtype=torch.int64, device="cuda")
+    p2, _ = qamw.encode(case.W_dev, case.cb_dev, bits, block, chan_scale=case.s_dev, signs=case.sg_dev,
+                        pair_sigma=case.sigma_dev, full_scans=scans)
+    torch.cuda.synchronize()
+    assert np.array_equal(p2.cpu().numpy(), packed)
+    n_scans = int(scans.item())
+    say(f"    whole-codebook scans: {n_scans} of {got.size} pairs")
+    if kernel_path == 1:
+        assert n_scans == 0                                  # the general kernels do not count
+    elif kind in ("far_codebook", "duplicates_across_chunks"):
+        assert n_scans == got.size                           # nothing can be separated: every pair is scanned
+    else:
+        assert 0 <= n_scans < got.size
     if kind == "duplicates_across_chunks":
         assert np.all(ref["idx"] < 128) and np.all(got < 128)
         half = Case(orc, 61, d_out, d_in, 7, block, dtype="bf16", codebook=cb[:128], sigma=sigma).oracle_encode(orc)

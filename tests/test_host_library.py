@@ -100,6 +100,11 @@ def test_device_entry_points_reject_bad_arguments_before_any_launch():
         assert f(d_in=384, ldw=384, block=256) == qamw.ERR_SHAPE   # does not divide d_in
         assert f(ldw=255) == qamw.ERR_SHAPE                    # leading dimension too small
     assert enc(dtype=7) == qamw.ERR_INVALID_ARG
+    a = good
+    assert L.qamw_encode_stats(a["W"], 0, 8, 256, 256, None, None, None, a["cb"], 11, 128, a["packed"], a["norms"], None,
+                               None) == qamw.ERR_INVALID_ARG          # the counter is required
+    assert L.qamw_encode_stats(None, 0, 8, 256, 256, None, None, None, a["cb"], 11, 128, a["packed"], a["norms"], p,
+                               None) == qamw.ERR_INVALID_ARG
 
     def cal(**kw):
         a = {**good, "max_rows": 1024, "ws": p, "ws_bytes": 1 << 30, **kw}
