@@ -475,3 +475,50 @@ def test_full_size_matrices_sampled_rows(orc, codebooks, wl_name, mat):
     ws = f32_d.double() * s_d.double()[None, :]
     ratio = (ws.norm(dim=1) / norms_d.double())
     assert float((ratio - 1).abs().max()) < 0.05
+
+
+def test_full_layer_in_the_bench_configuration(orc, codebooks):
+    """One layer of the 7B workload exactly as bench.py runs it: per-matrix calibration and encode, ONE
+    qamw_decode_batch launch for the layer's seven matrices, ONE qamw_matmul_batch call; the oracle checks
+    64 seeded rows of every matrix (decode element by element; products against its fp64 decode)."""
+    wl = synth.WORKLOADS["c2_llama2_7b_b11"]
+    say(f"[full layer] {wl.name}: {len(wl.matrices)} matrices, one decode launch, one matmul call")
+    cb = codebooks[wl.bits]
+    cb_d = torch.from_numpy(cb).cuda()
+    m_rows = 2
+    mats, dec_entries, mm_entries = [], [], []
+    for name, d_out, d_in, site in wl.matrices:
+        Wd = synth.weight_device(synth.seed_for(wl.config_id, 1, name), d_out, d_in, wl.row_sigma, wl.dtype)
+        s = qamw.channel_scales(synth.act_rms_host(synth.seed_for(wl.config_id, 1, site), d_in), wl.alpha)
+        sg = qamw.sign_mask(synth.seed_for(wl.config_id, 1, "mask-" + site), d_in)
+        s_d, sg_d = torch.from_numpy(s).cuda(), torch.from_numpy(sg).cuda()
+        sigma_d = qamw.calibrate_sigma(Wd, wl.block, chan_scale=s_d, signs=sg_d)
+        packed_d, norms_d = qamw.encode(Wd, cb_d, wl.bits, wl.block, chan_scale=s_d, signs=sg_d, pair_sigma=sigma_d)
+        del Wd
+        out_d = torch.empty((d_out, d_in), dtype=torch.bfloat16, device="cuda")
+        X = torch.randn((m_rows, d_in), device="cuda", generator=torch.Generator("cuda").manual_seed(d_out + d_in)).to(torch.bfloat16)
+        Y = torch.empty((m_rows, d_out), device="cuda")
+        mats.append(dict(name=name, d_out=d_out, d_in=d_in, s=s, sg=sg, sigma=sigma_d.cpu().numpy(), packed=packed_d,
+                         norms=norms_d, out=out_d, X=X, Y=Y))
+        dec_entries.append((packed_d, norms_d, d_in, s_d, sg_d, sigma_d, out_d))
+        mm_entries.append((X, packed_d, norms_d, s_d, sg_d, sigma_d, Y))
+    qamw.decode_batch(qamw.make_decode_items(dec_entries), cb_d, wl.bits, wl.block)
+    items = qamw.make_matmul_items(mm_entries)
+    ws = torch.empty(items[4], dtype=torch.uint8, device="cuda")
+    qamw.matmul_batch(items, cb_d, wl.bits, wl.block, ws)
+    torch.cuda.synchronize()
+    for m in mats:
+        rows = _sampled_rows(m["d_out"], 64, 11)
+        rows_t = torch.from_numpy(rows).cuda()
+        idx = orc.unpack(m["packed"][rows_t].cpu().numpy(), m["d_in"], wl.bits)
+        nr = m["norms"][rows_t].cpu().numpy()
+        case = Case.__new__(Case)
+        case.d_in, case.bits, case.block, case.cb, case.s, case.sg, case.sigma = m["d_in"], wl.bits, wl.block, cb, m["s"], m["sg"], m["sigma"]
+        got16 = m["out"][rows_t].cpu().view(torch.int16).numpy().view(np.uint16)
+        rep = check_decode(orc, case, idx, nr, got_bf16=got16)
+        Wt = case.oracle_decode(orc, idx, nr, mode=orc.MODE_TRUTH)["w"]
+        X = m["X"].float().cpu().numpy().astype(np.float64)
+        err = np.abs(m["Y"][:, rows_t].cpu().numpy() - X @ Wt.T)
+        bound = 1e-6 * np.linalg.norm(X, axis=1)[:, None] * np.linalg.norm(Wt, axis=1)[None, :]
+        assert np.all(err <= bound)
+        say(f"    {m['name']}: decode {rep}, product error / (||x|| ||w||) max {float((err / (bound / 1e-6)).max()):.1e}")
