@@ -341,7 +341,7 @@ def test_fused_matmul_batch_equals_single_calls(orc, codebooks):
 
 
 def test_config0_full_matrix(orc, codebooks):
-    """BASELINE config 0: 2048 x 2048 fp32, b = 128, K = 2048, every pair checked."""
+    """The small single-matrix configuration: 2048 x 2048 fp32, b = 128, K = 2048, every pair checked."""
     say("[config0] 2048x2048 B=11 b=128")
     wl = synth.WORKLOADS["c0_single_2048"]
     seed = synth.seed_for(0, 0, "q")
