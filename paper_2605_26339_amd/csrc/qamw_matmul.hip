@@ -12,13 +12,13 @@
 // for a bf16 matrix.
 //
 // Kernels: k_rotate_x (one wave per activation row and 1024-column slab, the encoder's register
-// transform) and k_qgemv: a workgroup of 4 waves owns 16 rows of one matrix; wave w takes the
+// transform) and k_qgemv: a workgroup of 4 waves owns 8 rows of one matrix; wave w takes the
 // 1024-column slabs w, w+4, ...; per slab it holds the slab's z in registers, requests the packed
 // words of a group of rows at once, and per row unpacks 8 indices, gathers 8 codewords from the
 // LDS codebook and multiply-adds them into per-row, per-lane accumulators.  Nothing crosses lanes
 // until the wave has finished its slabs: then one transposing reduction (two half-swaps that halve
 // the number of live sums, a butterfly over the remaining 16 lanes), a sum over the 4 waves in
-// LDS in a fixed order, times r_i, and the store of 16 x m outputs.
+// LDS in a fixed order, times r_i, and the store of 8 x m outputs.
 #include <cmath>
 
 #include "qamw_common.hpp"
@@ -30,7 +30,7 @@ namespace qamw {
 constexpr int GV_THREADS = 256;
 constexpr int GV_WAVES = GV_THREADS / WAVE;
 constexpr int GV_SLAB = 1024;
-constexpr int GV_UNIT_ROWS = 16;       // rows of one unit of work; lane r keeps the result of row r
+constexpr int GV_UNIT_ROWS = 8;        // rows per workgroup (8: more, shorter workgroups balance a layer-sized launch better than 16 or 32)
 constexpr int GV_MAX_M = 8;
 
 typedef uint32_t gv_u32x4_t __attribute__((ext_vector_type(4)));
@@ -46,7 +46,7 @@ struct GemvMat {
     int d_out, d_in, n_slabs;
     float sigma_default;                   // 1/sqrt(d_in), used when pair_sigma is NULL
 };
-// Work lists of one launch: rotation items (activation row, slab) and row groups (16 rows), each numbered
+// Work lists of one launch: rotation items (activation row, slab) and row groups (GV_UNIT_ROWS rows), each numbered
 // matrix-major.
 struct GemvBatch {
     GemvMat mat[QAMW_MATMUL_MAX_BATCH];
@@ -135,13 +135,13 @@ template <int RG> __device__ __forceinline__ void gv_reduce_rows(float (&a)[RG])
     }
 }
 
-// Y[t][row] = r_row * sum over the row's pairs of <c[idx], z_t>, 16 rows per workgroup
+// Y[t][row] = r_row * sum over the row's pairs of <c[idx], z_t>, GV_UNIT_ROWS rows per workgroup
 template <int BITS, int MT, int RG>
 __global__ __launch_bounds__(GV_THREADS) void k_qgemv(GemvBatch bt) {
     extern __shared__ __align__(16) float gv_lds[];
     typedef gv_u32x4_t u32x4_a4_t __attribute__((aligned(4)));
     float2 *cb_lds = reinterpret_cast<float2 *>(gv_lds);        // K codewords
-    float *red = gv_lds + 2 * bt.K;                             // [waves][16 rows][MT]
+    float *red = gv_lds + 2 * bt.K;                             // [waves][rows][MT]
     const int lane = threadIdx.x & (WAVE - 1);
     const int wid = threadIdx.x >> 6;
     const float2 *cbk = reinterpret_cast<const float2 *>(bt.codebook);
