@@ -149,6 +149,35 @@ int qamw_encode_stats(const void *W, int dtype, int d_out, int d_in, int64_t ldw
                       int hadamard_block, uint8_t *packed_out, float *row_norms_out,
                       unsigned long long *full_scans, void *stream);
 
+/* Codebook training on the device (Sec. 3.5; a codebook fitted to a checkpoint's own pairs is the follow-up
+ * named in the paper's discussion).
+ *
+ * qamw_normalised_pairs: the points the encoder quantises -- encoder steps 1-4 (channel scale, row norm,
+ * rotation, division by sigma_k) written out instead of searched: pairs_out[i][2k], [2k+1] = pair k of row i,
+ * bit for bit what qamw_encode sees.  pairs_out: device, d_out * d_in floats, 16-byte aligned.
+ * row_norms_out: device, d_out floats.  Shapes as qamw_encode_polar; otherwise QAMW_ERR_UNSUPPORTED.
+ *
+ * qamw_lloyd_device: Lloyd iterations over n_samples 2-D points in device memory (8-byte aligned, x then y).
+ * codebook: device, 2^bits x 2 floats: the initial points on entry, the trained points on return.  Each
+ * iteration assigns every sample to its nearest point by exact fp32 squared distances over the whole
+ * codebook (lowest index on ties) and moves every point to the mean of its cell; the cell sums are kept in
+ * 64-bit fixed point (2^-30; coordinates beyond +-256 enter the sums clamped), so the result is the same on
+ * every run.  An empty cell keeps its point (the CPU trainer re-seeds it).  Stops as qamw_train_codebook
+ * does: relative change of the mean squared error below tol, or max_iters assignments; the points are not
+ * moved after the last assignment, so the codebook and *mse_out belong together.
+ * The call BLOCKS: it synchronises the stream once per iteration to read the error.
+ * workspace: device, qamw_lloyd_workspace_bytes() bytes, 16-byte aligned, owned by the caller.
+ * mse_out / iters_out: host, nullable.
+ * Errors: bits outside [1,12], n_samples < 2^bits or > 2^24, max_iters < 1, tol < 0, NULL or misaligned
+ * buffers, workspace too small -> INVALID_ARG. */
+int qamw_normalised_pairs(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
+                          const int8_t *signs, const float *pair_sigma, int hadamard_block, float *pairs_out,
+                          float *row_norms_out, void *stream);
+int qamw_lloyd_workspace_bytes(int bits, size_t *bytes_out);
+int qamw_lloyd_device(const float *samples, uint64_t n_samples, int bits, float *codebook, int max_iters,
+                      double tol, void *workspace, size_t workspace_bytes, double *mse_out, int *iters_out,
+                      void *stream);
+
 /* Polar baseline of Sec. 3 ("Polar Baseline"; distortion: the polar pair theorem and the
  * Rayleigh-Lloyd corollary).
  *

@@ -138,6 +138,40 @@ int qamw_encode_stats(const void *W, int dtype, int d_out, int d_in, int64_t ldw
                        row_norms_out, full_scans, stream);
 }
 
+int qamw_normalised_pairs(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
+                          const int8_t *signs, const float *pair_sigma, int hadamard_block, float *pairs_out,
+                          float *row_norms_out, void *stream) {
+    if (!W || !pairs_out || !row_norms_out) return QAMW_ERR_INVALID_ARG;
+    if (dtype != QAMW_DTYPE_F32 && dtype != QAMW_DTYPE_BF16) return QAMW_ERR_INVALID_ARG;
+    int rc = check_common(d_out, d_in, 1, hadamard_block);
+    if (rc != QAMW_OK) return rc;
+    if (ldw < d_in) return QAMW_ERR_SHAPE;
+    qamw::Problem p = make_problem(d_out, d_in, chan_scale, signs, pair_sigma, nullptr, 1, hadamard_block, stream);
+    if (!qamw::pairs_launchable(W, dtype, ldw, p, pairs_out)) return QAMW_ERR_UNSUPPORTED;
+    if (launch_norms(W, dtype, ldw, d_out, p, row_norms_out) != hipSuccess) return QAMW_ERR_DEVICE;
+    return qamw::launch_pairs(W, dtype, ldw, p, row_norms_out, pairs_out) == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
+}
+
+int qamw_lloyd_workspace_bytes(int bits, size_t *bytes_out) {
+    if (!bytes_out || bits < 1 || bits > QAMW_MAX_BITS) return QAMW_ERR_INVALID_ARG;
+    *bytes_out = qamw::lloyd_workspace_bytes(1 << bits);
+    return QAMW_OK;
+}
+
+int qamw_lloyd_device(const float *samples, uint64_t n_samples, int bits, float *codebook, int max_iters, double tol,
+                      void *workspace, size_t workspace_bytes, double *mse_out, int *iters_out, void *stream) {
+    if (!samples || !codebook || !workspace || bits < 1 || bits > QAMW_MAX_BITS || max_iters < 1 || !(tol >= 0.0))
+        return QAMW_ERR_INVALID_ARG;
+    const int K = 1 << bits;
+    if (n_samples < (uint64_t)K || n_samples > (1ull << 24)) return QAMW_ERR_INVALID_ARG;
+    if (workspace_bytes < qamw::lloyd_workspace_bytes(K) || (reinterpret_cast<uintptr_t>(workspace) & 15) ||
+        (reinterpret_cast<uintptr_t>(samples) & 7) || (reinterpret_cast<uintptr_t>(codebook) & 7))
+        return QAMW_ERR_INVALID_ARG;
+    hipError_t e = qamw::run_lloyd(samples, (long long)n_samples, K, codebook, max_iters, tol, workspace, mse_out, iters_out,
+                                   (hipStream_t)stream);
+    return e == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
+}
+
 int qamw_encode_polar(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
                       const int8_t *signs, const float *pair_sigma, const float *levels, int bits_a, int bits_p,
                       int hadamard_block, uint8_t *packed_out, float *row_norms_out, void *stream) {

@@ -80,6 +80,11 @@ struct MatmulItem {
     int d_out, d_in;
 };
 hipError_t launch_matmul_batch(const MatmulItem *items, int n, int xdtype, int m, const Problem &p, void *workspace);
+size_t lloyd_workspace_bytes(int K);
+hipError_t run_lloyd(const float *samples, long long n, int K, float *codebook, int max_iters, double tol, void *workspace,
+                     double *mse_out, int *iters_out, hipStream_t stream);
+bool pairs_launchable(const void *W, int dtype, int64_t ldw, const Problem &p, const float *pairs);
+hipError_t launch_pairs(const void *W, int dtype, int64_t ldw, const Problem &p, const float *norms, float *pairs);
 bool mfma_encode_supported(const Problem &p);
 hipError_t launch_encode_mfma(const void *W, int dtype, int64_t ldw, const Problem &p, const float *norms,
                               uint8_t *packed);

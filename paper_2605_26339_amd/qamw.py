@@ -21,6 +21,7 @@ EXPORTS = [
     "qamw_channel_scales", "qamw_train_codebook", "qamw_calibrate_workspace_bytes", "qamw_calibrate_sigma", "qamw_encode", "qamw_decode",
     "qamw_decode_f32", "qamw_decode_batch", "qamw_set_kernel_path", "qamw_polar_codebook", "qamw_encode_polar",
     "qamw_matmul_workspace_bytes", "qamw_matmul", "qamw_matmul_batch", "qamw_encode_stats",
+    "qamw_normalised_pairs", "qamw_lloyd_workspace_bytes", "qamw_lloyd_device",
 ]
 
 
@@ -81,6 +82,9 @@ def lib() -> C.CDLL:
         L.qamw_matmul_workspace_bytes.argtypes = [i32, i32, i32, C.POINTER(C.c_size_t)]
         L.qamw_matmul.argtypes = [vp, i32, i32, i64, vp, vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, C.c_size_t, vp, i64, vp]
         L.qamw_matmul_batch.argtypes = [C.POINTER(MatmulItem), i32, i32, i32, vp, i32, i32, vp, C.c_size_t, vp]
+        L.qamw_normalised_pairs.argtypes = [vp, i32, i32, i32, i64, vp, vp, vp, i32, vp, vp, vp]
+        L.qamw_lloyd_workspace_bytes.argtypes = [i32, C.POINTER(C.c_size_t)]
+        L.qamw_lloyd_device.argtypes = [vp, u64, i32, vp, i32, C.c_double, vp, C.c_size_t, C.POINTER(C.c_double), C.POINTER(i32), vp]
         L.qamw_polar_codebook.argtypes = [i32, i32, vp, vp, C.POINTER(C.c_double)]
         L.qamw_encode_polar.argtypes = [vp, i32, i32, i32, i64, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp]
         for name in EXPORTS:
@@ -138,6 +142,39 @@ def train_codebook(bits: int, n_samples: int = 1 << 20, seed: int = 0, max_iters
     _check(lib().qamw_train_codebook(bits, n_samples, seed & (2**64 - 1), max_iters, tol, out.ctypes.data,
                                      C.byref(mse), C.byref(it)), "qamw_train_codebook")
     return out, float(mse.value), int(it.value)
+
+
+def normalised_pairs(W, block: int, chan_scale=None, signs=None, pair_sigma=None, stream=None):
+    """The points the encoder quantises: (pairs float32 [d_out][d_in/2][2], row_norms float32 [d_out])."""
+    import torch
+
+    _require_cuda(W, chan_scale, signs, pair_sigma)
+    if W.dim() != 2 or W.stride(1) != 1:
+        raise ValueError("W must be 2-D with unit column stride")
+    d_out, d_in = W.shape
+    pairs = torch.empty((d_out, d_in // 2, 2), dtype=torch.float32, device=W.device)
+    norms = torch.empty(d_out, dtype=torch.float32, device=W.device)
+    _check(lib().qamw_normalised_pairs(_ptr(W), _dtype_code(W), d_out, d_in, W.stride(0), _ptr(chan_scale), _ptr(signs),
+                                       _ptr(pair_sigma), block, _ptr(pairs), _ptr(norms), _stream(stream)),
+           "qamw_normalised_pairs")
+    return pairs, norms
+
+
+def lloyd_device(samples, init_codebook, bits: int, max_iters: int = 200, tol: float = 1e-7, stream=None):
+    """Lloyd iterations on the device over samples (CUDA float32 [n][2]) from init_codebook ([2^bits][2]).
+    Returns (codebook CUDA float32 [2^bits][2], mse, iterations).  Blocks until done."""
+    import torch
+
+    _require_cuda(samples, init_codebook)
+    samples = samples.contiguous()
+    cb = init_codebook.to(torch.float32).contiguous().clone()
+    need = C.c_size_t()
+    _check(lib().qamw_lloyd_workspace_bytes(bits, C.byref(need)), "qamw_lloyd_workspace_bytes")
+    ws = torch.empty(need.value, dtype=torch.uint8, device=samples.device)
+    mse, it = C.c_double(), C.c_int()
+    _check(lib().qamw_lloyd_device(_ptr(samples), samples.shape[0], bits, _ptr(cb), max_iters, tol, _ptr(ws), need.value,
+                                   C.byref(mse), C.byref(it), _stream(stream)), "qamw_lloyd_device")
+    return cb, float(mse.value), int(it.value)
 
 
 def polar_codebook(bits_a: int, bits_p: int):

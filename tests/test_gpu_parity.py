@@ -533,3 +533,67 @@ def test_full_layer_in_the_bench_configuration(orc, codebooks):
         bound = 1e-6 * np.linalg.norm(X, axis=1)[:, None] * np.linalg.norm(Wt, axis=1)[None, :]
         assert np.all(err <= bound)
         say(f"    {m['name']}: decode {rep}, product error / (||x|| ||w||) max {float((err / (bound / 1e-6)).max()):.1e}")
+
+
+@pytest.mark.parametrize("d_out,d_in,block,dtype,sigma", [(19, 2048, 128, "bf16", "calibrated"), (7, 5632, 512, "f32", None)])
+def test_normalised_pairs_are_the_encoders_points(orc, d_out, d_in, block, dtype, sigma):
+    """The pairs written out by the library are, bit for bit, the oracle's fp32-ordered front half."""
+    say(f"[pairs] {d_out}x{d_in} b={block} {dtype}")
+    dummy = np.array([[0.0, 0.0], [1.0, 1.0]], dtype=np.float32)
+    case = Case(orc, 111, d_out, d_in, 1, block, dtype=dtype, codebook=dummy, sigma=sigma)
+    ref = orc.encode(case.W, dummy, 1, block, chan_scale=case.s, signs=case.sg, pair_sigma=case.sigma, want_gaps=False,
+                     want_x=True)
+    pairs, norms = qamw.normalised_pairs(case.W_dev, block, chan_scale=case.s_dev, signs=case.sg_dev, pair_sigma=case.sigma_dev)
+    torch.cuda.synchronize()
+    ref_norms = ref["norms"].astype(np.float32)
+    got_norms = norms.cpu().numpy()
+    same = got_norms == ref_norms                              # a norm may differ in its last bit (fp64 summation order)
+    assert np.abs(got_norms.view(np.int32).astype(np.int64) - ref_norms.view(np.int32).astype(np.int64)).max() <= 1
+    assert np.array_equal(pairs.cpu().numpy()[same], ref["x"].astype(np.float32)[same])
+
+
+@pytest.mark.parametrize("K,iters", [(16, 1), (16, 4), (64, 12)])
+def test_device_lloyd_follows_the_oracle(orc, K, iters):
+    """Same samples, same initial points, same number of iterations: the device's codebook is the oracle's
+    (the device assigns with fp32 distances and sums in fixed point, so a sample on a cell edge may change
+    sides: 1e-4 absolute on the points), the error the same to 1e-5 relative."""
+    say(f"[lloyd] K={K} iterations={iters}")
+    bits = int(np.log2(K))
+    xy = orc.gauss_samples(5, 1 << 14).astype(np.float32)
+    init = orc.codebook_init(K).astype(np.float32)
+    want_cb, want_mse, want_it = orc.lloyd(xy.astype(np.float64), K, init=init.astype(np.float64), max_iters=iters, tol=0.0)
+    cb, mse, it = qamw.lloyd_device(torch.from_numpy(xy).cuda(), torch.from_numpy(init).cuda(), bits, max_iters=iters, tol=0.0)
+    assert it == want_it == iters
+    assert np.abs(cb.cpu().numpy().astype(np.float64) - want_cb).max() < 1e-4
+    assert abs(mse - want_mse) < 1e-5 * want_mse
+    cb2, mse2, _ = qamw.lloyd_device(torch.from_numpy(xy).cuda(), torch.from_numpy(init).cuda(), bits, max_iters=iters, tol=0.0)
+    assert torch.equal(cb, cb2) and mse == mse2               # fixed-point sums: the same on every run
+
+
+def test_codebook_learned_on_a_matrix_own_pairs(orc):
+    """The follow-up the paper names: fit the codebook to a matrix's own normalised pairs, all on the device.
+    The result satisfies the Lloyd conditions on those pairs and lowers the matrix's quantisation error below
+    that of the Gaussian-trained codebook's starting point."""
+    bits, block, d_out, d_in = 8, 128, 512, 2048
+    say(f"[learned codebook] {d_out}x{d_in} B={bits}")
+    start = qamw.train_codebook(bits, 1 << 16, seed=0, max_iters=20)[0]
+    case = Case(orc, 121, d_out, d_in, bits, block, codebook=start, row_sigma=0.5)
+    pairs, _ = qamw.normalised_pairs(case.W_dev, block, chan_scale=case.s_dev, signs=case.sg_dev, pair_sigma=case.sigma_dev)
+    samples = pairs.reshape(-1, 2)
+    cb0, mse0, _ = qamw.lloyd_device(samples, case.cb_dev, bits, max_iters=1)
+    cb, mse, it = qamw.lloyd_device(samples, case.cb_dev, bits, max_iters=100, tol=1e-6)
+    say(f"    mean squared pair error {mse0:.6f} -> {mse:.6f} after {it} assignments")
+    assert mse < mse0 and torch.equal(cb0, case.cb_dev)       # one assignment: error of the start, points unmoved
+    # Lloyd conditions, checked by the oracle's exact assignment on a subsample
+    # Lloyd conditions, checked with the oracle's exact (fp64) assignment of every sample
+    host = samples.cpu().numpy().astype(np.float64)
+    cbh = cb.cpu().numpy().astype(np.float64)
+    full, err = orc.assign(host, cbh, threads=16)
+    assert abs(err.mean() - mse) < 1e-5 * mse                  # the reported error belongs to the returned points
+    cnt = np.bincount(full, minlength=1 << bits)
+    means = np.stack([np.bincount(full, weights=host[:, e], minlength=1 << bits) for e in (0, 1)], 1)
+    ok = cnt > 50
+    assert ok.sum() > 200
+    drift = np.abs(means[ok] / cnt[ok, None] - cbh[ok]).max()
+    say(f"    largest distance between a point and the mean of its cell: {drift:.2e}")
+    assert drift < 2e-2

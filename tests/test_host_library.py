@@ -227,6 +227,49 @@ def test_matmul_rejects_bad_arguments():
     assert L.qamw_matmul_workspace_bytes(256, 8, 1, None) == qamw.ERR_INVALID_ARG
 
 
+def test_device_lloyd_and_pairs_reject_bad_arguments():
+    L = qamw.lib()
+    p = C.c_void_p(0x1000)
+    need = C.c_size_t()
+    assert L.qamw_lloyd_workspace_bytes(11, C.byref(need)) == qamw.OK and need.value >= 2048 * 40
+    assert L.qamw_lloyd_workspace_bytes(0, C.byref(need)) == qamw.ERR_INVALID_ARG
+    assert L.qamw_lloyd_workspace_bytes(11, None) == qamw.ERR_INVALID_ARG
+
+    def ll(**kw):
+        a = dict(samples=p, n=4096, bits=4, cb=p, iters=10, tol=1e-6, ws=p, ws_bytes=1 << 20)
+        a.update(kw)
+        return L.qamw_lloyd_device(a["samples"], a["n"], a["bits"], a["cb"], a["iters"], a["tol"], a["ws"], a["ws_bytes"], None,
+                                   None, None)
+
+    assert ll(samples=None) == qamw.ERR_INVALID_ARG
+    assert ll(cb=None) == qamw.ERR_INVALID_ARG
+    assert ll(ws=None) == qamw.ERR_INVALID_ARG
+    assert ll(bits=0) == qamw.ERR_INVALID_ARG
+    assert ll(bits=13) == qamw.ERR_INVALID_ARG
+    assert ll(n=8) == qamw.ERR_INVALID_ARG                    # fewer samples than points
+    assert ll(n=(1 << 24) + 1) == qamw.ERR_INVALID_ARG
+    assert ll(iters=0) == qamw.ERR_INVALID_ARG
+    assert ll(tol=-1.0) == qamw.ERR_INVALID_ARG
+    assert ll(ws_bytes=100) == qamw.ERR_INVALID_ARG
+    assert ll(ws=C.c_void_p(0x1008)) == qamw.ERR_INVALID_ARG
+    assert ll(samples=C.c_void_p(0x1004)) == qamw.ERR_INVALID_ARG
+
+    def pr(**kw):
+        a = dict(W=p, dtype=0, d_out=8, d_in=256, ldw=256, block=128, pairs=p, norms=p)
+        a.update(kw)
+        return L.qamw_normalised_pairs(a["W"], a["dtype"], a["d_out"], a["d_in"], a["ldw"], None, None, None, a["block"],
+                                       a["pairs"], a["norms"], None)
+
+    assert pr(W=None) == qamw.ERR_INVALID_ARG
+    assert pr(pairs=None) == qamw.ERR_INVALID_ARG
+    assert pr(norms=None) == qamw.ERR_INVALID_ARG
+    assert pr(dtype=4) == qamw.ERR_INVALID_ARG
+    assert pr(d_in=255, ldw=255) == qamw.ERR_SHAPE
+    assert pr(block=48) == qamw.ERR_SHAPE
+    assert pr(d_in=64, ldw=64, block=32) == qamw.ERR_UNSUPPORTED
+    assert pr(pairs=C.c_void_p(0x1004)) == qamw.ERR_UNSUPPORTED
+
+
 def test_kernel_path_switch():
     prev = qamw.set_kernel_path(1)
     assert qamw.set_kernel_path(0) == 1
