@@ -597,3 +597,53 @@ def test_codebook_learned_on_a_matrix_own_pairs(orc):
     drift = np.abs(means[ok] / cnt[ok, None] - cbh[ok]).max()
     say(f"    largest distance between a point and the mean of its cell: {drift:.2e}")
     assert drift < 2e-2
+
+
+def test_entry_points_can_be_captured_in_a_graph(orc, codebooks):
+    """The device entry points allocate nothing and do not synchronise, so a caller can record them into a HIP
+    graph: calibration, encode, batched decode and the fused product are captured once and replayed several
+    times on changing inputs, with eager work in between; every replay equals the eager result."""
+    say("[graph] capture of calibrate + encode + decode_batch + matmul_batch")
+    bits, block, m = 11, 128, 2
+    cb = torch.from_numpy(codebooks[bits]).cuda()
+    shapes = [(96, 2048), (40, 5632)]
+    g = torch.Generator("cuda").manual_seed(7)
+    Ws = [torch.randn(s, device="cuda", generator=g) for s in shapes]
+    Xs = [torch.randn((m, s[1]), device="cuda", generator=g) for s in shapes]
+    sig = [torch.empty(s[1] // 2, device="cuda") for s in shapes]
+    pk = [torch.empty((s[0], qamw.packed_row_bytes(s[1], bits)), dtype=torch.uint8, device="cuda") for s in shapes]
+    nr = [torch.empty(s[0], device="cuda") for s in shapes]
+    out = [torch.empty(s, dtype=torch.bfloat16, device="cuda") for s in shapes]
+    Y = [torch.empty((m, s[0]), device="cuda") for s in shapes]
+    ws_cal = torch.empty(max(qamw.calibrate_workspace_bytes(s[1], s[0]) for s in shapes), dtype=torch.uint8, device="cuda")
+    dec_items = qamw.make_decode_items([(pk[i], nr[i], shapes[i][1], None, None, sig[i], out[i]) for i in range(2)])
+    mm_items = qamw.make_matmul_items([(Xs[i], pk[i], nr[i], None, None, sig[i], Y[i]) for i in range(2)])
+    ws_mm = torch.empty(mm_items[4], dtype=torch.uint8, device="cuda")
+
+    def work():
+        for i in range(2):
+            qamw.calibrate_sigma(Ws[i], block, workspace=ws_cal, out=sig[i])
+            qamw.encode(Ws[i], cb, bits, block, pair_sigma=sig[i], out=(pk[i], nr[i]))
+        qamw.decode_batch(dec_items, cb, bits, block)
+        qamw.matmul_batch(mm_items, cb, bits, block, ws_mm)
+
+    work()                                                    # eager once (also warms everything up)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        work()
+    for rep in range(3):
+        for W in Ws:
+            W.normal_(generator=g)                            # new inputs in the same buffers
+        for X in Xs:
+            X.normal_(generator=g)
+        work()
+        torch.cuda.synchronize()
+        want = [t.clone() for t in pk + nr + out + Y]
+        for t in pk + nr + out + Y:
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(pk + nr + out + Y, want):
+            assert torch.equal(a, b), f"replay {rep} differs from the eager result"
