@@ -12,13 +12,16 @@
 // for a bf16 matrix.
 //
 // Kernels: k_rotate_x (one wave per activation row and 1024-column slab, the encoder's register
-// transform) and k_qgemv: a workgroup of 4 waves owns 8 rows of one matrix; wave w takes the
-// 1024-column slabs w, w+4, ...; per slab it holds the slab's z in registers, requests the packed
-// words of a group of rows at once, and per row unpacks 8 indices, gathers 8 codewords from the
-// LDS codebook and multiply-adds them into per-row, per-lane accumulators.  Nothing crosses lanes
-// until the wave has finished its slabs: then one transposing reduction (two half-swaps that halve
-// the number of live sums, a butterfly over the remaining 16 lanes), a sum over the 4 waves in
-// LDS in a fixed order, times r_i, and the store of 8 x m outputs.
+// transform) and k_qgemv: a workgroup of 4 waves owns up to 64 rows of one matrix; wave w takes
+// the 1024-column slabs w, w+4, ...; per slab it holds the slab's z in registers and walks the rows
+// in groups of 8 (the group's packed words requested together); per row it unpacks 8 indices,
+// gathers 8 codewords from the LDS codebook and multiply-adds them into per-row, per-lane
+// accumulators.  After each group one transposing reduction (each step
+// trades half of the live sums with the lane whose number differs in one bit, so 8 sums per lane end
+// as one row total per lane) adds the group's totals to the wave's running totals in LDS; at the end
+// the 4 waves' totals are summed in a fixed order, times r_i, and stored.  The row count per
+// workgroup is chosen per matrix so that every wave of a launch walks about the same number of
+// (slab, row group) steps.
 #include <cmath>
 
 #include "qamw_common.hpp"
@@ -30,7 +33,9 @@ namespace qamw {
 constexpr int GV_THREADS = 256;
 constexpr int GV_WAVES = GV_THREADS / WAVE;
 constexpr int GV_SLAB = 1024;
-constexpr int GV_UNIT_ROWS = 8;        // rows per workgroup (8: more, shorter workgroups balance a layer-sized launch better than 16 or 32)
+constexpr int GV_RG = 8;                // rows per group: requested together, accumulated together
+constexpr int GV_GROUPS_PER_WAVE = 8;   // target number of (slab, row group) steps per wave
+constexpr int GV_MAX_ROWS_PER_WG = 64;
 constexpr int GV_MAX_M = 8;
 
 typedef uint32_t gv_u32x4_t __attribute__((ext_vector_type(4)));
@@ -44,9 +49,10 @@ struct GemvMat {
     float *Z, *Y;
     int64_t ldx, ldy, row_bytes;
     int d_out, d_in, n_slabs;
+    int rows_per_wg;                       // rows one workgroup takes: a multiple of GV_RG, at most GV_MAX_ROWS_PER_WG
     float sigma_default;                   // 1/sqrt(d_in), used when pair_sigma is NULL
 };
-// Work lists of one launch: rotation items (activation row, slab) and row groups (GV_UNIT_ROWS rows), each numbered
+// Work lists of one launch: rotation items (activation row, slab) and workgroups (rows_per_wg rows), each numbered
 // matrix-major.
 struct GemvBatch {
     GemvMat mat[QAMW_MATMUL_MAX_BATCH];
@@ -113,97 +119,141 @@ template <int BITS> __device__ __forceinline__ uint32_t gv_field(const uint32_t 
     return v & ((1u << BITS) - 1u);
 }
 
-// Sums over the 64 lanes of RG per-lane values a[0..RG): two half-swaps leave RG/4 values per lane (lane bits
-// 5 and 4 select which), a butterfly over lane bits 0-3 finishes them.  On return a[0 .. RG/4) hold the totals
-// of rows  (lane>>5) * RG/2 + ((lane>>4)&1) * RG/4 + j  (the same in all 16 lanes of a row of lanes).
-template <int RG> __device__ __forceinline__ void gv_reduce_rows(float (&a)[RG]) {
-    static_assert(RG == 4 || RG == 8 || RG == 16, "rows per reduction");
+// Sums over the 64 lanes of N per-lane values a[0..N), N a power of two <= 64, leaving ONE total per lane:
+// each step pairs lane l with lane l ^ 2^bit (bit = 5, 4, ..., ), every lane keeps the half of the live values
+// selected by that bit of its number and adds what its partner held for that half.  When one value is left
+// the remaining bits are summed in the ordinary way.  On return a[0] is the total of row gv_lane_row<N>(lane).
+template <int N> __device__ __forceinline__ int gv_lane_row(int lane) {
+    int row = 0, n = N;
 #pragma unroll
-    for (int r = 0; r < RG / 2; ++r) {
-        auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(a[r]), __float_as_uint(a[r + RG / 2]), false, false);
-        a[r] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+    for (int bit = 5; bit >= 0 && n > 1; --bit) {
+        n >>= 1;
+        row += ((lane >> bit) & 1) * n;
     }
+    return row;
+}
+// one step: LIVE values are live in a[0..LIVE); lane l pairs with lane l ^ 2^BIT
+template <int N, int LIVE, int BIT> __device__ __forceinline__ void gv_reduce_step(float (&a)[N], int lane) {
+    if constexpr (LIVE > 1) {
+        constexpr int H = LIVE / 2;
 #pragma unroll
-    for (int r = 0; r < RG / 4; ++r) {
-        auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(a[r]), __float_as_uint(a[r + RG / 4]), false, false);
-        a[r] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
-    }
-#pragma unroll
-    for (int r = 0; r < RG / 4; ++r) {
-#pragma unroll
-        for (int s = 1; s < 16; s <<= 1) a[r] += __shfl_xor(a[r], s, WAVE);
+        for (int r = 0; r < H; ++r) {
+            if constexpr (BIT == 5) {
+                auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(a[r]), __float_as_uint(a[r + H]), false, false);
+                a[r] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+            } else if constexpr (BIT == 4) {
+                auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(a[r]), __float_as_uint(a[r + H]), false, false);
+                a[r] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+            } else {
+                const bool up = (lane >> BIT) & 1;
+                const float send = up ? a[r] : a[r + H], keep = up ? a[r + H] : a[r];
+                a[r] = keep + __shfl_xor(send, 1 << BIT, WAVE);
+            }
+        }
+    } else {
+        a[0] += __shfl_xor(a[0], 1 << BIT, WAVE);
     }
 }
+template <int N> __device__ __forceinline__ void gv_reduce_rows(float (&a)[N], int lane) {
+    static_assert(N >= 1 && N <= 64 && (N & (N - 1)) == 0, "rows per reduction");
+    gv_reduce_step<N, N, 5>(a, lane);
+    gv_reduce_step<N, (N > 1 ? N / 2 : 1), 4>(a, lane);
+    gv_reduce_step<N, (N > 2 ? N / 4 : 1), 3>(a, lane);
+    gv_reduce_step<N, (N > 4 ? N / 8 : 1), 2>(a, lane);
+    gv_reduce_step<N, (N > 8 ? N / 16 : 1), 1>(a, lane);
+    gv_reduce_step<N, (N > 16 ? N / 32 : 1), 0>(a, lane);
+}
 
-// Y[t][row] = r_row * sum over the row's pairs of <c[idx], z_t>, GV_UNIT_ROWS rows per workgroup
-template <int BITS, int MT, int RG>
+// Y[t][row] = r_row * sum over the row's pairs of <c[idx], z_t>
+template <int BITS, int MT>
 __global__ __launch_bounds__(GV_THREADS) void k_qgemv(GemvBatch bt) {
+    constexpr int RG = MT == 8 ? 4 : GV_RG, UR = GV_MAX_ROWS_PER_WG;
     extern __shared__ __align__(16) float gv_lds[];
     typedef gv_u32x4_t u32x4_a4_t __attribute__((aligned(4)));
     float2 *cb_lds = reinterpret_cast<float2 *>(gv_lds);        // K codewords
-    float *red = gv_lds + 2 * bt.K;                             // [waves][rows][MT]
+    float *red = gv_lds + 2 * bt.K;                             // [waves][UR rows][MT]
     const int lane = threadIdx.x & (WAVE - 1);
     const int wid = threadIdx.x >> 6;
-    const float2 *cbk = reinterpret_cast<const float2 *>(bt.codebook);
-    for (int i = threadIdx.x; i < bt.K; i += GV_THREADS) cb_lds[i] = cbk[i];
-    __syncthreads();
 
-    const int grp = blockIdx.x;                                 // the grid is exactly the number of row groups
+    const int grp = blockIdx.x;                                 // the grid is exactly the number of workgroups
     const int mi = gv_find(bt.grp_begin, bt.n, grp);
     const GemvMat &M = bt.mat[mi];
-    const int row0 = (grp - bt.grp_begin[mi]) * GV_UNIT_ROWS;
+    const int rpw = M.rows_per_wg;
+    const int row0 = (grp - bt.grp_begin[mi]) * rpw;
+    const int n_g = rpw / RG;                                   // row groups of this workgroup
     const int n_slabs = M.n_slabs, m = bt.m;
-    const int d_out = M.d_out, d_in = M.d_in, last_row = M.d_out - 1;
+    const int d_in = M.d_in, last_row = M.d_out - 1;
     const int64_t row_bytes = M.row_bytes;
     const uint8_t *packed = M.packed;
     const float *Z = M.Z;
     const unsigned row_dw = (unsigned)(row_bytes >> 2);
 
-    for (int rg = 0; rg < GV_UNIT_ROWS / RG; ++rg) {
-        float a[MT][RG];                                        // per-lane sums of this group's rows
-#pragma unroll
-        for (int t = 0; t < MT; ++t)
-#pragma unroll
-            for (int r = 0; r < RG; ++r) a[t][r] = 0.0f;
-        for (int slab = wid; slab < n_slabs; slab += GV_WAVES) {
-            const int col0 = slab * GV_SLAB + 16 * lane;       // no transform here: lanes in natural column order
-            const bool active = col0 < d_in;
-            const int c = active ? col0 : 0;
-            const unsigned lane_off = (unsigned)(c >> 4) * BITS;   // the lane's 8 fields: BITS bytes, same place in every row
-            const unsigned lane_b0 = lane_off & ~3u;
-            const int sh = (int)(lane_off & 3u) * 8;
-            // packed words of the group's rows, all requested before any is used
-            uint32_t d[RG][4];
+    auto lane_col = [&](int slab) {                             // first of the lane's 16 columns (0 for idle lanes)
+        const int col0 = slab * GV_SLAB + 16 * lane;           // no transform here: lanes in natural column order
+        return col0 < d_in ? col0 : 0;
+    };
+    auto fetch = [&](int slab, int g, uint32_t (&d)[RG][4]) {
+        const unsigned lane_b0 = ((unsigned)(lane_col(slab) >> 4) * BITS) & ~3u;   // the lane's 8 fields: BITS bytes, same place in every row
+        const int r0 = row0 + g * RG;
+        if (r0 + RG - 1 < last_row) {
+            // 16 bytes from a 4-byte-aligned address; may run a few bytes into the next row
+            const uint8_t *base = packed + (int64_t)r0 * row_bytes + lane_b0;
 #pragma unroll
             for (int r = 0; r < RG; ++r) {
-                const int row = min(row0 + rg * RG + r, last_row);  // rows past the end re-read the last row
-                const uint8_t *rowp = packed + (int64_t)row * row_bytes;
-                if (row != last_row) {
-                    // 16 bytes from a 4-byte-aligned address; may run a few bytes into the next row
-                    const gv_u32x4_t v = *reinterpret_cast<const u32x4_a4_t *>(rowp + lane_b0);
-                    d[r][0] = v[0]; d[r][1] = v[1]; d[r][2] = v[2]; d[r][3] = v[3];
-                } else {
-                    // last row of the matrix: stay inside it (the clamped words are beyond the lane's fields)
-                    const uint32_t *rw = reinterpret_cast<const uint32_t *>(rowp);
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) d[r][k] = rw[min((lane_b0 >> 2) + k, row_dw - 1u)];
-                }
+                const gv_u32x4_t v = *reinterpret_cast<const u32x4_a4_t *>(base + (int64_t)r * row_bytes);
+                d[r][0] = v[0]; d[r][1] = v[1]; d[r][2] = v[2]; d[r][3] = v[3];
             }
-            // the slab's rotated activations, zero for missing tokens and idle lanes
-            float z[MT][16];
+        } else {
+            // the group reaches the matrix's last row: rows past the end re-read the last row, and every
+            // load stays inside its row (the clamped words are beyond the lane's fields)
 #pragma unroll
-            for (int t = 0; t < MT; ++t) {
-                const bool have = active && t < m;
-                const float4 *src = reinterpret_cast<const float4 *>(Z + (int64_t)(t < m ? t : 0) * d_in + c);
+            for (int r = 0; r < RG; ++r) {
+                const uint32_t *rw = reinterpret_cast<const uint32_t *>(packed + (int64_t)min(r0 + r, last_row) * row_bytes);
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float4 v = src[q];
-                    z[t][4 * q] = have ? v.x : 0.0f;
-                    z[t][4 * q + 1] = have ? v.y : 0.0f;
-                    z[t][4 * q + 2] = have ? v.z : 0.0f;
-                    z[t][4 * q + 3] = have ? v.w : 0.0f;
-                }
+                for (int k = 0; k < 4; ++k) d[r][k] = rw[min((lane_b0 >> 2) + k, row_dw - 1u)];
             }
+        }
+    };
+    auto load_z = [&](int slab, float (&z)[MT][16]) {           // the slab's rotated activations, zero for missing rows of X and idle lanes
+        const bool active = slab * GV_SLAB + 16 * lane < d_in;
+        const int c = lane_col(slab);
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            const bool have = active && t < m;
+            const float4 *src = reinterpret_cast<const float4 *>(Z + (int64_t)(t < m ? t : 0) * d_in + c);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 v = src[q];
+                z[t][4 * q] = have ? v.x : 0.0f;
+                z[t][4 * q + 1] = have ? v.y : 0.0f;
+                z[t][4 * q + 2] = have ? v.z : 0.0f;
+                z[t][4 * q + 3] = have ? v.w : 0.0f;
+            }
+        }
+    };
+
+    float z[MT][16];
+    if (wid < n_slabs) load_z(wid, z);                          // on its way while the codebook is staged
+    const float2 *cbk = reinterpret_cast<const float2 *>(bt.codebook);
+    for (int i = threadIdx.x; i < bt.K; i += GV_THREADS) cb_lds[i] = cbk[i];
+    __syncthreads();
+
+    // this wave's running row totals live in its own part of LDS (only this wave touches it until the barrier)
+    for (int i = lane; i < UR * MT; i += WAVE) red[wid * UR * MT + i] = 0.0f;
+    const int my_row = gv_lane_row<RG>(lane);                   // after the reduction: which of the group's rows this lane holds
+#pragma unroll 1
+    for (int slab = wid; slab < n_slabs; slab += GV_WAVES) {
+        const int sh = (int)(((unsigned)(lane_col(slab) >> 4) * BITS) & 3u) * 8;
+        const bool more_slabs = slab + GV_WAVES < n_slabs;
+#pragma unroll 1
+        for (int g = 0; g < n_g; ++g) {
+            uint32_t d[RG][4];
+            fetch(slab, g, d);
+            float acc[MT][RG];
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int r = 0; r < RG; ++r) acc[t][r] = 0.0f;
 #pragma unroll
             for (int r = 0; r < RG; ++r) {
                 uint32_t w[4];
@@ -216,30 +266,26 @@ __global__ __launch_bounds__(GV_THREADS) void k_qgemv(GemvBatch bt) {
                     const float2 cw = cb_lds[gv_field<BITS>(w, k)];
 #pragma unroll
                     for (int t = 0; t < MT; ++t)
-                        a[t][r] = __builtin_fmaf(cw.y, z[t][2 * k + 1], __builtin_fmaf(cw.x, z[t][2 * k], a[t][r]));
+                        acc[t][r] = __builtin_fmaf(cw.y, z[t][2 * k + 1], __builtin_fmaf(cw.x, z[t][2 * k], acc[t][r]));
                 }
             }
-        }
-        // totals over the lanes; one lane of each 16-lane row stores its RG/4 rows
-        const int first = rg * RG + (lane >> 5) * (RG / 2) + ((lane >> 4) & 1) * (RG / 4);
+            // totals over the lanes: every lane ends with one of the group's 8 rows (8 lanes hold each); one of them adds it in
 #pragma unroll
-        for (int t = 0; t < MT; ++t) {
-            gv_reduce_rows<RG>(a[t]);
-            if ((lane & 15) == 0) {
-#pragma unroll
-                for (int j = 0; j < RG / 4; ++j) red[(wid * GV_UNIT_ROWS + first + j) * MT + t] = a[t][j];
+            for (int t = 0; t < MT; ++t) {
+                gv_reduce_rows<RG>(acc[t], lane);
+                if ((lane & 7) == 0) red[(wid * UR + g * RG + my_row) * MT + t] += acc[t][0];
             }
         }
+        if (more_slabs) load_z(slab + GV_WAVES, z);
     }
     __syncthreads();
     // the 4 waves' sums in wave order, times the row norm
-    const int o = threadIdx.x;
-    if (o < GV_UNIT_ROWS * MT) {
+    for (int o = threadIdx.x; o < rpw * MT; o += GV_THREADS) {
         const int row = o / MT, t = o - row * MT;
         if (t < m && row0 + row <= last_row) {
             float s = 0.0f;
 #pragma unroll
-            for (int w = 0; w < GV_WAVES; ++w) s += red[(w * GV_UNIT_ROWS + row) * MT + t];
+            for (int w = 0; w < GV_WAVES; ++w) s += red[(w * UR + row) * MT + t];
             M.Y[(int64_t)t * M.ldy + row0 + row] = M.norms[row0 + row] * s;
         }
     }
@@ -274,13 +320,13 @@ static hipError_t launch_rotate(const GemvBatch &bt, int block, hipStream_t stre
 template <int BITS>
 static hipError_t launch_qgemv(const GemvBatch &bt, hipStream_t stream) {
     const unsigned blocks = (unsigned)bt.grp_begin[bt.n];
-#define QAMW_GV(MM, RR)                                                                                              \
-    hipLaunchKernelGGL((k_qgemv<BITS, MM, RR>), dim3(blocks), dim3(GV_THREADS),                                        \
-                       ((size_t)bt.K * 2 + (size_t)GV_WAVES * GV_UNIT_ROWS * MM) * sizeof(float), stream, bt)
-    if (bt.m == 1) QAMW_GV(1, 8);
-    else if (bt.m == 2) QAMW_GV(2, 8);
-    else if (bt.m <= 4) QAMW_GV(4, 8);
-    else QAMW_GV(8, 4);
+#define QAMW_GV(MM)                                                                                                  \
+    hipLaunchKernelGGL((k_qgemv<BITS, MM>), dim3(blocks), dim3(GV_THREADS),                                            \
+                       ((size_t)bt.K * 2 + (size_t)GV_WAVES * GV_MAX_ROWS_PER_WG * MM) * sizeof(float), stream, bt)
+    if (bt.m == 1) QAMW_GV(1);
+    else if (bt.m == 2) QAMW_GV(2);
+    else if (bt.m <= 4) QAMW_GV(4);
+    else QAMW_GV(8);
 #undef QAMW_GV
     return hipGetLastError();
 }
@@ -315,10 +361,16 @@ hipError_t launch_matmul_batch(const MatmulItem *items, int n, int xdtype, int m
         M.row_bytes = (((int64_t)(M.d_in / 2) * p.bits + 31) / 32) * 4;
         M.Z = reinterpret_cast<float *>(ws);
         ws += matmul_workspace_bytes(M.d_in, M.d_out, m);
+        // rows per workgroup: about GV_GROUPS_PER_WAVE (slab, row group) steps for the busiest wave, whatever d_in is
+        const int slabs_per_wave = (M.n_slabs + GV_WAVES - 1) / GV_WAVES;
+        int groups_per_wg = GV_GROUPS_PER_WAVE / slabs_per_wave;
+        if (groups_per_wg < 1) groups_per_wg = 1;
+        M.rows_per_wg = groups_per_wg * GV_RG;
+        if (M.rows_per_wg > GV_MAX_ROWS_PER_WG) M.rows_per_wg = GV_MAX_ROWS_PER_WG;
         bt.rot_begin[i] = (int)rot;
         bt.grp_begin[i] = (int)groups;
         rot += (int64_t)m * M.n_slabs;
-        groups += (M.d_out + GV_UNIT_ROWS - 1) / GV_UNIT_ROWS;
+        groups += (M.d_out + M.rows_per_wg - 1) / M.rows_per_wg;
         if (groups > 0x3fffffff || rot > 0x3fffffff) return hipErrorNotSupported;
     }
     for (int i = n; i <= QAMW_MATMUL_MAX_BATCH; ++i) {
