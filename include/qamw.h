@@ -178,6 +178,38 @@ int qamw_lloyd_device(const float *samples, uint64_t n_samples, int bits, float 
                       double tol, void *workspace, size_t workspace_bytes, double *mse_out, int *iters_out,
                       void *stream);
 
+/* Pruned nearest-codeword search (the search step of Sec. 3.1 with fewer distance evaluations; the index is
+ * the one the whole-codebook search of qamw_encode returns, bit for bit).
+ *
+ * qamw_search_grid_size (host): the grid has G x G cells, G = 2^(ceil(bits/2) + 2); the table takes
+ * 32 + 16 G^2 bytes.  Either output may be NULL.
+ *
+ * qamw_search_grid_build (host): codebook: host, 2^bits x 2 finite floats.  grid_out: host, grid_bytes >=
+ * the size above.  Layout: eight 32-bit words {0x44524751, bits, G, 8, fp32 cells per unit length
+ * inv_h = G / 2R, fp32 R, 0, 0}, R = 1.25 max |coordinate| of the codebook (1 if that is 0); then G x G
+ * records, record iy * G + ix for the cell {x : floor(x0 inv_h + G/2) = ix, floor(x1 inv_h + G/2) = iy},
+ * each eight 16-bit codeword indices in ascending order: every codeword that can be nearest to a point of
+ * the cell (a codeword is left out only if its smallest distance to the cell, widened by the rounding of
+ * the cell lookup, exceeds by more than 1e-5 relative the smallest over the codebook of the largest
+ * distance to the cell).  A shorter list is padded with its first entry; a cell with more than eight
+ * candidates holds the first seven and 0xFFFF, and its points get the whole-codebook scan.
+ * max_candidates_out / overflow_cells_out (nullable): the longest list, the number of such cells.
+ * Errors: bits outside [1,12], NULL codebook or grid_out, non-finite codeword, grid_bytes too small.
+ *
+ * qamw_encode_pruned (device): qamw_encode with the search restricted to the pair's cell record; pairs
+ * outside [-R, R)^2 or in an overflowing cell are decided by the whole-codebook scan and, if full_scans
+ * (device, one 64-bit counter, nullable) is given, ADDED to it.  grid: device, the table as built, 16-byte
+ * aligned; it must have been built from `codebook` with the same bits -- a table of another codebook gives
+ * wrong indices (never an out-of-range access: the grid size is taken from bits, indices are reduced mod K).
+ * Shapes: as qamw_encode_polar; anything else -> QAMW_ERR_UNSUPPORTED. */
+int qamw_search_grid_size(int bits, int *cells_per_side_out, size_t *bytes_out);
+int qamw_search_grid_build(const float *codebook, int bits, void *grid_out, size_t grid_bytes,
+                           int *max_candidates_out, uint64_t *overflow_cells_out);
+int qamw_encode_pruned(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
+                       const int8_t *signs, const float *pair_sigma, const float *codebook, int bits,
+                       int hadamard_block, const void *grid, uint8_t *packed_out, float *row_norms_out,
+                       unsigned long long *full_scans, void *stream);
+
 /* Polar baseline of Sec. 3 ("Polar Baseline"; distortion: the polar pair theorem and the
  * Rayleigh-Lloyd corollary).
  *

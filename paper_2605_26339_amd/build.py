@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqamw.so")
 
 SOURCES = ["qamw_host.cpp", "qamw_api.hip", "qamw_general.hip", "qamw_decode_fast.hip", "qamw_encode_fast.hip",
-           "qamw_encode_mfma.hip", "qamw_encode_polar.hip", "qamw_calibrate_fast.hip",
+           "qamw_encode_mfma.hip", "qamw_encode_polar.hip", "qamw_encode_grid.hip", "qamw_calibrate_fast.hip",
            "qamw_matmul.hip", "qamw_lloyd.hip"]
 
 # -ffp-contract=off: the codec's fp32 steps are rounded one by one; fused multiply-adds appear only

@@ -190,6 +190,28 @@ int qamw_encode_polar(const void *W, int dtype, int d_out, int d_in, int64_t ldw
     return e == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
 }
 
+int qamw_encode_pruned(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
+                       const int8_t *signs, const float *pair_sigma, const float *codebook, int bits, int hadamard_block,
+                       const void *grid, uint8_t *packed_out, float *row_norms_out, unsigned long long *full_scans,
+                       void *stream) {
+    if (!W || !codebook || !grid || !packed_out || !row_norms_out) return QAMW_ERR_INVALID_ARG;
+    if (dtype != QAMW_DTYPE_F32 && dtype != QAMW_DTYPE_BF16) return QAMW_ERR_INVALID_ARG;
+    int rc = check_common(d_out, d_in, bits, hadamard_block);
+    if (rc != QAMW_OK) return rc;
+    if (ldw < d_in) return QAMW_ERR_SHAPE;
+    if (reinterpret_cast<uintptr_t>(grid) & 15) return QAMW_ERR_INVALID_ARG;
+    qamw::Problem p = make_problem(d_out, d_in, chan_scale, signs, pair_sigma, codebook, bits, hadamard_block, stream);
+    p.full_scans = full_scans;
+    qamw::SearchGridView g;
+    g.table = grid;
+    if (qamw_search_grid_size(bits, &g.G, nullptr) != QAMW_OK) return QAMW_ERR_INVALID_ARG;
+    // nothing is launched for a shape outside the kernel's range
+    if (!qamw::grid_encode_launchable(W, dtype, ldw, p, g)) return QAMW_ERR_UNSUPPORTED;
+    if (launch_norms(W, dtype, ldw, d_out, p, row_norms_out) != hipSuccess) return QAMW_ERR_DEVICE;
+    hipError_t e = qamw::launch_encode_grid(W, dtype, ldw, p, g, row_norms_out, packed_out);
+    return e == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
+}
+
 int qamw_decode(const uint8_t *packed, const float *row_norms, int d_out, int d_in, const float *chan_scale,
                 const int8_t *signs, const float *pair_sigma, const float *codebook, int bits, int hadamard_block,
                 uint16_t *W_out, int64_t ldo, void *stream) {

@@ -1,0 +1,202 @@
+// QAM-W encoder with a pruned nearest-codeword search (the search step of Sec. 3.1; the result is
+// the same index the whole-codebook search returns).
+//
+// A uniform G x G grid covers the square [-R, R)^2 that holds the codebook.  For every cell the host
+// lists, in ascending index order, every codeword that can be nearest to some point of the cell
+// (qamw_search_grid_build: a codeword whose smallest distance to the cell exceeds the smallest over
+// the codebook of the LARGEST distance to the cell can never win).  The kernel locates the pair's
+// cell, reads its record of 8 candidates (one 16-byte load) and takes the minimum of the exact fp32
+// squared distances over them, strict comparison in ascending index order, so the lowest index wins
+// a tie exactly as in the whole-codebook scan.  A pair outside the square, or in a cell with more
+// than 8 candidates, is decided by the exact scan of the whole codebook (64 lanes x K/64 codewords).
+//
+// Front half as in the other fast encoders: a wave owns one row's slab of 1024 columns, 8 pairs per
+// lane, everything in registers; the codebook sits in LDS, the grid stays in global memory (1 MB at
+// K = 2048: resident in L2).
+#include "qamw_front.hpp"
+
+namespace qamw {
+
+constexpr int GF_THREADS = 256;
+constexpr int GF_WAVES = GF_THREADS / WAVE;
+constexpr int GSLAB = 1024;
+constexpr float GBIG = 3.0e38f;
+
+__device__ __forceinline__ float gdist2(float x0, float x1, float2 c) {
+    float e0 = x0 - c.x, e1 = x1 - c.y;
+    return __builtin_fmaf(e1, e1, e0 * e0);
+}
+
+template <int DTYPE, int B>
+__global__ __launch_bounds__(GF_THREADS) void k_encode_grid(const void *__restrict__ W, int64_t ldw, Problem p,
+                                                            const uint32_t *__restrict__ table, int G,
+                                                            const float *__restrict__ norms,
+                                                            uint8_t *__restrict__ packed, int n_slabs, int n_items) {
+    extern __shared__ __align__(16) float2 gcb[];               // K codewords
+    const int K = p.K;
+    const float2 *cbk = reinterpret_cast<const float2 *>(p.codebook);
+    for (int i = threadIdx.x; i < K; i += GF_THREADS) gcb[i] = cbk[i];
+    __syncthreads();
+
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int wid = threadIdx.x >> 6;
+    const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * GF_WAVES + wid);
+    if (item >= n_items) return;
+    // the table: a 32-byte header (word 4 = cells per unit length, as a float), then G x G records of 8 x 16 bits
+    const float inv_h = __uint_as_float(table[4]);
+    const float half_g = 0.5f * (float)G, g_f = (float)G;
+    const uint4 *cells = reinterpret_cast<const uint4 *>(table + 8);
+    const int row = item / n_slabs, slab = item - row * n_slabs;
+    const LaneSigns<B> ls(lane);
+    const int pos = slab_pos(lane);
+    const int col0 = slab * GSLAB + 16 * pos;
+    const bool active = col0 < p.d_in;
+    const int c = active ? col0 : 0;
+
+    // ---------------- front half: x_k = (F S (W D_s / r))_pair k / sigma_k, in registers
+    float x[16];
+    rotated_unit_row<DTYPE, B>(x, W, (int64_t)row * ldw, c, norms[row], p, ls);
+    {
+        float g[8];
+        if (p.pair_sigma) {
+            const float4 *g4 = reinterpret_cast<const float4 *>(p.pair_sigma + (c >> 1));
+            float4 a = g4[0], b = g4[1];
+            const float sg8[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+            for (int k = 0; k < 8; ++k) g[k] = 1.0f / sg8[k];                     // IEEE division
+        } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) g[k] = p.g_default;
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) x[e] = x[e] * g[e >> 1];
+    }
+
+    // ---------------- the cells' records: all 8 requested before the first is used
+    uint4 rec[8];
+    unsigned scan = 0;                                          // bit k: pair k needs the whole-codebook scan
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        // clamped to [-1, G] before the conversion (a NaN becomes -1): outside the square either way
+        const int ix = (int)floorf(fminf(fmaxf(__builtin_fmaf(x[2 * k], inv_h, half_g), -1.0f), g_f));
+        const int iy = (int)floorf(fminf(fmaxf(__builtin_fmaf(x[2 * k + 1], inv_h, half_g), -1.0f), g_f));
+        const bool inside = (unsigned)ix < (unsigned)G && (unsigned)iy < (unsigned)G;
+        rec[k] = cells[inside ? iy * G + ix : 0];
+        if (!inside) scan |= 1u << k;
+    }
+    unsigned idx[8];
+    const unsigned kmask = (unsigned)K - 1u;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const float x0 = x[2 * k], x1 = x[2 * k + 1];
+        const unsigned cand[8] = {rec[k].x & 0xffffu, rec[k].x >> 16, rec[k].y & 0xffffu, rec[k].y >> 16,
+                                  rec[k].z & 0xffffu, rec[k].z >> 16, rec[k].w & 0xffffu, rec[k].w >> 16};
+        if (cand[7] == 0xffffu) scan |= 1u << k;                // more candidates than a record holds
+        float bd = GBIG;
+        unsigned bi = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const unsigned ci = cand[j] & kmask;                // (the overflow mark stays inside the codebook)
+            const float dd = gdist2(x0, x1, gcb[ci]);
+            if (dd < bd) {
+                bd = dd;
+                bi = ci;
+            }
+        }
+        idx[k] = bi;
+    }
+
+    // ---------------- the exact scan for the pairs that need it: the whole wave works on one pair at a time
+    if (!active) scan = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        unsigned long long mask = __ballot((scan >> k) & 1u);
+        if (p.full_scans && mask && lane == 0) atomicAdd(p.full_scans, (unsigned long long)__popcll(mask));
+        while (mask) {
+            const int src = __ffsll((long long)mask) - 1;
+            mask &= mask - 1;
+            const float x0 = __shfl(x[2 * k], src, WAVE), x1 = __shfl(x[2 * k + 1], src, WAVE);
+            float bd = GBIG;
+            int bi = 0x7fffffff;
+            for (int j = lane; j < K; j += WAVE) {
+                const float dd = gdist2(x0, x1, gcb[j]);
+                if (dd < bd) {
+                    bd = dd;
+                    bi = j;
+                }
+            }
+#pragma unroll
+            for (int m = 1; m < WAVE; m <<= 1) {
+                const float od = __shfl_xor(bd, m, WAVE);
+                const int oi = __shfl_xor(bi, m, WAVE);
+                if (od < bd || (od == bd && oi < bi)) {
+                    bd = od;
+                    bi = oi;
+                }
+            }
+            if (bi == 0x7fffffff) bi = 0;                       // every distance NaN: as the plain scan, index 0
+            if (lane == src) idx[k] = (unsigned)bi;
+        }
+    }
+
+    // ---------------- pack: the lane's 8 fields are exactly `bits` bytes, byte aligned in the row
+    if (active) {
+        const int bits = p.bits;
+        uint8_t *dst = packed + (int64_t)row * p.row_bytes + (int64_t)(c >> 4) * bits;
+        unsigned __int128 acc = 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc |= (unsigned __int128)idx[k] << (k * bits);
+        for (int t = 0; t < bits; ++t) dst[t] = (uint8_t)(acc >> (8 * t));
+        if (col0 + 16 == p.d_in) {                              // last lane of the row zeroes the padding
+            const int64_t used = (int64_t)(p.d_in >> 4) * bits;
+            uint8_t *rowp = packed + (int64_t)row * p.row_bytes;
+            for (int64_t t = used; t < p.row_bytes; ++t) rowp[t] = 0;
+        }
+    }
+}
+
+static bool grid_encode_supported(const Problem &p) {
+    const int unit = p.block > 16 ? p.block : 16;
+    if (p.d_in % unit || p.block < 64) return false;
+    return p.bits >= 1 && p.bits <= 12;
+}
+
+template <int DTYPE, int B>
+static hipError_t launch_gdb(const void *W, int64_t ldw, const Problem &p, const SearchGridView &g, const float *norms,
+                             uint8_t *packed) {
+    const int n_slabs = (p.d_in + GSLAB - 1) / GSLAB;
+    const int64_t n_items = (int64_t)p.d_out * n_slabs;
+    if (n_items > 0x7fffffff) return hipErrorNotSupported;
+    const unsigned blocks = (unsigned)((n_items + GF_WAVES - 1) / GF_WAVES);
+    const size_t lds = (size_t)p.K * sizeof(float2);
+    hipLaunchKernelGGL((k_encode_grid<DTYPE, B>), dim3(blocks), dim3(GF_THREADS), lds, p.stream, W, ldw, p,
+                       reinterpret_cast<const uint32_t *>(g.table), g.G, norms, packed, n_slabs, (int)n_items);
+    return hipGetLastError();
+}
+
+template <int DTYPE>
+static hipError_t launch_gd(const void *W, int64_t ldw, const Problem &p, const SearchGridView &g, const float *norms,
+                            uint8_t *packed) {
+    switch (p.block) {
+        case 64: return launch_gdb<DTYPE, 64>(W, ldw, p, g, norms, packed);
+        case 128: return launch_gdb<DTYPE, 128>(W, ldw, p, g, norms, packed);
+        case 256: return launch_gdb<DTYPE, 256>(W, ldw, p, g, norms, packed);
+        case 512: return launch_gdb<DTYPE, 512>(W, ldw, p, g, norms, packed);
+        case 1024: return launch_gdb<DTYPE, 1024>(W, ldw, p, g, norms, packed);
+        default: return hipErrorNotSupported;
+    }
+}
+
+bool grid_encode_launchable(const void *W, int dtype, int64_t ldw, const Problem &p, const SearchGridView &g) {
+    return grid_encode_supported(p) && front_alignment_ok(W, dtype, ldw, p) && g.table &&
+           ((reinterpret_cast<uintptr_t>(g.table) & 15) == 0) && g.G >= 1 && g.G <= 4096;
+}
+
+// Returns hipErrorNotSupported (nothing launched) when the shape or alignment is outside this kernel's range.
+hipError_t launch_encode_grid(const void *W, int dtype, int64_t ldw, const Problem &p, const SearchGridView &g,
+                              const float *norms, uint8_t *packed) {
+    if (!grid_encode_launchable(W, dtype, ldw, p, g)) return hipErrorNotSupported;
+    return dtype == 0 ? launch_gd<0>(W, ldw, p, g, norms, packed) : launch_gd<1>(W, ldw, p, g, norms, packed);
+}
+
+}  // namespace qamw

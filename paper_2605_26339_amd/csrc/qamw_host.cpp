@@ -350,3 +350,103 @@ extern "C" int qamw_polar_codebook(int bits_a, int bits_p, float *levels_out, fl
     if (c_lm_out) *c_lm_out = D;
     return QAMW_OK;
 }
+
+// ---------------------------------------------------------------------------------------------
+// Search grid for the pruned nearest-codeword search.
+namespace {
+constexpr uint32_t GRID_MAGIC = 0x44524751u;   // "QGRD"
+constexpr int GRID_ENTRIES = 8;
+constexpr size_t GRID_HEADER_BYTES = 32;
+}  // namespace
+
+extern "C" int qamw_search_grid_size(int bits, int *cells_per_side_out, size_t *bytes_out) {
+    if (bits < 1 || bits > QAMW_MAX_BITS) return QAMW_ERR_INVALID_ARG;
+    const int G = 1 << ((bits + 1) / 2 + 2);                    // about 16-32 cells per codeword
+    if (cells_per_side_out) *cells_per_side_out = G;
+    if (bytes_out) *bytes_out = GRID_HEADER_BYTES + (size_t)G * G * GRID_ENTRIES * sizeof(uint16_t);
+    return QAMW_OK;
+}
+
+extern "C" int qamw_search_grid_build(const float *codebook, int bits, void *grid_out, size_t grid_bytes,
+                                      int *max_candidates_out, uint64_t *overflow_cells_out) {
+    int G = 0;
+    size_t need = 0;
+    if (!codebook || !grid_out || qamw_search_grid_size(bits, &G, &need) != QAMW_OK || grid_bytes < need)
+        return QAMW_ERR_INVALID_ARG;
+    const int K = 1 << bits;
+    double cmax = 0.0;
+    for (int i = 0; i < 2 * K; ++i) {
+        if (!std::isfinite(codebook[i])) return QAMW_ERR_INVALID_ARG;
+        cmax = std::max(cmax, std::fabs((double)codebook[i]));
+    }
+    // the square [-R, R)^2: a quarter wider than the codebook, so that few points fall outside
+    const double R = cmax > 0.0 ? 1.25 * cmax : 1.0;
+    const float inv_h = (float)((double)G / (2.0 * R));         // cells per unit length, as the kernel uses it
+    const double h = 1.0 / (double)inv_h;
+    // The kernel takes floor(fma(x, inv_h, G/2)) in fp32; the rounding of that fma moves a point by at most
+    // 2^-24 G cells.  Every cell is widened by four times that on each side, so that a point the kernel
+    // assigns to a cell lies in the widened cell.
+    const double margin = std::ldexp((double)G * h, -22);
+    std::vector<double> lo(G), hi(G);
+    for (int i = 0; i < G; ++i) {
+        lo[i] = ((double)i - 0.5 * G) * h - margin;
+        hi[i] = ((double)(i + 1) - 0.5 * G) * h + margin;
+    }
+    // per axis and codeword: squared smallest / largest distance from the coordinate to the cell's interval
+    std::vector<double> nx((size_t)K * G), fx((size_t)K * G), ny((size_t)K * G), fy((size_t)K * G);
+    for (int c = 0; c < K; ++c)
+        for (int a = 0; a < 2; ++a) {
+            const double v = codebook[2 * c + a];
+            double *nn = (a == 0 ? nx : ny).data() + (size_t)c * G, *ff = (a == 0 ? fx : fy).data() + (size_t)c * G;
+            for (int i = 0; i < G; ++i) {
+                const double dn = std::max(std::max(lo[i] - v, v - hi[i]), 0.0);
+                const double df = std::max(std::fabs(v - lo[i]), std::fabs(v - hi[i]));
+                nn[i] = dn * dn;
+                ff[i] = df * df;
+            }
+        }
+    uint32_t *hdr = static_cast<uint32_t *>(grid_out);
+    std::memset(hdr, 0, GRID_HEADER_BYTES);
+    hdr[0] = GRID_MAGIC;
+    hdr[1] = (uint32_t)bits;
+    hdr[2] = (uint32_t)G;
+    hdr[3] = (uint32_t)GRID_ENTRIES;
+    std::memcpy(&hdr[4], &inv_h, sizeof(float));
+    const float Rf = (float)R;
+    std::memcpy(&hdr[5], &Rf, sizeof(float));
+    uint16_t *cells = reinterpret_cast<uint16_t *>(static_cast<char *>(grid_out) + GRID_HEADER_BYTES);
+    std::vector<int> row_max(G, 0);
+    std::vector<uint64_t> row_over(G, 0);
+    parallel_tasks(G, [&](int64_t iy) {
+        std::vector<int> cand;
+        for (int ix = 0; ix < G; ++ix) {
+            // no codeword farther from every point of the cell than U can be nearest to a point of the cell
+            double U = std::numeric_limits<double>::infinity();
+            for (int c = 0; c < K; ++c) U = std::min(U, fx[(size_t)c * G + ix] + fy[(size_t)c * G + iy]);
+            // fp32 evaluation of a squared distance is within 2^-22 of it, relatively: 1e-5 covers both sides with room
+            const double lim = U * (1.0 + 1e-5) + 1e-30;
+            cand.clear();
+            for (int c = 0; c < K; ++c)
+                if (nx[(size_t)c * G + ix] + ny[(size_t)c * G + iy] <= lim) cand.push_back(c);
+            uint16_t *rec = cells + ((size_t)iy * G + ix) * GRID_ENTRIES;
+            const int n = (int)cand.size();
+            row_max[iy] = std::max(row_max[iy], n);
+            if (n <= GRID_ENTRIES) {
+                for (int j = 0; j < GRID_ENTRIES; ++j) rec[j] = (uint16_t)cand[j < n ? j : 0];
+            } else {                                            // too many: the kernel scans the whole codebook
+                for (int j = 0; j < GRID_ENTRIES - 1; ++j) rec[j] = (uint16_t)cand[j];
+                rec[GRID_ENTRIES - 1] = 0xFFFFu;
+                ++row_over[iy];
+            }
+        }
+    });
+    int mx = 0;
+    uint64_t over = 0;
+    for (int i = 0; i < G; ++i) {
+        mx = std::max(mx, row_max[i]);
+        over += row_over[i];
+    }
+    if (max_candidates_out) *max_candidates_out = mx;
+    if (overflow_cells_out) *overflow_cells_out = over;
+    return QAMW_OK;
+}

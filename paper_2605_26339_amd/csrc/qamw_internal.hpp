@@ -85,6 +85,14 @@ hipError_t run_lloyd(const float *samples, long long n, int K, float *codebook, 
                      double *mse_out, int *iters_out, hipStream_t stream);
 bool pairs_launchable(const void *W, int dtype, int64_t ldw, const Problem &p, const float *pairs);
 hipError_t launch_pairs(const void *W, int dtype, int64_t ldw, const Problem &p, const float *norms, float *pairs);
+// The pruned-search table in device memory (layout: qamw_search_grid_build) and its grid size, which follows from bits.
+struct SearchGridView {
+    const void *table;
+    int G;
+};
+bool grid_encode_launchable(const void *W, int dtype, int64_t ldw, const Problem &p, const SearchGridView &g);
+hipError_t launch_encode_grid(const void *W, int dtype, int64_t ldw, const Problem &p, const SearchGridView &g,
+                              const float *norms, uint8_t *packed);
 bool mfma_encode_supported(const Problem &p);
 hipError_t launch_encode_mfma(const void *W, int dtype, int64_t ldw, const Problem &p, const float *norms,
                               uint8_t *packed);

@@ -22,6 +22,7 @@ EXPORTS = [
     "qamw_decode_f32", "qamw_decode_batch", "qamw_set_kernel_path", "qamw_polar_codebook", "qamw_encode_polar",
     "qamw_matmul_workspace_bytes", "qamw_matmul", "qamw_matmul_batch", "qamw_encode_stats",
     "qamw_normalised_pairs", "qamw_lloyd_workspace_bytes", "qamw_lloyd_device",
+    "qamw_search_grid_size", "qamw_search_grid_build", "qamw_encode_pruned",
 ]
 
 
@@ -87,6 +88,9 @@ def lib() -> C.CDLL:
         L.qamw_lloyd_device.argtypes = [vp, u64, i32, vp, i32, C.c_double, vp, C.c_size_t, C.POINTER(C.c_double), C.POINTER(i32), vp]
         L.qamw_polar_codebook.argtypes = [i32, i32, vp, vp, C.POINTER(C.c_double)]
         L.qamw_encode_polar.argtypes = [vp, i32, i32, i32, i64, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp]
+        L.qamw_search_grid_size.argtypes = [i32, C.POINTER(i32), C.POINTER(C.c_size_t)]
+        L.qamw_search_grid_build.argtypes = [vp, i32, vp, C.c_size_t, C.POINTER(i32), C.POINTER(u64)]
+        L.qamw_encode_pruned.argtypes = [vp, i32, i32, i32, i64, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp]
         for name in EXPORTS:
             if name != "qamw_status_string":
                 getattr(L, name).restype = C.c_int
@@ -271,6 +275,51 @@ def encode(W, codebook, bits: int, block: int, chan_scale=None, signs=None, pair
     _check(lib().qamw_encode(_ptr(W), _dtype_code(W), d_out, d_in, W.stride(0), _ptr(chan_scale), _ptr(signs),
                              _ptr(pair_sigma), _ptr(codebook), bits, block, _ptr(packed), _ptr(norms),
                              _stream(stream)), "qamw_encode")
+    return packed, norms
+
+
+def search_grid_size(bits: int):
+    """(cells per side G, table bytes) of the pruned-search grid for 2^bits codewords."""
+    g, n = C.c_int(), C.c_size_t()
+    _check(lib().qamw_search_grid_size(bits, C.byref(g), C.byref(n)), "qamw_search_grid_size")
+    return int(g.value), int(n.value)
+
+
+def search_grid(codebook, bits: int):
+    """Build the pruned-search table of a codebook (host array [2^bits][2] float32).
+    Returns (table uint8 [bytes], longest candidate list, number of cells with more than 8 candidates)."""
+    cb = np.ascontiguousarray(codebook, dtype=np.float32).reshape(-1)
+    if cb.size != 2 << bits:
+        raise ValueError("codebook must hold 2^bits pairs")
+    _, n = search_grid_size(bits)
+    table = np.zeros(n, dtype=np.uint8)
+    mx, over = C.c_int(), C.c_uint64()
+    _check(lib().qamw_search_grid_build(cb.ctypes.data, bits, table.ctypes.data, C.c_size_t(n), C.byref(mx), C.byref(over)),
+           "qamw_search_grid_build")
+    return table, int(mx.value), int(over.value)
+
+
+def encode_pruned(W, codebook, grid, bits: int, block: int, chan_scale=None, signs=None, pair_sigma=None, out=None,
+                  stream=None, full_scans=None):
+    """qamw_encode with the pruned search: grid is the table of search_grid() as a CUDA uint8 tensor.
+    Returns (packed uint8 [d_out][row_bytes], row_norms float32 [d_out])."""
+    import torch
+
+    _require_cuda(W, codebook, grid, chan_scale, signs, pair_sigma, full_scans)
+    if W.dim() != 2 or W.stride(1) != 1:
+        raise ValueError("W must be 2-D with unit column stride")
+    if grid.numel() * grid.element_size() < search_grid_size(bits)[1]:
+        raise ValueError("grid table too small for these bits")
+    d_out, d_in = W.shape
+    rb = packed_row_bytes(d_in, bits)
+    if out is None:
+        packed = torch.empty((d_out, rb), dtype=torch.uint8, device=W.device)
+        norms = torch.empty(d_out, dtype=torch.float32, device=W.device)
+    else:
+        packed, norms = out
+    _check(lib().qamw_encode_pruned(_ptr(W), _dtype_code(W), d_out, d_in, W.stride(0), _ptr(chan_scale), _ptr(signs),
+                                    _ptr(pair_sigma), _ptr(codebook), bits, block, _ptr(grid), _ptr(packed), _ptr(norms),
+                                    _ptr(full_scans), _stream(stream)), "qamw_encode_pruned")
     return packed, norms
 
 

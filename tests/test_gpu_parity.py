@@ -190,6 +190,117 @@ def test_shortlist_stress(orc, codebooks, kernel_path, kind):
         say("   ", rep)
 
 
+def _grid_dev(cb, bits):
+    table, longest, overflow = qamw.search_grid(cb, bits)
+    return torch.from_numpy(table).to("cuda"), longest, overflow
+
+
+def _pruned_encode(case, grid, scans=None):
+    packed, norms = qamw.encode_pruned(case.W_dev, case.cb_dev, grid, case.bits, case.block, chan_scale=case.s_dev,
+                                       signs=case.sg_dev, pair_sigma=case.sigma_dev, full_scans=scans)
+    torch.cuda.synchronize()
+    return packed.cpu().numpy(), norms.cpu().numpy()
+
+
+# the pruned search takes the shapes of the fast front half: block >= 64, d_in a multiple of max(block, 16)
+PRUNED_SHAPES = [sh for sh in SHAPES if sh[4] >= 64]
+
+
+@pytest.mark.parametrize("seed,d_out,d_in,bits,block,dtype", PRUNED_SHAPES)
+def test_pruned_encode_matches_oracle_and_the_whole_codebook_search(orc, codebooks, seed, d_out, d_in, bits, block, dtype):
+    say(f"[pruned] seed={seed} {d_out}x{d_in} B={bits} b={block} {dtype}")
+    case = Case(orc, seed, d_out, d_in, bits, block, dtype=dtype, codebook=codebooks[bits])
+    grid, longest, overflow = _grid_dev(codebooks[bits], bits)
+    scans = torch.zeros(1, dtype=torch.int64, device="cuda")
+    packed, norms = _pruned_encode(case, grid, scans)
+    rep = {}
+    check_encode(orc, case, packed, norms, case.oracle_encode(orc), report=rep)
+    say("   ", rep, f"longest list {longest}, overflowing cells {overflow}, whole-codebook scans {int(scans.item())}")
+    # the same bytes as the encoder that searches the whole codebook, and the same on a second run
+    full_packed, full_norms = case.gpu_encode()
+    assert np.array_equal(packed, full_packed) and np.array_equal(norms, full_norms)
+    packed2, _ = _pruned_encode(case, grid)
+    assert np.array_equal(packed, packed2)
+    assert int(scans.item()) < max(64, packed.shape[0] * d_in // 2 // 20)
+
+
+@pytest.mark.parametrize("kind", ["heavy_tails", "far_codebook", "clustered", "duplicates", "wild_sigma", "zero_rows"])
+def test_pruned_search_stress(orc, codebooks, kind):
+    """Inputs that strain the cell lookup: points far outside the grid's square, a codebook far larger than
+    the data (every point in a few cells), codewords packed more densely than a record can list, exact
+    duplicates (lowest index must win), per-pair gains over six orders of magnitude, all-zero rows."""
+    say(f"[pruned stress] {kind}")
+    rng = np.random.default_rng(78)
+    bits, d_out, d_in, block = 8, 24, 2048, 128
+    cb = np.array(codebooks[8], dtype=np.float32)
+    sigma, W = "calibrated", None
+    if kind == "heavy_tails":
+        W = (rng.standard_t(1.5, (d_out, d_in))).astype(np.float32)
+        sigma = None
+    elif kind == "far_codebook":
+        cb = cb * np.float32(64.0)
+    elif kind == "clustered":
+        cb[64:] = (np.float32(0.5) + np.float32(1e-4) * rng.standard_normal((192, 2))).astype(np.float32)
+    elif kind == "duplicates":
+        cb[128:] = cb[:128]
+    elif kind == "wild_sigma":
+        sigma = (10.0 ** rng.uniform(-4.5, 1.5, d_in // 2) / np.sqrt(d_in)).astype(np.float32)
+    else:
+        W = rng.standard_normal((d_out, d_in)).astype(np.float32)
+        W[3] = 0.0
+        W[d_out - 1] = 0.0
+    case = Case(orc, 62, d_out, d_in, bits, block, dtype="bf16", codebook=cb, sigma=sigma, W=W)
+    grid, longest, overflow = _grid_dev(cb, bits)
+    scans = torch.zeros(1, dtype=torch.int64, device="cuda")
+    packed, norms = _pruned_encode(case, grid, scans)
+    n_scans, n_pairs = int(scans.item()), d_out * d_in // 2
+    say(f"    longest list {longest}, overflowing cells {overflow}, whole-codebook scans {n_scans} of {n_pairs}")
+    full_packed, full_norms = case.gpu_encode()
+    assert np.array_equal(packed, full_packed) and np.array_equal(norms, full_norms)
+    ref = case.oracle_encode(orc)
+    got = orc.unpack(packed, d_in, bits)
+    if kind == "duplicates":
+        assert np.all(ref["idx"] < 128) and np.all(got < 128)
+    else:
+        rep = {}
+        check_encode(orc, case, packed, norms, ref, report=rep)
+        say("   ", rep)
+    if kind in ("heavy_tails", "wild_sigma"):
+        assert 0 < n_scans < n_pairs                          # some points lie outside the square
+    if kind == "clustered":
+        assert overflow > 0 and n_scans > 0                  # cells near the cluster list more than a record holds
+
+
+def test_pruned_encode_full_size_matrix_sampled_rows(orc, codebooks):
+    """One matrix of the 7B configuration at full size, in the launch the bench times: every row equals the
+    whole-codebook encoder's, sampled rows equal the oracle's."""
+    d_out, d_in, bits, block = 4096, 11008, 11, 128
+    say(f"[pruned full] {d_out}x{d_in}")
+    W = synth.weight_device(991, d_out, d_in, 0.5, "bf16")
+    cb = codebooks[bits]
+    cb_dev = torch.from_numpy(cb).to("cuda")
+    s = orc.channel_scales(synth.act_rms_host(992, d_in), 0.3)
+    sg = orc.sign_mask(993, d_in)
+    s_dev, sg_dev = torch.from_numpy(s).to("cuda"), torch.from_numpy(sg).to("cuda")
+    sigma_dev = qamw.calibrate_sigma(W, block, chan_scale=s_dev, signs=sg_dev)
+    grid, _, _ = _grid_dev(cb, bits)
+    scans = torch.zeros(1, dtype=torch.int64, device="cuda")
+    packed, norms = qamw.encode_pruned(W, cb_dev, grid, bits, block, chan_scale=s_dev, signs=sg_dev, pair_sigma=sigma_dev,
+                                       full_scans=scans)
+    full_packed, full_norms = qamw.encode(W, cb_dev, bits, block, chan_scale=s_dev, signs=sg_dev, pair_sigma=sigma_dev)
+    torch.cuda.synchronize()
+    assert torch.equal(packed, full_packed) and torch.equal(norms, full_norms)
+    say(f"    whole-codebook scans: {int(scans.item())} of {d_out * d_in // 2} pairs")
+    rows = np.sort(np.random.default_rng(5).choice(d_out, 24, replace=False))
+    Wh = W[torch.from_numpy(rows).to("cuda")].float().cpu().numpy()
+    ref = orc.encode(Wh, cb, bits, block, chan_scale=s, signs=sg, pair_sigma=sigma_dev.cpu().numpy(), mode=orc.MODE_SPEC,
+                     threads=8)
+    got = orc.unpack(packed.cpu().numpy()[rows], d_in, bits)
+    diff = got != ref["idx"]
+    assert np.all((ref["d2"][diff] - ref["d1"][diff]) < 1e-6 * ref["d2"][diff])
+    assert np.array_equal(norms.cpu().numpy()[rows], ref["norms"].astype(np.float32))
+
+
 POLAR_CASES = [
     # seed d_out d_in bits_a bits_p block dtype
     (71, 21, 2048, 5, 6, 128, "bf16"),     # the 5+6 configuration the paper compares with at 11 bits
