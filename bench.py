@@ -6,6 +6,11 @@ already resident in HBM: for every matrix, pair-scale calibration (Eq. 1) and en
 rotation, nearest codeword, bit-pack), then decode of every layer to bf16 (one launch per layer).  Rank 0 prints one JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--layers L]
+                    [--decode-passes N] [--matmul M] [--polar] [--no-pruned] [--no-cpu-baseline]
+
+Beside the step: N decode-only passes over the set, one encode pass with the pruned nearest-codeword search
+(`pruned_search`; same indices, not part of `value` or of a roofline fraction), and on request the fused
+dequantise-and-multiply for M activation rows (`fused_matmul`) and the polar baseline (`polar_baseline`).
 
 Timing uses HIP events recorded on the stream the kernels are launched on.
 """
@@ -148,6 +153,7 @@ def main():
     ap.add_argument("--matmul", type=int, default=0, metavar="M",
                     help="also time the fused dequantise-and-multiply with M activation rows (1..8) over the whole set")
     ap.add_argument("--polar", action="store_true", help="also time the polar-baseline encoder at the same bits per pair")
+    ap.add_argument("--no-pruned", action="store_true", help="skip the pruned-search encoder leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -276,6 +282,44 @@ def main():
                  "encode_ms_per_pass": pol_ms, "encode_hbm_gb_per_s": in_bytes / (pol_ms * 1e-3) / 1e9,
                  "note": "same decoder as the joint code (table lookup); packed buffers are overwritten by this pass"}
 
+    # the encoder with the pruned nearest-codeword search (same indices, far fewer distance evaluations): one
+    # encode pass over the set with the pair scales already calibrated.  Not part of `value` or the roofline:
+    # the roofline accounts a search over all K codewords.
+    pruned = None
+    if not args.no_pruned:
+        t_b = time.perf_counter()
+        table, longest, overflow = qamw.search_grid(cb_host, wl.bits)
+        build_s = time.perf_counter() - t_b
+        grid = torch.from_numpy(table).to(dev)
+        first = [qamw.encode(m["W"], cb, wl.bits, wl.block, chan_scale=m["s"], signs=m["sg"], pair_sigma=m["sigma"])
+                 for m in mats[:per_layer]]                          # the whole-codebook encoder's output, first layer
+        scans_p = torch.zeros(1, dtype=torch.int64, device=dev)
+        for m in mats[:per_layer]:
+            qamw.encode_pruned(m["W"], cb, grid, wl.bits, wl.block, chan_scale=m["s"], signs=m["sg"], pair_sigma=m["sigma"],
+                               out=(m["packed"], m["norms"]), full_scans=scans_p)
+        same = all(torch.equal(m["packed"], f[0]) and torch.equal(m["norms"], f[1]) for m, f in zip(mats[:per_layer], first))
+        pr_ms = []
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for m in mats:
+                qamw.encode_pruned(m["W"], cb, grid, wl.bits, wl.block, chan_scale=m["s"], signs=m["sg"], pair_sigma=m["sigma"],
+                                   out=(m["packed"], m["norms"]))
+            e1.record()
+            e1.synchronize()
+            pr_ms.append(e0.elapsed_time(e1))
+        pr = sorted(pr_ms)[1]
+        pairs_set = sum(m["d_out"] * m["d_in"] // 2 for m in mats)
+        in_bytes = pairs_set * ((8 if wl.dtype == "f32" else 4) * 2 + wl.bits / 8.0)      # W is read twice: norms, then encode
+        pruned = {"encode_gpairs_per_s": pairs_set / (pr * 1e-3) / 1e9, "encode_ms_per_pass": pr,
+                  "encode_hbm_gb_per_s": in_bytes / (pr * 1e-3) / 1e9,
+                  "identical_to_whole_codebook_search": bool(same),
+                  "whole_codebook_scan_fraction": float(scans_p.item()) / sum(m["d_out"] * m["d_in"] // 2 for m in mats[:per_layer]),
+                  "grid_cells_per_side": qamw.search_grid_size(wl.bits)[0], "table_bytes": int(table.size),
+                  "longest_candidate_list": longest, "overflowing_cells": overflow, "table_build_s": build_s,
+                  "note": "median of 3 passes over the set (row norms + pruned-search kernel per matrix, pair scales given); "
+                          "first layer compared byte for byte with qamw_encode's output"}
+
     cal_ms = sum(e[0].elapsed_time(e[1]) for e in all_enc)
     enc_ms = sum(e[1].elapsed_time(e[2]) for e in all_enc)
     dec_ms = sum(e[0].elapsed_time(e[1]) for e in all_dec)
@@ -334,6 +378,8 @@ def main():
         result["fused_matmul"] = fused
     if polar:
         result["polar_baseline"] = polar
+    if pruned:
+        result["pruned_search"] = pruned
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, mats, cb_host)
     print(json.dumps(result))
