@@ -181,7 +181,7 @@ int qamw_lloyd_device(const float *samples, uint64_t n_samples, int bits, float 
 /* Pruned nearest-codeword search (the search step of Sec. 3.1 with fewer distance evaluations; the index is
  * the one the whole-codebook search of qamw_encode returns, bit for bit).
  *
- * qamw_search_grid_size (host): the grid has G x G cells, G = 2^(ceil(bits/2) + 2); the table takes
+ * qamw_search_grid_size (host): the grid has G x G cells, G = 2^floor((bits + 6) / 2); the table takes
  * 32 + 16 G^2 bytes.  Either output may be NULL.
  *
  * qamw_search_grid_build (host): codebook: host, 2^bits x 2 finite floats.  grid_out: host, grid_bytes >=
@@ -315,6 +315,7 @@ int qamw_matmul_batch(const qamw_matmul_item *items, int n_items, int x_dtype, i
 /* Which implementation the device entry points use: 0 = automatic (fast kernels when the shape
  * allows, otherwise the general ones), 1 = always the general kernels, 2 = as 0 but the encoder's
  * shortlist runs on the vector ALU instead of the matrix cores.  All three give the same indices.
+ * qamw_encode_pruned: 1 = every cell record read from global memory, otherwise the central cells in LDS.
  * Process-wide, for tests and measurements; returns the previous value (also for a value out of
  * range, which changes nothing). */
 int qamw_set_kernel_path(int path);

@@ -361,7 +361,7 @@ constexpr size_t GRID_HEADER_BYTES = 32;
 
 extern "C" int qamw_search_grid_size(int bits, int *cells_per_side_out, size_t *bytes_out) {
     if (bits < 1 || bits > QAMW_MAX_BITS) return QAMW_ERR_INVALID_ARG;
-    const int G = 1 << ((bits + 1) / 2 + 2);                    // about 16-32 cells per codeword
+    const int G = 1 << ((bits + 6) / 2);                        // about 16-32 cells per codeword
     if (cells_per_side_out) *cells_per_side_out = G;
     if (bytes_out) *bytes_out = GRID_HEADER_BYTES + (size_t)G * G * GRID_ENTRIES * sizeof(uint16_t);
     return QAMW_OK;

@@ -222,6 +222,13 @@ def test_pruned_encode_matches_oracle_and_the_whole_codebook_search(orc, codeboo
     packed2, _ = _pruned_encode(case, grid)
     assert np.array_equal(packed, packed2)
     assert int(scans.item()) < max(64, packed.shape[0] * d_in // 2 // 20)
+    # the kernel that reads every cell record from global memory (no central cells in LDS): the same bytes
+    prev = qamw.set_kernel_path(1)
+    try:
+        packed3, norms3 = _pruned_encode(case, grid)
+    finally:
+        qamw.set_kernel_path(prev)
+    assert np.array_equal(packed, packed3) and np.array_equal(norms, norms3)
 
 
 @pytest.mark.parametrize("kind", ["heavy_tails", "far_codebook", "clustered", "duplicates", "wild_sigma", "zero_rows"])
@@ -257,6 +264,12 @@ def test_pruned_search_stress(orc, codebooks, kind):
     say(f"    longest list {longest}, overflowing cells {overflow}, whole-codebook scans {n_scans} of {n_pairs}")
     full_packed, full_norms = case.gpu_encode()
     assert np.array_equal(packed, full_packed) and np.array_equal(norms, full_norms)
+    prev = qamw.set_kernel_path(1)                            # every cell record from global memory
+    try:
+        packed3, _ = _pruned_encode(case, grid)
+    finally:
+        qamw.set_kernel_path(prev)
+    assert np.array_equal(packed, packed3)
     ref = case.oracle_encode(orc)
     got = orc.unpack(packed, d_in, bits)
     if kind == "duplicates":

@@ -72,7 +72,7 @@ def test_every_whole_codebook_winner_is_a_candidate_of_its_cell(bits):
     cb, _, _ = qamw.train_codebook(bits, 1 << 17, 5, 40, 1e-7)
     table, longest, overflow = qamw.search_grid(cb, bits)
     b, G, inv_h, R, cells = parse(table)
-    assert b == bits and (G, len(table)) == qamw.search_grid_size(bits) and G == 1 << ((bits + 1) // 2 + 2)
+    assert b == bits and (G, len(table)) == qamw.search_grid_size(bits) and G == 1 << ((bits + 6) // 2)
     assert abs(R - 1.25 * np.abs(cb).max()) <= 1e-6 * R and abs(inv_h * 2 * R - G) <= 1e-5 * G
     K = 1 << bits
     # layout: ascending, padded with the first entry, or the overflow mark in the last slot
