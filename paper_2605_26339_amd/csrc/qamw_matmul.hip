@@ -12,9 +12,9 @@
 // for a bf16 matrix.
 //
 // Kernels: k_rotate_x (one wave per activation row and 1024-column slab, the encoder's register
-// transform) and k_qgemv: a workgroup of 4 waves owns up to 64 rows of one matrix; wave w takes
-// the 1024-column slabs w, w+4, ...; per slab it holds the slab's z in registers and walks the rows
-// in groups of 8 (the group's packed words requested together); per row it unpacks 8 indices,
+// transform) and k_qgemv: a workgroup of 4 waves owns up to 64 rows of one matrix; its work is cut
+// into (1024-column slab, 8-row group) steps, slab-major, and each wave takes a quarter of them; a
+// wave holds the current slab's z in registers (the group's packed words requested together); per row it unpacks 8 indices,
 // gathers 8 codewords from the LDS codebook and multiply-adds them into per-row, per-lane
 // accumulators.  After each group one transposing reduction (each step
 // trades half of the live sums with the lane whose number differs in one bit, so 8 sums per lane end
@@ -34,7 +34,8 @@ constexpr int GV_THREADS = 256;
 constexpr int GV_WAVES = GV_THREADS / WAVE;
 constexpr int GV_SLAB = 1024;
 constexpr int GV_RG = 8;                // rows per group: requested together, accumulated together
-constexpr int GV_GROUPS_PER_WAVE = 8;   // target number of (slab, row group) steps per wave
+constexpr int GV_STEPS_PER_WG = 32;     // target number of (slab, 8-row group) steps per workgroup: 8 per wave
+constexpr int GV_MIN_WGS = 64;          // a matrix is cut into at least this many workgroups when it has the rows
 constexpr int GV_MAX_ROWS_PER_WG = 64;
 constexpr int GV_MAX_M = 8;
 
@@ -232,8 +233,14 @@ __global__ __launch_bounds__(GV_THREADS) void k_qgemv(GemvBatch bt) {
         }
     };
 
+    // The workgroup's work is n_slabs x n_g steps (slab-major: one slab's row groups are consecutive); wave w takes
+    // the w-th quarter of them, so the waves are equally loaded whatever the slab count is.
+    const int n_steps = n_slabs * n_g;
+    const int per_wave = (n_steps + GV_WAVES - 1) / GV_WAVES;
+    const int step0 = wid * per_wave, step1 = min(n_steps, step0 + per_wave);
     float z[MT][16];
-    if (wid < n_slabs) load_z(wid, z);                          // on its way while the codebook is staged
+    int cur_slab = step0 < step1 ? step0 / n_g : -1;
+    if (cur_slab >= 0) load_z(cur_slab, z);                     // on its way while the codebook is staged
     const float2 *cbk = reinterpret_cast<const float2 *>(bt.codebook);
     for (int i = threadIdx.x; i < bt.K; i += GV_THREADS) cb_lds[i] = cbk[i];
     __syncthreads();
@@ -242,41 +249,41 @@ __global__ __launch_bounds__(GV_THREADS) void k_qgemv(GemvBatch bt) {
     for (int i = lane; i < UR * MT; i += WAVE) red[wid * UR * MT + i] = 0.0f;
     const int my_row = gv_lane_row<RG>(lane);                   // after the reduction: which of the group's rows this lane holds
 #pragma unroll 1
-    for (int slab = wid; slab < n_slabs; slab += GV_WAVES) {
+    for (int step = step0; step < step1; ++step) {
+        const int slab = step / n_g, g = step - slab * n_g;
+        if (slab != cur_slab) {
+            load_z(slab, z);
+            cur_slab = slab;
+        }
         const int sh = (int)(((unsigned)(lane_col(slab) >> 4) * BITS) & 3u) * 8;
-        const bool more_slabs = slab + GV_WAVES < n_slabs;
-#pragma unroll 1
-        for (int g = 0; g < n_g; ++g) {
-            uint32_t d[RG][4];
-            fetch(slab, g, d);
-            float acc[MT][RG];
+        uint32_t d[RG][4];
+        fetch(slab, g, d);
+        float acc[MT][RG];
 #pragma unroll
-            for (int t = 0; t < MT; ++t)
+        for (int t = 0; t < MT; ++t)
 #pragma unroll
-                for (int r = 0; r < RG; ++r) acc[t][r] = 0.0f;
+            for (int r = 0; r < RG; ++r) acc[t][r] = 0.0f;
 #pragma unroll
-            for (int r = 0; r < RG; ++r) {
-                uint32_t w[4];
-                w[0] = __builtin_amdgcn_alignbit(d[r][1], d[r][0], sh);
-                w[1] = __builtin_amdgcn_alignbit(d[r][2], d[r][1], sh);
-                w[2] = __builtin_amdgcn_alignbit(d[r][3], d[r][2], sh);
-                w[3] = d[r][3] >> sh;
+        for (int r = 0; r < RG; ++r) {
+            uint32_t w[4];
+            w[0] = __builtin_amdgcn_alignbit(d[r][1], d[r][0], sh);
+            w[1] = __builtin_amdgcn_alignbit(d[r][2], d[r][1], sh);
+            w[2] = __builtin_amdgcn_alignbit(d[r][3], d[r][2], sh);
+            w[3] = d[r][3] >> sh;
 #pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    const float2 cw = cb_lds[gv_field<BITS>(w, k)];
+            for (int k = 0; k < 8; ++k) {
+                const float2 cw = cb_lds[gv_field<BITS>(w, k)];
 #pragma unroll
-                    for (int t = 0; t < MT; ++t)
-                        acc[t][r] = __builtin_fmaf(cw.y, z[t][2 * k + 1], __builtin_fmaf(cw.x, z[t][2 * k], acc[t][r]));
-                }
-            }
-            // totals over the lanes: every lane ends with one of the group's 8 rows (8 lanes hold each); one of them adds it in
-#pragma unroll
-            for (int t = 0; t < MT; ++t) {
-                gv_reduce_rows<RG>(acc[t], lane);
-                if ((lane & 7) == 0) red[(wid * UR + g * RG + my_row) * MT + t] += acc[t][0];
+                for (int t = 0; t < MT; ++t)
+                    acc[t][r] = __builtin_fmaf(cw.y, z[t][2 * k + 1], __builtin_fmaf(cw.x, z[t][2 * k], acc[t][r]));
             }
         }
-        if (more_slabs) load_z(slab + GV_WAVES, z);
+        // totals over the lanes: every lane ends with one of the group's 8 rows (8 lanes hold each); one of them adds it in
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            gv_reduce_rows<RG>(acc[t], lane);
+            if ((lane & 7) == 0) red[(wid * UR + g * RG + my_row) * MT + t] += acc[t][0];
+        }
     }
     __syncthreads();
     // the 4 waves' sums in wave order, times the row norm
@@ -361,12 +368,14 @@ hipError_t launch_matmul_batch(const MatmulItem *items, int n, int xdtype, int m
         M.row_bytes = (((int64_t)(M.d_in / 2) * p.bits + 31) / 32) * 4;
         M.Z = reinterpret_cast<float *>(ws);
         ws += matmul_workspace_bytes(M.d_in, M.d_out, m);
-        // rows per workgroup: about GV_GROUPS_PER_WAVE (slab, row group) steps for the busiest wave, whatever d_in is
-        const int slabs_per_wave = (M.n_slabs + GV_WAVES - 1) / GV_WAVES;
-        int groups_per_wg = GV_GROUPS_PER_WAVE / slabs_per_wave;
+        // Rows per workgroup, from the matrix's own shape only (so a product gives the same bits alone and in a
+        // batch): about GV_STEPS_PER_WG (slab, row group) steps per workgroup, halved while the matrix would
+        // otherwise make fewer than GV_MIN_WGS workgroups.
+        int groups_per_wg = GV_STEPS_PER_WG / M.n_slabs;
         if (groups_per_wg < 1) groups_per_wg = 1;
+        if (groups_per_wg > GV_MAX_ROWS_PER_WG / GV_RG) groups_per_wg = GV_MAX_ROWS_PER_WG / GV_RG;
+        while (groups_per_wg > 1 && (M.d_out + groups_per_wg * GV_RG - 1) / (groups_per_wg * GV_RG) < GV_MIN_WGS) groups_per_wg >>= 1;
         M.rows_per_wg = groups_per_wg * GV_RG;
-        if (M.rows_per_wg > GV_MAX_ROWS_PER_WG) M.rows_per_wg = GV_MAX_ROWS_PER_WG;
         bt.rot_begin[i] = (int)rot;
         bt.grp_begin[i] = (int)groups;
         rot += (int64_t)m * M.n_slabs;
