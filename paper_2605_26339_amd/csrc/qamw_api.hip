@@ -204,7 +204,7 @@ int qamw_encode_pruned(const void *W, int dtype, int d_out, int d_in, int64_t ld
     p.full_scans = full_scans;
     qamw::SearchGridView g;
     g.table = grid;
-    g.variant = g_kernel_path.load() == 1 ? 1 : 0;
+    g.variant = g_kernel_path.load();
     if (qamw_search_grid_size(bits, &g.G, nullptr) != QAMW_OK) return QAMW_ERR_INVALID_ARG;
     // nothing is launched for a shape outside the kernel's range
     if (!qamw::grid_encode_launchable(W, dtype, ldw, p, g)) return QAMW_ERR_UNSUPPORTED;

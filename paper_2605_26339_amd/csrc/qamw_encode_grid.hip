@@ -392,22 +392,23 @@ static hipError_t launch_gdb(const void *W, int64_t ldw, const Problem &p, const
     const int64_t n_items = (int64_t)p.d_out * n_slabs;
     if (n_items > 0x7fffffff) return hipErrorNotSupported;
     const uint32_t *table = reinterpret_cast<const uint32_t *>(g.table);
-    const int gc = central_cells(g.G, p.K);
-    // The LDS variant pays when the central square is at least half the grid's width (+-3 sigma of the pairs for
-    // a Lloyd codebook of the unit Gaussian); at K = 4096 the LDS holds less and every record is read from memory.
-    if (g.variant == 1 || 2 * gc < g.G) {
-        const unsigned blocks = (unsigned)((n_items + GF_WAVES - 1) / GF_WAVES);
-        hipLaunchKernelGGL((k_encode_grid<DTYPE, B>), dim3(blocks), dim3(GF_THREADS), (size_t)p.K * sizeof(float2), p.stream,
-                           W, ldw, p, table, g.G, norms, packed, n_slabs, (int)n_items);
-        return hipGetLastError();
-    }
-    // one workgroup of 16 waves per CU, each wave a strided share of the items
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
         cus < 1) {
         (void)hipGetLastError();
         return hipErrorNotSupported;
     }
+    const int gc = central_cells(g.G, p.K);
+    // The LDS variant pays when the central square is at least half the grid's width (+-3 sigma of the pairs for
+    // a Lloyd codebook of the unit Gaussian; at K = 4096 the LDS holds less) and when there is enough work to
+    // amortise staging it (at least 4 items per CU); otherwise every record is read from memory.
+    if (g.variant == 1 || 2 * gc < g.G || (g.variant == 0 && n_items < 4 * (int64_t)cus)) {
+        const unsigned blocks = (unsigned)((n_items + GF_WAVES - 1) / GF_WAVES);
+        hipLaunchKernelGGL((k_encode_grid<DTYPE, B>), dim3(blocks), dim3(GF_THREADS), (size_t)p.K * sizeof(float2), p.stream,
+                           W, ldw, p, table, g.G, norms, packed, n_slabs, (int)n_items);
+        return hipGetLastError();
+    }
+    // one workgroup of 16 waves per CU, each wave a strided share of the items
     const size_t lds = (size_t)p.K * sizeof(float2) + (size_t)gc * gc * sizeof(uint2);
     if (lds > 64 * 1024) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_grid_lds<DTYPE, B>),

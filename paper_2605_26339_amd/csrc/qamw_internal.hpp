@@ -89,7 +89,7 @@ hipError_t launch_pairs(const void *W, int dtype, int64_t ldw, const Problem &p,
 struct SearchGridView {
     const void *table;
     int G;
-    int variant = 0;   // 0: central cells in LDS (the default); 1: every record from global memory
+    int variant = 0;   // 0: chosen by size; 1: every record from global memory; 2: central cells in LDS whatever the size
 };
 bool grid_encode_launchable(const void *W, int dtype, int64_t ldw, const Problem &p, const SearchGridView &g);
 hipError_t launch_encode_grid(const void *W, int dtype, int64_t ldw, const Problem &p, const SearchGridView &g,

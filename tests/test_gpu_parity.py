@@ -222,13 +222,14 @@ def test_pruned_encode_matches_oracle_and_the_whole_codebook_search(orc, codeboo
     packed2, _ = _pruned_encode(case, grid)
     assert np.array_equal(packed, packed2)
     assert int(scans.item()) < max(64, packed.shape[0] * d_in // 2 // 20)
-    # the kernel that reads every cell record from global memory (no central cells in LDS): the same bytes
-    prev = qamw.set_kernel_path(1)
-    try:
-        packed3, norms3 = _pruned_encode(case, grid)
-    finally:
-        qamw.set_kernel_path(prev)
-    assert np.array_equal(packed, packed3) and np.array_equal(norms, norms3)
+    # both kernels -- every cell record from global memory (1), the central cells in LDS (2) -- give the same bytes
+    for path in (1, 2):
+        prev = qamw.set_kernel_path(path)
+        try:
+            packed3, norms3 = _pruned_encode(case, grid)
+        finally:
+            qamw.set_kernel_path(prev)
+        assert np.array_equal(packed, packed3) and np.array_equal(norms, norms3), path
 
 
 @pytest.mark.parametrize("kind", ["heavy_tails", "far_codebook", "clustered", "duplicates", "wild_sigma", "zero_rows"])
@@ -264,12 +265,15 @@ def test_pruned_search_stress(orc, codebooks, kind):
     say(f"    longest list {longest}, overflowing cells {overflow}, whole-codebook scans {n_scans} of {n_pairs}")
     full_packed, full_norms = case.gpu_encode()
     assert np.array_equal(packed, full_packed) and np.array_equal(norms, full_norms)
-    prev = qamw.set_kernel_path(1)                            # every cell record from global memory
-    try:
-        packed3, _ = _pruned_encode(case, grid)
-    finally:
-        qamw.set_kernel_path(prev)
-    assert np.array_equal(packed, packed3)
+    for path in (1, 2):                                       # every cell record from global memory / central cells in LDS
+        prev = qamw.set_kernel_path(path)
+        try:
+            scans3 = torch.zeros(1, dtype=torch.int64, device="cuda")
+            packed3, _ = _pruned_encode(case, grid, scans3)
+        finally:
+            qamw.set_kernel_path(prev)
+        assert np.array_equal(packed, packed3), path
+        say(f"    path {path}: whole-codebook scans {int(scans3.item())}")
     ref = case.oracle_encode(orc)
     got = orc.unpack(packed, d_in, bits)
     if kind == "duplicates":
