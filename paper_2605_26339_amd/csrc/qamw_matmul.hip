@@ -174,7 +174,7 @@ __global__ __launch_bounds__(GV_THREADS) void k_qgemv(GemvBatch bt) {
     float2 *cb_lds = reinterpret_cast<float2 *>(gv_lds);        // K codewords
     float *red = gv_lds + 2 * bt.K;                             // [waves][UR rows][MT]
     const int lane = threadIdx.x & (WAVE - 1);
-    const int wid = threadIdx.x >> 6;
+    const int wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform over the wave: keeps the step bookkeeping scalar
 
     const int grp = blockIdx.x;                                 // the grid is exactly the number of workgroups
     const int mi = gv_find(bt.grp_begin, bt.n, grp);
@@ -280,9 +280,10 @@ __global__ __launch_bounds__(GV_THREADS) void k_qgemv(GemvBatch bt) {
         }
         // totals over the lanes: every lane ends with one of the group's 8 rows (8 lanes hold each); one of them adds it in
 #pragma unroll
-        for (int t = 0; t < MT; ++t) {
-            gv_reduce_rows<RG>(acc[t], lane);
-            if ((lane & 7) == 0) red[(wid * UR + g * RG + my_row) * MT + t] += acc[t][0];
+        for (int t = 0; t < MT; ++t) gv_reduce_rows<RG>(acc[t], lane);
+        if ((lane & 7) == 0) {
+#pragma unroll
+            for (int t = 0; t < MT; ++t) red[(wid * UR + g * RG + my_row) * MT + t] += acc[t][0];
         }
     }
     __syncthreads();
