@@ -19,7 +19,8 @@
 // Work split: a wave owns 512 pairs (one row's 1024-column slab).  Front half in registers as in
 // the vector-ALU encoder; the pairs are then transposed through LDS into the matrix layout
 // (lane = point of a 32-point block, lanes 0-31 / 32-63 = the two coordinates).  A chunk is the
-// lane's 16 accumulator rows {8q + 4h + t} of two consecutive 32-codeword blocks.
+// lane's 16 accumulator rows {8q + 4h + t} of two consecutive 32-codeword blocks (of one block for
+// codebooks of up to 256 points).
 #include "qamw_front.hpp"
 
 namespace qamw {
@@ -56,7 +57,9 @@ __device__ __forceinline__ float mdist2(float x0, float x1, float2 c) {
     return __builtin_fmaf(e1, e1, e0 * e0);
 }
 
-template <int DTYPE, int B>
+// CH: 32-codeword blocks per chunk.  Two halve the tracking work of the main loop; one halves the exact distances
+// of the decision stage (8 instead of 16 per lane and point), which is what matters for a small codebook.
+template <int DTYPE, int B, int CH>
 __global__ __launch_bounds__(MF_THREADS) void k_encode_mfma(const void *__restrict__ W, int64_t ldw, Problem p,
                                                             const float *__restrict__ norms,
                                                             uint8_t *__restrict__ packed, int n_slabs, int n_items) {
@@ -167,10 +170,20 @@ __global__ __launch_bounds__(MF_THREADS) void k_encode_mfma(const void *__restri
                 const float s0 = mmin3(e[0], e[1], e[2]), s1 = mmin3(e[3], e[4], e[5]), s2 = mmin3(e[6], e[7], e[8]);
                 const float s3 = mmin3(e[9], e[10], e[11]), s4 = mmin3(e[12], e[13], e[14]);
                 const float r0 = mmin3(t0, t1, t2), r1 = mmin3(t3, t4, d[15]), r2 = mmin3(s0, s1, s2), r3 = mmin3(s3, s4, e[15]);
-                const float cm = __builtin_fminf(mmin3(r0, r1, r2), r3);
-                best[pb] = (cm < m1[pb]) ? cb : best[pb];
-                m2[pb] = __builtin_amdgcn_fmed3f(m1[pb], m2[pb], cm);   // m1 <= m2: second smallest chunk minimum
-                m1[pb] = __builtin_fminf(m1[pb], cm);
+                if (CH == 2) {
+                    const float cm = __builtin_fminf(mmin3(r0, r1, r2), r3);
+                    best[pb] = (cm < m1[pb]) ? cb : best[pb];
+                    m2[pb] = __builtin_amdgcn_fmed3f(m1[pb], m2[pb], cm);   // m1 <= m2: second smallest chunk minimum
+                    m1[pb] = __builtin_fminf(m1[pb], cm);
+                } else {
+                    const float cm0 = __builtin_fminf(r0, r1), cm1 = __builtin_fminf(r2, r3);
+                    best[pb] = (cm0 < m1[pb]) ? cb : best[pb];
+                    m2[pb] = __builtin_amdgcn_fmed3f(m1[pb], m2[pb], cm0);
+                    m1[pb] = __builtin_fminf(m1[pb], cm0);
+                    best[pb] = (cm1 < m1[pb]) ? cb + 1 : best[pb];
+                    m2[pb] = __builtin_amdgcn_fmed3f(m1[pb], m2[pb], cm1);
+                    m1[pb] = __builtin_fminf(m1[pb], cm1);
+                }
             }
         }
 
@@ -185,7 +198,7 @@ __global__ __launch_bounds__(MF_THREADS) void k_encode_mfma(const void *__restri
             const float M1 = __builtin_fminf(m1[pb], o1);
             const float M2 = __builtin_fminf(__builtin_fmaxf(m1[pb], o1), __builtin_fminf(m2[pb], o2));
             const int cbb = other ? ob : best[pb];                 // first block of the best chunk ...
-            const int hb = other ? (hs ^ 1) : hs;                  // ... and which 16 rows of its two blocks
+            const int hb = other ? (hs ^ 1) : hs;                  // ... and which 16 rows of each of its blocks
             const float2 x = pts[32 * pbg + j];
             const float n1 = fabsf(x.x) + fabsf(x.y);
             const float emax = 1.91e-6f * (R + n1) * (R + n1);                   // 2^-19 (R + n1)^2
@@ -194,11 +207,11 @@ __global__ __launch_bounds__(MF_THREADS) void k_encode_mfma(const void *__restri
             const float rho = sqrtf(d2) * 1.000001f + 0.0625f;
             const float eps = 1.92e-6f * (2.0f * n1 + rho) * (2.0f * n1 + rho);
             const bool safe = (M2 - M1 > 2.0f * eps) && (emax < 1.0e-3f);
-            // this lane checks rows 8q + 4hb + t of both blocks for q = 2hs, 2hs+1 (ascending index), its partner the other two q
+            // this lane checks rows 8q + 4hb + t of the chunk's blocks for q = 2hs, 2hs+1 (ascending index), its partner the other two q
             float bd = MBIG;
             int bi = 0x7fffffff;
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
+            for (int u = 0; u < CH; ++u) {
 #pragma unroll
                 for (int qq = 0; qq < 2; ++qq) {
 #pragma unroll
@@ -278,8 +291,8 @@ bool mfma_encode_supported(const Problem &p) {
     return p.block >= 64;
 }
 
-template <int DTYPE, int B>
-static hipError_t launch_mdb(const void *W, int64_t ldw, const Problem &p, const float *norms, uint8_t *packed) {
+template <int DTYPE, int B, int CH>
+static hipError_t launch_mdbc(const void *W, int64_t ldw, const Problem &p, const float *norms, uint8_t *packed) {
     const int n_slabs = (p.d_in + MSLAB - 1) / MSLAB;
     const int64_t n_items = (int64_t)p.d_out * n_slabs;
     if (n_items > 0x7fffffff) return hipErrorNotSupported;
@@ -288,16 +301,22 @@ static hipError_t launch_mdb(const void *W, int64_t ldw, const Problem &p, const
     if (lds > 64 * 1024) {
         // More than the default 64 KB of LDS per workgroup has to be asked for (a host-side setting
         // of the current device, cheap enough to repeat on every launch).
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_mfma<DTYPE, B>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_mfma<DTYPE, B, CH>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, MF_MAX_LDS_BYTES);
         if (e != hipSuccess) {
             (void)hipGetLastError();
             return hipErrorNotSupported;
         }
     }
-    hipLaunchKernelGGL((k_encode_mfma<DTYPE, B>), dim3(blocks), dim3(MF_THREADS), lds, p.stream, W, ldw, p, norms, packed,
+    hipLaunchKernelGGL((k_encode_mfma<DTYPE, B, CH>), dim3(blocks), dim3(MF_THREADS), lds, p.stream, W, ldw, p, norms, packed,
                        n_slabs, (int)n_items);
     return hipGetLastError();
+}
+
+// one-block chunks for codebooks of up to 256 points, where the decision stage outweighs the main loop
+template <int DTYPE, int B>
+static hipError_t launch_mdb(const void *W, int64_t ldw, const Problem &p, const float *norms, uint8_t *packed) {
+    return p.K <= 256 ? launch_mdbc<DTYPE, B, 1>(W, ldw, p, norms, packed) : launch_mdbc<DTYPE, B, 2>(W, ldw, p, norms, packed);
 }
 
 template <int DTYPE>
