@@ -730,8 +730,9 @@ def test_codebook_learned_on_a_matrix_own_pairs(orc):
 def test_entry_points_can_be_captured_in_a_graph(orc, codebooks):
     """The device entry points allocate nothing and do not synchronise, so a caller can record them into a HIP
     graph: calibration, encode, batched decode and the fused product are captured once and replayed several
-    times on changing inputs, with eager work in between; every replay equals the eager result."""
-    say("[graph] capture of calibrate + encode + decode_batch + matmul_batch")
+    times on changing inputs, with eager work in between; every replay equals the eager result (and the pruned
+    search's bytes equal the whole-codebook encoder's in every replay)."""
+    say("[graph] capture of calibrate + encode + encode_pruned + decode_batch + matmul_batch")
     bits, block, m = 11, 128, 2
     cb = torch.from_numpy(codebooks[bits]).cuda()
     shapes = [(96, 2048), (40, 5632)]
@@ -747,11 +748,15 @@ def test_entry_points_can_be_captured_in_a_graph(orc, codebooks):
     dec_items = qamw.make_decode_items([(pk[i], nr[i], shapes[i][1], None, None, sig[i], out[i]) for i in range(2)])
     mm_items = qamw.make_matmul_items([(Xs[i], pk[i], nr[i], None, None, sig[i], Y[i]) for i in range(2)])
     ws_mm = torch.empty(mm_items[4], dtype=torch.uint8, device="cuda")
+    grid = torch.from_numpy(qamw.search_grid(codebooks[bits], bits)[0]).cuda()
+    pk2 = [torch.empty_like(t) for t in pk]
+    nr2 = [torch.empty_like(t) for t in nr]
 
     def work():
         for i in range(2):
             qamw.calibrate_sigma(Ws[i], block, workspace=ws_cal, out=sig[i])
             qamw.encode(Ws[i], cb, bits, block, pair_sigma=sig[i], out=(pk[i], nr[i]))
+            qamw.encode_pruned(Ws[i], cb, grid, bits, block, pair_sigma=sig[i], out=(pk2[i], nr2[i]))
         qamw.decode_batch(dec_items, cb, bits, block)
         qamw.matmul_batch(mm_items, cb, bits, block, ws_mm)
 
@@ -768,10 +773,12 @@ def test_entry_points_can_be_captured_in_a_graph(orc, codebooks):
         work()
         torch.cuda.synchronize()
         want = [t.clone() for t in pk + nr + out + Y]
-        for t in pk + nr + out + Y:
+        for t in pk + nr + out + Y + pk2 + nr2:
             t.zero_()
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
         for a, b in zip(pk + nr + out + Y, want):
             assert torch.equal(a, b), f"replay {rep} differs from the eager result"
+        for a, b in zip(pk2 + nr2, pk + nr):
+            assert torch.equal(a, b), f"replay {rep}: pruned search differs"
