@@ -224,16 +224,31 @@ __global__ __launch_bounds__(GL_THREADS) void k_encode_grid_lds(const void *__re
         return (int)floorf(fminf(fmaxf(__builtin_fmaf(v, inv_h, half_g), -1.0f), g_f));
     };
 
-    for (int item = __builtin_amdgcn_readfirstlane(blockIdx.x * GL_WAVES + wid); item < n_items;
-         item += (int)gridDim.x * GL_WAVES) {
+    // The weights of the next item are requested before the current item is searched: a wave has only three
+    // others on its SIMD to hide the HBM round trip behind.
+    const int stride = (int)gridDim.x * GL_WAVES;
+    int item = __builtin_amdgcn_readfirstlane(blockIdx.x * GL_WAVES + wid);
+    auto request = [&](int it, RawRow<DTYPE> &raw, float &norm) {
+        const int r = it / n_slabs, sl = it - r * n_slabs;
+        const int cc = sl * GSLAB + 16 * pos;
+        load_raw_row<DTYPE>(raw, W, (int64_t)r * ldw, cc < p.d_in ? cc : 0);
+        norm = norms[r];
+    };
+    RawRow<DTYPE> raw_next;
+    float norm_next = 0.0f;
+    if (item < n_items) request(item, raw_next, norm_next);
+    for (; item < n_items; item += stride) {
         const int row = item / n_slabs, slab = item - row * n_slabs;
         const int col0 = slab * GSLAB + 16 * pos;
         const bool active = col0 < p.d_in;
         const int c = active ? col0 : 0;
+        const RawRow<DTYPE> raw = raw_next;
+        const float norm = norm_next;
+        if (item + stride < n_items) request(item + stride, raw_next, norm_next);
 
         // ---------------- front half
         float x[16];
-        rotated_unit_row<DTYPE, B>(x, W, (int64_t)row * ldw, c, norms[row], p, ls);
+        rotated_unit_row_from<DTYPE, B>(x, raw, c, norm, p, ls);
         {
             float g[8];
             if (p.pair_sigma) {

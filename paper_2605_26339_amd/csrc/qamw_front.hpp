@@ -9,30 +9,44 @@
 
 namespace qamw {
 
-// c: first of the lane's 16 columns (multiple of 16, < d_in); r: the row's norm.
-// Requires 16-byte aligned rows and side arrays (checked on the host).
-template <int DTYPE, int B>
-__device__ __forceinline__ void rotated_unit_row(float (&y)[16], const void *__restrict__ W, int64_t row_base, int c,
-                                                 float r, const Problem &p, const LaneSigns<B> &ls) {
+// The lane's 16 weights as loaded: 16 fp32 (DTYPE 0) or 16 bf16 in 8 dwords (DTYPE 1).  Split from the arithmetic so that
+// a kernel can request the next row before it works on the current one.
+template <int DTYPE> struct RawRow {
+    uint32_t w[DTYPE == 0 ? 16 : 8];
+};
+template <int DTYPE>
+__device__ __forceinline__ void load_raw_row(RawRow<DTYPE> &raw, const void *__restrict__ W, int64_t row_base, int c) {
     const int64_t base = row_base + c;
     if (DTYPE == 0) {
-        const float4 *w4 = reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(W) + base);
+        const uint4 *w4 = reinterpret_cast<const uint4 *>(reinterpret_cast<const float *>(W) + base);
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            float4 v = w4[t];
-            y[4 * t] = v.x; y[4 * t + 1] = v.y; y[4 * t + 2] = v.z; y[4 * t + 3] = v.w;
+            const uint4 v = w4[t];
+            raw.w[4 * t] = v.x; raw.w[4 * t + 1] = v.y; raw.w[4 * t + 2] = v.z; raw.w[4 * t + 3] = v.w;
         }
     } else {
         const uint4 *w4 = reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(W) + base);
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            uint4 v = w4[t];
-            const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+            const uint4 v = w4[t];
+            raw.w[4 * t] = v.x; raw.w[4 * t + 1] = v.y; raw.w[4 * t + 2] = v.z; raw.w[4 * t + 3] = v.w;
+        }
+    }
+}
+
+// c: first of the lane's 16 columns (multiple of 16, < d_in); r: the row's norm.
+// Requires 16-byte aligned rows and side arrays (checked on the host).
+template <int DTYPE, int B>
+__device__ __forceinline__ void rotated_unit_row_from(float (&y)[16], const RawRow<DTYPE> &raw, int c, float r, const Problem &p,
+                                                      const LaneSigns<B> &ls) {
+    if (DTYPE == 0) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {                       // bf16 is the upper half of an fp32
-                y[8 * t + 2 * q] = __uint_as_float(u[q] << 16);
-                y[8 * t + 2 * q + 1] = __uint_as_float(u[q] & 0xFFFF0000u);
-            }
+        for (int e = 0; e < 16; ++e) y[e] = __uint_as_float(raw.w[e]);
+    } else {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {                           // bf16 is the upper half of an fp32
+            y[2 * q] = __uint_as_float(raw.w[q] << 16);
+            y[2 * q + 1] = __uint_as_float(raw.w[q] & 0xFFFF0000u);
         }
     }
     if (p.chan_scale) {
@@ -57,6 +71,14 @@ __device__ __forceinline__ void rotated_unit_row(float (&y)[16], const void *__r
     fwht_wave<B>(y, ls);
 #pragma unroll
     for (int e = 0; e < 16; ++e) y[e] = (y[e] * ls.parity) * p.inv_sqrt_block;
+}
+
+template <int DTYPE, int B>
+__device__ __forceinline__ void rotated_unit_row(float (&y)[16], const void *__restrict__ W, int64_t row_base, int c,
+                                                 float r, const Problem &p, const LaneSigns<B> &ls) {
+    RawRow<DTYPE> raw;
+    load_raw_row<DTYPE>(raw, W, row_base, c);
+    rotated_unit_row_from<DTYPE, B>(y, raw, c, r, p, ls);
 }
 
 // Host-side check of what the vector loads above assume.
