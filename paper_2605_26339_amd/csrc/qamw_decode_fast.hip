@@ -19,18 +19,15 @@ namespace qamw {
 #ifndef QAMW_DF_THREADS
 #define QAMW_DF_THREADS 256
 #endif
-#ifndef QAMW_DF_ROWS
-#define QAMW_DF_ROWS 2
-#endif
-#ifndef QAMW_DF_UNIT_ROWS
-#define QAMW_DF_UNIT_ROWS 16
-#endif
 constexpr int DF_THREADS = QAMW_DF_THREADS;
 constexpr int DF_WAVES = DF_THREADS / WAVE;
 constexpr int SLAB = 1024;
 constexpr int DF_MAX_BATCH = QAMW_DECODE_MAX_BATCH;
-constexpr int DF_ROWS = QAMW_DF_ROWS;            // rows a wave has in flight at a time
-constexpr int DF_UNIT_ROWS = QAMW_DF_UNIT_ROWS;  // rows of one unit of work (a multiple of DF_ROWS)
+// Rows of one unit of work: a wave requests the packed words of all of them at the start, in two halves, and
+// computes and stores one half while the other is still on its way.  Small units mean many waves per launch and a
+// short dependent chain per wave; measured best (7B and 13B shapes): 8 rows at 11 bits (704 packed bytes per row
+// and slab), 16 rows at 7 and 8 bits (448 / 512 bytes).
+constexpr int df_unit_rows(int bits) { return bits >= 10 ? 8 : 16; }
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float floatx2_t __attribute__((ext_vector_type(2)));
@@ -105,7 +102,7 @@ struct DecodeMat {
     float sigma_default;                  // 1/sqrt(d_in), used when pair_sigma is NULL
 };
 
-// Work list of one launch.  A unit is (matrix, group of DF_UNIT_ROWS rows, slab), numbered matrix-major,
+// Work list of one launch.  A unit is (matrix, group of df_unit_rows(bits) rows, slab), numbered matrix-major,
 // then row-group-major, slab fastest: unit numbers follow memory order.
 struct DecodeBatch {
     DecodeMat m[DF_MAX_BATCH];
@@ -117,14 +114,15 @@ struct DecodeBatch {
 };
 
 // Decode kernel over a batch of matrices.  A block (4 waves) stages the codebook into LDS once; wave w
-// of the grid takes unit w: DF_UNIT_ROWS rows of one 1024-column slab, with the slab's column constants
+// of the grid takes unit w: 2R rows of one 1024-column slab, with the slab's column constants
 // loaded once.  Units are numbered in memory order and blocks are dispatched in that order, which
-// keeps the reads and writes in flight close together in HBM.  The row loop is software pipelined:
-// the packed words of the next R rows are requested before the current R rows are computed and
-// stored, so a wave never waits for its own stores to drain before its next loads are under way
-// (loads and stores retire through one in-order counter on this chip).
+// keeps the reads and writes in flight close together in HBM.  The packed words of both halves of
+// the unit are requested before anything is stored, so a wave never waits for its own stores to
+// drain before its loads are under way (loads and stores retire through one in-order counter on
+// this chip).
 template <int BITS, int B, bool OUT_BF16, int R>
 __global__ __launch_bounds__(DF_THREADS) void k_decode_fast(DecodeBatch bt, int n_waves) {
+    constexpr int UNIT = 2 * R;                                 // rows of a unit: two halves of R rows
     extern __shared__ float2 cb_lds[];                          // K codewords
     typedef u32x4_t u32x4_a4_t __attribute__((aligned(4)));     // a 16-byte load that is only 4-byte aligned
     const int lane = threadIdx.x & (WAVE - 1);
@@ -148,7 +146,7 @@ __global__ __launch_bounds__(DF_THREADS) void k_decode_fast(DecodeBatch bt, int 
     const int n_slabs = M.n_slabs;
     // the division runs on the vector ALU; readfirstlane returns the (uniform) results to scalar registers
     const int slab = __builtin_amdgcn_readfirstlane(local % n_slabs);
-    const int row0 = __builtin_amdgcn_readfirstlane((local / n_slabs) * DF_UNIT_ROWS);
+    const int row0 = __builtin_amdgcn_readfirstlane((local / n_slabs) * UNIT);
     const int d_in = M.d_in, last_row = M.d_out - 1;
     const int64_t row_bytes = M.row_bytes, ldo = M.ldo;
     const uint8_t *packed = M.packed;
@@ -251,21 +249,15 @@ __global__ __launch_bounds__(DF_THREADS) void k_decode_fast(DecodeBatch bt, int 
                 }
             }
         };
-        // two buffers, used alternately: rows sub .. sub+R-1 are computed while the next R rows are on their way
+        // both halves are requested before the first is used: the second arrives while the first is computed and stored
         uint32_t d0[R][4], d1[R][4];
         float rn0[R], rn1[R];
         fetch(0, d0, rn0);
-        for (int sub = 0; sub < DF_UNIT_ROWS; sub += 2 * R) {
-            if (!FULL && row0 + sub > last_row) break;
-            if (FULL || row0 + sub + R <= last_row) fetch(sub + R, d1, rn1);
-            rows(sub, d0, rn0);
-            if (!FULL && row0 + sub + R > last_row) break;
-            if (sub + 2 * R < DF_UNIT_ROWS && (FULL || row0 + sub + 2 * R <= last_row)) fetch(sub + 2 * R, d0, rn0);
-            rows(sub + R, d1, rn1);
-        }
+        if (FULL || row0 + R <= last_row) fetch(R, d1, rn1);
+        rows(0, d0, rn0);
+        if (FULL || row0 + R <= last_row) rows(R, d1, rn1);
     };
-    static_assert(DF_UNIT_ROWS % (2 * R) == 0, "the row loop handles two groups of R rows per trip");
-    if (slab_cols == SLAB && row0 + DF_UNIT_ROWS <= last_row)
+    if (slab_cols == SLAB && row0 + UNIT <= last_row)
         run(std::true_type{});
     else
         run(std::false_type{});
@@ -290,6 +282,7 @@ static bool decode_alignment_ok(const DecodeItem &it, bool out_bf16) {
 
 template <int BITS, int B>
 static hipError_t launch_bb(const DecodeItem *items, int n, const Problem &p, bool out_bf16) {
+    constexpr int UNIT = df_unit_rows(BITS), R = UNIT / 2;
     DecodeBatch bt;
     int64_t units = 0;
     for (int i = 0; i < n; ++i) {
@@ -307,7 +300,7 @@ static hipError_t launch_bb(const DecodeItem *items, int n, const Problem &p, bo
         M.n_slabs = (M.d_in + SLAB - 1) / SLAB;
         M.sigma_default = (float)(1.0 / std::sqrt((double)M.d_in));
         bt.unit_begin[i] = (int)units;
-        units += (int64_t)M.n_slabs * ((M.d_out + DF_UNIT_ROWS - 1) / DF_UNIT_ROWS);
+        units += (int64_t)M.n_slabs * ((M.d_out + UNIT - 1) / UNIT);
         if (units > 0x3fffffff) return hipErrorNotSupported;
     }
     for (int i = n; i <= DF_MAX_BATCH; ++i) bt.unit_begin[i] = (int)units;
@@ -322,9 +315,9 @@ static hipError_t launch_bb(const DecodeItem *items, int n, const Problem &p, bo
     const unsigned blocks = (unsigned)((n_waves + DF_WAVES - 1) / DF_WAVES);
     const size_t lds = (size_t)p.K * sizeof(float2);
     if (out_bf16)
-        hipLaunchKernelGGL((k_decode_fast<BITS, B, true, DF_ROWS>), dim3(blocks), dim3(DF_THREADS), lds, p.stream, bt, (int)n_waves);
+        hipLaunchKernelGGL((k_decode_fast<BITS, B, true, R>), dim3(blocks), dim3(DF_THREADS), lds, p.stream, bt, (int)n_waves);
     else
-        hipLaunchKernelGGL((k_decode_fast<BITS, B, false, DF_ROWS>), dim3(blocks), dim3(DF_THREADS), lds, p.stream, bt, (int)n_waves);
+        hipLaunchKernelGGL((k_decode_fast<BITS, B, false, R>), dim3(blocks), dim3(DF_THREADS), lds, p.stream, bt, (int)n_waves);
     return hipGetLastError();
 }
 
