@@ -127,16 +127,16 @@ __global__ __launch_bounds__(DF_THREADS) void k_decode_fast(DecodeBatch bt, int 
     typedef u32x4_t u32x4_a4_t __attribute__((aligned(4)));     // a 16-byte load that is only 4-byte aligned
     const int lane = threadIdx.x & (WAVE - 1);
     const int wid = threadIdx.x >> 6;
-    const int wave = __builtin_amdgcn_readfirstlane(blockIdx.x * DF_WAVES + wid);
+    const int wave_id = __builtin_amdgcn_readfirstlane(blockIdx.x * DF_WAVES + wid);
     const LaneSigns<B> ls(lane);
     const int pos = slab_pos(lane);
     // after the half exchange: whose sub-block this lane stores in the first / second store instruction, and which half
     const int pos_a = slab_pos(lane & 31), pos_b = slab_pos((lane & 31) + 32), half = lane >> 5;
 
-    const float2 *cbk = reinterpret_cast<const float2 *>(bt.codebook);
-    for (int i = threadIdx.x; i < bt.K; i += DF_THREADS) cb_lds[i] = cbk[i];
-    __syncthreads();
-    if (wave >= n_waves) return;                                // n_waves = number of units; surplus waves of the last block
+    // n_waves = number of units.  A surplus wave of the last block goes through the motions on the last unit
+    // (it has to reach the barrier below) and stores nothing.
+    const bool surplus = wave_id >= n_waves;
+    const int wave = surplus ? n_waves - 1 : wave_id;
 
     // which matrix, slab and rows (all uniform over the wave)
     int mi = 0;
@@ -176,26 +176,53 @@ __global__ __launch_bounds__(DF_THREADS) void k_decode_fast(DecodeBatch bt, int 
     // FULL: every row of the unit exists and is not the matrix's last row, and the slab has all 1024
     // columns.  Then every load and store below is unconditional, which lets the compiler count them
     // (s_waitcnt vmcnt(N) with N > 0) instead of draining the stores before each wait for loads.
+    const bool full = slab_cols == SLAB && row0 + UNIT <= last_row && !surplus;
+    const bool second = full || row0 + R <= last_row;           // the unit's second half has at least one row
+    auto fetch = [&](auto full_tag, int sub, uint32_t (&d)[R][4], float (&rn)[R]) {
+        constexpr bool FULL = decltype(full_tag)::value;
+#pragma unroll
+        for (int t = 0; t < R; ++t) {
+            const int row = FULL ? row0 + sub + t : min(row0 + sub + t, last_row);   // rows past the end re-read the last row
+            const uint8_t *rowp = packed + (int64_t)row * row_bytes;
+            if (FULL || row != last_row) {
+                // 16 bytes from a 4-byte-aligned address; may run a few bytes into the next row
+                const u32x4_t v = *reinterpret_cast<const u32x4_a4_t *>(rowp + lane_b0);
+                d[t][0] = v[0]; d[t][1] = v[1]; d[t][2] = v[2]; d[t][3] = v[3];
+            } else {
+                // last row of the matrix: stay inside it (the clamped words are beyond the lane's fields)
+                const uint32_t *rw = reinterpret_cast<const uint32_t *>(rowp);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) d[t][k] = rw[min((lane_b0 >> 2) + k, row_dw - 1u)];
+            }
+            rn[t] = norms[row];
+        }
+    };
+    // Both halves of the unit are requested before anything is computed: the second arrives while the first is
+    // computed and stored.  With the longer units (7 and 8 bits) the requests go out even before the block stages
+    // the codebook; with 8-row units that would cost registers (5 instead of 6 waves per SIMD), so there they are
+    // issued after the barrier (inside run()).
+    constexpr bool EARLY = R > 4;
+    auto stage = [&]() {
+        const float2 *cbk = reinterpret_cast<const float2 *>(bt.codebook);
+        for (int i = threadIdx.x; i < bt.K; i += DF_THREADS) cb_lds[i] = cbk[i];
+        __syncthreads();
+    };
+    uint32_t d0[R][4], d1[R][4];
+    float rn0[R], rn1[R];
+    if (EARLY) {
+        if (full) {
+            fetch(std::true_type{}, 0, d0, rn0);
+            fetch(std::true_type{}, R, d1, rn1);
+        } else {
+            fetch(std::false_type{}, 0, d0, rn0);
+            if (second) fetch(std::false_type{}, R, d1, rn1);
+        }
+    }
+    stage();
+    if (surplus) return;
+
     auto run = [&](auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
-        auto fetch = [&](int sub, uint32_t (&d)[R][4], float (&rn)[R]) {
-#pragma unroll
-            for (int t = 0; t < R; ++t) {
-                const int row = FULL ? row0 + sub + t : min(row0 + sub + t, last_row);   // rows past the end re-read the last row
-                const uint8_t *rowp = packed + (int64_t)row * row_bytes;
-                if (FULL || row != last_row) {
-                    // 16 bytes from a 4-byte-aligned address; may run a few bytes into the next row
-                    const u32x4_t v = *reinterpret_cast<const u32x4_a4_t *>(rowp + lane_b0);
-                    d[t][0] = v[0]; d[t][1] = v[1]; d[t][2] = v[2]; d[t][3] = v[3];
-                } else {
-                    // last row of the matrix: stay inside it (the clamped words are beyond the lane's fields)
-                    const uint32_t *rw = reinterpret_cast<const uint32_t *>(rowp);
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) d[t][k] = rw[min((lane_b0 >> 2) + k, row_dw - 1u)];
-                }
-                rn[t] = norms[row];
-            }
-        };
         auto rows = [&](int sub, const uint32_t (&d)[R][4], const float (&rn)[R]) {
 #pragma unroll
             for (int t = 0; t < R; ++t) {
@@ -249,15 +276,14 @@ __global__ __launch_bounds__(DF_THREADS) void k_decode_fast(DecodeBatch bt, int 
                 }
             }
         };
-        // both halves are requested before the first is used: the second arrives while the first is computed and stored
-        uint32_t d0[R][4], d1[R][4];
-        float rn0[R], rn1[R];
-        fetch(0, d0, rn0);
-        if (FULL || row0 + R <= last_row) fetch(R, d1, rn1);
+        if (!EARLY) {
+            fetch(full_tag, 0, d0, rn0);
+            if (FULL || second) fetch(full_tag, R, d1, rn1);
+        }
         rows(0, d0, rn0);
-        if (FULL || row0 + R <= last_row) rows(R, d1, rn1);
+        if (FULL || second) rows(R, d1, rn1);
     };
-    if (slab_cols == SLAB && row0 + UNIT <= last_row)
+    if (full)
         run(std::true_type{});
     else
         run(std::false_type{});
