@@ -281,7 +281,8 @@ int qamw_decode_batch(const qamw_decode_item *items, int n_items, const float *c
  * X: device, m rows of d_in elements (fp32 or bf16), leading dimension ldx.  Y: device, m rows of d_out
  * floats, leading dimension ldy.  workspace: device, at least qamw_matmul_workspace_bytes() bytes, 16-byte
  * aligned, owned by the caller (the rotated activations; contents unspecified afterwards).
- * Accumulation is fp32 in a fixed order (deterministic).
+ * Accumulation is fp32 in a fixed order that depends on the matrix's shape and m only: deterministic, and the
+ * same bits whether a product is computed alone or inside a batch.
  * Errors: m outside [1, QAMW_MATMUL_MAX_ROWS], NULL pointers, workspace too small or misaligned ->
  * INVALID_ARG; ldx < d_in, ldy < d_out -> SHAPE.  Shapes: bits in {7, 8, 11}, hadamard_block >= 64, d_in a
  * multiple of max(hadamard_block, 16), packed 4-byte aligned; anything else -> QAMW_ERR_UNSUPPORTED. */
@@ -294,7 +295,7 @@ int qamw_matmul(const void *X, int x_dtype, int m, int64_t ldx, const uint8_t *p
 
 /* The same for up to QAMW_MATMUL_MAX_BATCH independent products Y_i = X_i W_i^T that share the codebook, bits,
  * hadamard_block, m and the element type of X (for instance the projections of one layer applied to their
- * inputs): three launches in all instead of three per matrix.  items: host array, read during the call only;
+ * inputs): two launches in all (rotation, products) instead of two per matrix.  items: host array, read during the call only;
  * every pointer in it is a device pointer.  workspace: at least the sum of qamw_matmul_workspace_bytes() over
  * the items, 16-byte aligned.  Errors as qamw_matmul, per item; nothing is launched if any item is rejected. */
 typedef struct qamw_matmul_item {
