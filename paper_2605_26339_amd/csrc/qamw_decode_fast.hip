@@ -202,9 +202,18 @@ __global__ __launch_bounds__(DF_THREADS) void k_decode_fast(DecodeBatch bt, int 
     // the codebook; with 8-row units that would cost registers (5 instead of 6 waves per SIMD), so there they are
     // issued after the barrier (inside run()).
     constexpr bool EARLY = R > 4;
+    // The codebook goes from memory straight into LDS (no registers on the way): wave w copies the 1 KB pieces
+    // w, w + 4, ..., lane l the 16 bytes l of a piece (the instruction places lane l's bytes at base + 16 l).
     auto stage = [&]() {
-        const float2 *cbk = reinterpret_cast<const float2 *>(bt.codebook);
-        for (int i = threadIdx.x; i < bt.K; i += DF_THREADS) cb_lds[i] = cbk[i];
+        const char *src = reinterpret_cast<const char *>(bt.codebook);
+        const int bytes = bt.K * (int)sizeof(float2);
+        for (int off = __builtin_amdgcn_readfirstlane(wid) * 1024; off < bytes; off += DF_WAVES * 1024) {
+            if (off + 16 * lane < bytes)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + off + 16 * lane),
+                                                 (__attribute__((address_space(3))) void *)(reinterpret_cast<char *>(cb_lds) + off),
+                                                 16, 0, 0);
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0): this wave's pieces have landed before the barrier
         __syncthreads();
     };
     uint32_t d0[R][4], d1[R][4];
