@@ -57,8 +57,31 @@ __device__ __forceinline__ void rotated_unit_row_from(float (&y)[16], const RawR
             y[4 * t] *= v.x; y[4 * t + 1] *= v.y; y[4 * t + 2] *= v.z; y[4 * t + 3] *= v.w;
         }
     }
+    // u = ws / r, the correctly rounded quotient.  With q = fl(1/r) correctly rounded, q0 = fl(ws q) and the exact
+    // remainder rem = ws - q0 r (one fused multiply-add), fl(q0 + rem q) IS the correctly rounded ws / r (Markstein's
+    // division theorem) as long as nothing under- or overflows on the way: r within 2^+-60 and every |ws| at least
+    // 2^-100.  A wave that holds anything else (an exact zero included) takes the plain division for all its lanes.
+    if (r > 0.0f) {
+        float amin = fminf(fabsf(y[0]), fabsf(y[1]));
 #pragma unroll
-    for (int e = 0; e < 16; ++e) y[e] = (r > 0.0f) ? y[e] / r : 0.0f;          // IEEE division
+        for (int e = 2; e < 16; e += 2) amin = fminf(amin, fminf(fabsf(y[e]), fabsf(y[e + 1])));
+        const bool plain = !(amin >= 7.8886090522e-31f) || !(r >= 8.6736173799e-19f && r <= 1.1529215046e18f);
+        if (__ballot(plain) != 0ull) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) y[e] = y[e] / r;                       // IEEE division
+        } else {
+            const float q = 1.0f / r;                                           // IEEE division, once
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const float q0 = y[e] * q;
+                const float rem = __builtin_fmaf(-q0, r, y[e]);
+                y[e] = __builtin_fmaf(rem, q, q0);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) y[e] = 0.0f;
+    }
     if (p.signs) {
         const uint4 sg = *reinterpret_cast<const uint4 *>(p.signs + c);
         const uint32_t wds[4] = {sg.x, sg.y, sg.z, sg.w};

@@ -680,6 +680,36 @@ def test_normalised_pairs_are_the_encoders_points(orc, d_out, d_in, block, dtype
     assert np.array_equal(pairs.cpu().numpy()[same], ref["x"].astype(np.float32)[same])
 
 
+@pytest.mark.parametrize("kind", ["wide_range", "zeros_and_tiny"])
+def test_row_normalisation_is_the_correctly_rounded_quotient(orc, kind):
+    """u = ws / r bit for bit (the oracle divides in IEEE arithmetic; the kernels use one reciprocal per row and a
+    fused remainder correction, and plain division where that could under- or overflow): many rows with norms
+    from 1e-25 to 1e+25, and rows that hold exact zeros and values down to 1e-38."""
+    say(f"[division] {kind}")
+    rng = np.random.default_rng(314)
+    d_out, d_in, block = 384, 4096, 128
+    W = rng.standard_normal((d_out, d_in)).astype(np.float32)
+    if kind == "wide_range":
+        W *= (10.0 ** rng.uniform(-25, 25, (d_out, 1))).astype(np.float32)
+        W *= (10.0 ** rng.uniform(-3, 0, (d_out, d_in))).astype(np.float32)
+    else:
+        W[rng.random((d_out, d_in)) < 0.02] = 0.0
+        tiny = rng.random((d_out, d_in)) < 0.02
+        W[tiny] = (W[tiny] * 1e-30 * 10.0 ** rng.uniform(-8, 0, int(tiny.sum()))).astype(np.float32)
+        W[5] *= np.float32(1e-22)
+    dummy = np.array([[0.0, 0.0], [1.0, 1.0]], dtype=np.float32)
+    case = Case(orc, 112, d_out, d_in, 1, block, dtype="f32", codebook=dummy, sigma=None, scale=False, W=W)
+    ref = orc.encode(case.W, dummy, 1, block, chan_scale=case.s, signs=case.sg, pair_sigma=case.sigma, want_gaps=False,
+                     want_x=True)
+    pairs, norms = qamw.normalised_pairs(case.W_dev, block, chan_scale=case.s_dev, signs=case.sg_dev, pair_sigma=case.sigma_dev)
+    torch.cuda.synchronize()
+    ref_norms = ref["norms"].astype(np.float32)
+    got_norms = norms.cpu().numpy()
+    same = got_norms == ref_norms
+    assert same.sum() >= 0.9 * d_out
+    assert np.array_equal(pairs.cpu().numpy()[same], ref["x"].astype(np.float32)[same])
+
+
 @pytest.mark.parametrize("K,iters", [(16, 1), (16, 4), (64, 12)])
 def test_device_lloyd_follows_the_oracle(orc, K, iters):
     """Same samples, same initial points, same number of iterations: the device's codebook is the oracle's
