@@ -283,10 +283,15 @@ int qamw_decode_batch(const qamw_decode_item *items, int n_items, const float *c
  * aligned, owned by the caller (the rotated activations; contents unspecified afterwards).
  * Accumulation is fp32 in a fixed order that depends on the matrix's shape and m only: deterministic, and the
  * same bits whether a product is computed alone or inside a batch.
+ * m <= QAMW_MATMUL_VECTOR_ROWS: all arithmetic in fp32 on the vector ALU (error about 1e-8 ||x|| ||w_i||).
+ * m > QAMW_MATMUL_VECTOR_ROWS: the products run on the bf16 matrix cores -- z and the codewords are rounded to
+ * bf16 (round to nearest even), products are exact, accumulation is fp32: what the paper's pipeline
+ * (dequantise to bf16, then a bf16 matmul) does to its operands, in the rotated domain; the error is about
+ * 2^-9 per operand.  This path also needs d_in a multiple of 256 and 8-byte aligned packed rows.
  * Errors: m outside [1, QAMW_MATMUL_MAX_ROWS], NULL pointers, workspace too small or misaligned ->
  * INVALID_ARG; ldx < d_in, ldy < d_out -> SHAPE.  Shapes: bits in {7, 8, 11}, hadamard_block >= 64, d_in a
  * multiple of max(hadamard_block, 16), packed 4-byte aligned; anything else -> QAMW_ERR_UNSUPPORTED. */
-enum { QAMW_MATMUL_MAX_ROWS = 8, QAMW_MATMUL_MAX_BATCH = 16 };
+enum { QAMW_MATMUL_MAX_ROWS = 64, QAMW_MATMUL_VECTOR_ROWS = 8, QAMW_MATMUL_MAX_BATCH = 16 };
 int qamw_matmul_workspace_bytes(int d_in, int d_out, int m, size_t *bytes_out);
 int qamw_matmul(const void *X, int x_dtype, int m, int64_t ldx, const uint8_t *packed, const float *row_norms,
                 int d_out, int d_in, const float *chan_scale, const int8_t *signs, const float *pair_sigma,

@@ -37,9 +37,17 @@ constexpr int GV_RG = 8;                // rows per group: requested together, a
 constexpr int GV_STEPS_PER_WG = 32;     // target number of (slab, 8-row group) steps per workgroup: 8 per wave
 constexpr int GV_MIN_WGS = 64;          // a matrix is cut into at least this many workgroups when it has the rows
 constexpr int GV_MAX_ROWS_PER_WG = 64;
-constexpr int GV_MAX_M = 8;
+constexpr int GV_MAX_M = 8;                // activation rows of the vector-ALU kernel
+constexpr int GM_MAX_M = 64;               // ... of the matrix-core kernel (QAMW_MATMUL_MAX_ROWS of the public header)
+constexpr int GM_ROWS = 64;                // weight rows of a workgroup: two 32-row tiles
+constexpr int GM_CHUNK = 256;              // columns of one step of a wave: 2 halves x 16 instructions x 8 columns
 
 typedef uint32_t gv_u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t gv_u32x2_t __attribute__((ext_vector_type(2)));
+typedef float gv_f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 gv_bf16x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 gv_bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float gv_f32x16_t __attribute__((ext_vector_type(16)));
 
 // One product of a batch, as the kernels see it.  Z and partial point into the caller's workspace.
 struct GemvMat {
@@ -60,6 +68,7 @@ struct GemvBatch {
     int rot_begin[QAMW_MATMUL_MAX_BATCH + 1];
     int grp_begin[QAMW_MATMUL_MAX_BATCH + 1];
     int n, m, K;
+    int z_bf16;                            // 1: k_rotate_x writes bf16 rows, padded with zero rows to a multiple of 32 (matrix-core kernel)
     float inv_sqrt_block;
     const float *codebook;
 };
@@ -69,7 +78,15 @@ __device__ __forceinline__ int gv_find(const int *begin, int n, int u) {
     return i;
 }
 
-// z = sigma (.) F S (x / s) for every activation row, fp32, row-major [m][d_in].
+// Where the matrix-core kernel keeps 8 consecutive bf16 columns col .. col+7 (col a multiple of 8) of activation row tok:
+// in the order its B operand is read -- [32-row tile][256-column chunk][half of the chunk][instruction 0..15][row in the
+// tile][8 columns] -- so that the 32 lanes of a half-wave load 512 consecutive bytes.  In elements.
+__device__ __forceinline__ int64_t gm_z_offset(int tok, int col, int d_in) {
+    const int tile = tok >> 5, r = tok & 31, ch = col >> 8, within = col & 255, h = within >> 7, j = (within & 127) >> 3;
+    return ((((int64_t)tile * (d_in >> 8) + ch) * 2 + h) * 16 + j) * 256 + r * 8;
+}
+
+// z = sigma (.) F S (x / s) for every activation row: fp32, row-major [m][d_in], or bf16 in the order above.
 template <int XDTYPE, int B>
 __global__ __launch_bounds__(GV_THREADS) void k_rotate_x(GemvBatch bt) {
     const int lane = threadIdx.x & (WAVE - 1);
@@ -82,6 +99,15 @@ __global__ __launch_bounds__(GV_THREADS) void k_rotate_x(GemvBatch bt) {
     const int n_slabs = M.n_slabs;
     const int tok = __builtin_amdgcn_readfirstlane(local / n_slabs), slab = __builtin_amdgcn_readfirstlane(local % n_slabs);
     const int d_in = M.d_in;
+    if (tok >= bt.m) {                                          // a padding row of the bf16 layout: zeros
+        const int col = slab * GV_SLAB + 16 * lane;
+        if (col < d_in) {
+            uint16_t *zb = reinterpret_cast<uint16_t *>(M.Z);
+            *reinterpret_cast<uint4 *>(zb + gm_z_offset(tok, col, d_in)) = make_uint4(0, 0, 0, 0);
+            *reinterpret_cast<uint4 *>(zb + gm_z_offset(tok, col + 8, d_in)) = make_uint4(0, 0, 0, 0);
+        }
+        return;
+    }
     const float *chan_scale = M.chan_scale, *pair_sigma = M.pair_sigma;
     const int8_t *signs = M.signs;
     const LaneSigns<B> ls(lane);
@@ -107,10 +133,20 @@ __global__ __launch_bounds__(GV_THREADS) void k_rotate_x(GemvBatch bt) {
         const float sg = pair_sigma ? pair_sigma[(c + e) >> 1] : sigma_default;
         y[e] = ((y[e] * ls.parity) * bt.inv_sqrt_block) * sg;
     }
-    if (active) {
+    if (active && !bt.z_bf16) {
         float4 *dst = reinterpret_cast<float4 *>(M.Z + (int64_t)tok * d_in + c);
 #pragma unroll
         for (int t = 0; t < 4; ++t) dst[t] = make_float4(y[4 * t], y[4 * t + 1], y[4 * t + 2], y[4 * t + 3]);
+    } else if (active) {                                        // bf16, round to nearest even
+        uint32_t o[8];
+#pragma unroll
+        for (int e = 0; e < 16; e += 2) {
+            const gv_f32x2_t v = {y[e], y[e + 1]};
+            o[e >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, gv_bf16x2_t));
+        }
+        uint16_t *zb = reinterpret_cast<uint16_t *>(M.Z);
+        *reinterpret_cast<uint4 *>(zb + gm_z_offset(tok, c, d_in)) = make_uint4(o[0], o[1], o[2], o[3]);
+        *reinterpret_cast<uint4 *>(zb + gm_z_offset(tok, c + 8, d_in)) = make_uint4(o[4], o[5], o[6], o[7]);
     }
 }
 
@@ -314,16 +350,192 @@ __global__ __launch_bounds__(GV_THREADS) void k_qgemv(GemvBatch bt) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// More than 8 activation rows: the products go to the bf16 matrix cores.
+//   Y[t][i] = r_i * sum_k < bf16(c[idx_ik]), bf16(z_tk) >,   fp32 accumulation,
+// z as above but rounded to bf16 (round to nearest even) by k_rotate_x, the codewords rounded to bf16 when the
+// workgroup stages them: what a bf16 matmul on a bf16 copy of the rotated-domain operands computes.
+//
+// v_mfma_f32_32x32x16_bf16 with A = 32 weight rows x 16 columns, B = 16 columns x 32 activation rows: lane
+// (r, h) supplies row r's 8 columns of half h to A -- exactly 4 pairs, i.e. 4 codewords, each one 32-bit
+// LDS gather of (bf16 c0, bf16 c1) -- and activation row r's same 8 columns to B (16 bytes of z).
+// A workgroup of 4 waves owns 64 weight rows (two tiles); the 256-column chunks of the rows are dealt to
+// the waves in equal consecutive shares; within a chunk half h of the wave covers columns 128h .. 128h+127,
+// so a lane walks 64 consecutive pairs of its row: 8*BITS consecutive bytes, loaded as BITS 8-byte words
+// and unpacked at compile-time bit offsets.  No LDS staging of weights or activations and no barrier inside
+// the loop; the four waves' tiles are summed through LDS in wave order at the end.
+template <int BITS> __device__ __forceinline__ uint32_t gm_field_x4(const uint32_t (&w)[2 * BITS], int i) {
+    // 4 * (field i of the lane's 64-field stream): the byte offset of the codeword in the bf16 table
+    const int bit = i * BITS, word = bit >> 5, off = bit & 31;
+    const uint32_t v = (off + BITS <= 32) ? (w[word] >> off) : __builtin_amdgcn_alignbit(w[word + 1], w[word], off);
+    return (v & ((1u << BITS) - 1u)) << 2;
+}
+
+template <int BITS, int MT>
+__global__ __launch_bounds__(GV_THREADS) __attribute__((amdgpu_waves_per_eu(2, 8)))   // two workgroups per CU: at most 256 registers
+void k_qgemm(GemvBatch bt) {
+    extern __shared__ __align__(16) uint32_t gm_lds[];
+    uint32_t *cbh = gm_lds;                                     // K codewords as (bf16 c0) | (bf16 c1) << 16
+    // after the codebook: per wave a 64-row tile of packed bytes (pitch GM_PITCH<BITS>) during the loop, and, after
+    // it, the partial tiles of waves 1..3: [3 waves][2 tiles][MT][16][64 lanes]
+    float *red = reinterpret_cast<float *>(gm_lds + bt.K);
+    constexpr int PITCH = 16 * BITS + 8;                        // bytes; an odd number of 8-byte words: the lanes' 8-byte reads spread over all banks
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = lane & 31, h = lane >> 5;
+    char *tile = reinterpret_cast<char *>(gm_lds + bt.K) + (size_t)wid * (GM_ROWS * PITCH);
+
+    const int grp = blockIdx.x;
+    const int mi = gv_find(bt.grp_begin, bt.n, grp);
+    const GemvMat &M = bt.mat[mi];
+    const int row0 = (grp - bt.grp_begin[mi]) * GM_ROWS;
+    const int d_in = M.d_in, last_row = M.d_out - 1, m = bt.m;
+    const int64_t row_bytes = M.row_bytes;
+    const uint16_t *Zb = reinterpret_cast<const uint16_t *>(M.Z);
+    const int n_chunks = d_in / GM_CHUNK;
+
+    {   // stage the codebook, rounded to bf16
+        const float2 *cbk = reinterpret_cast<const float2 *>(bt.codebook);
+        for (int i = threadIdx.x; i < bt.K; i += GV_THREADS) {
+            const float2 c = cbk[i];
+            const gv_f32x2_t v = {c.x, c.y};
+            cbh[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, gv_bf16x2_t));
+        }
+        __syncthreads();
+    }
+
+
+    // The chunk's packed bytes of the workgroup's 64 rows -- BITS 16-byte pieces per row -- are loaded with consecutive
+    // lanes on consecutive pieces (piece 64 i + lane of the row-major 64 x BITS array) and laid down in LDS row by row.
+    // Rows past the end of the matrix re-read the last row (their results are not stored).
+    // (the offsets are recomputed where they are used: the vector ALU is idle here and the registers are not)
+    auto src_off = [&](int i) {
+        const int piece = 64 * i + lane, row = piece / BITS, c16 = piece - row * BITS;
+        return min(row0 + row, last_row) * (int)row_bytes + 16 * c16;
+    };
+    auto dst_off = [&](int i) {
+        const int piece = 64 * i + lane, row = piece / BITS, c16 = piece - row * BITS;
+        return row * PITCH + 16 * c16;
+    };
+    const uint16_t *zrow[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) zrow[t] = Zb + ((int64_t)t * n_chunks * 2 + h) * 16 * 256 + r * 8;   // padded rows exist and are zero
+
+    gv_f32x16_t acc[2][MT];
+#pragma unroll
+    for (int T = 0; T < 2; ++T)
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[T][t][i] = 0.0f;
+
+    // Wave w takes the chunks w, w + 4, ...: at any time the four waves read neighbouring pieces of the same rows.
+    // The packed bytes of the wave's next chunk and the activations of the current one are requested before the
+    // current chunk's matrix instructions start: with two waves per SIMD (the LDS tiles limit the workgroups per CU)
+    // nothing else would hide the memory round trips.
+    typedef gv_u32x4_t u32x4_a4_t __attribute__((aligned(4)));
+    gv_u32x4_t v[BITS];
+    if (wid < n_chunks) {
+        const uint8_t *src = M.packed + (int64_t)wid * (16 * BITS);
+#pragma unroll
+        for (int i = 0; i < BITS; ++i) v[i] = *reinterpret_cast<const u32x4_a4_t *>(src + src_off(i));
+    }
+#pragma unroll 1
+    for (int ch = wid; ch < n_chunks; ch += GV_WAVES) {
+        // the chunk's packed bytes go through LDS: written piece by piece, read back as the lane's two 64-pair streams
+#pragma unroll
+        for (int i = 0; i < BITS; ++i) {
+            gv_u32x2_t *dst = reinterpret_cast<gv_u32x2_t *>(tile + dst_off(i));
+            dst[0] = gv_u32x2_t{v[i][0], v[i][1]};
+            dst[1] = gv_u32x2_t{v[i][2], v[i][3]};
+        }
+        uint32_t w[2][2 * BITS];
+#pragma unroll
+        for (int T = 0; T < 2; ++T) {
+            const gv_u32x2_t *src = reinterpret_cast<const gv_u32x2_t *>(tile + (32 * T + r) * PITCH + 8 * BITS * h);
+#pragma unroll
+            for (int q = 0; q < BITS; ++q) {
+                const gv_u32x2_t x2 = src[q];
+                w[T][2 * q] = x2[0];
+                w[T][2 * q + 1] = x2[1];
+            }
+        }
+        // activations of this chunk: all 16 instructions' worth for one tile of activation rows (MT == 1), else 8 at a time
+        constexpr int ZB = MT == 1 ? 16 : 8;
+        gv_u32x4_t zb[MT][ZB];
+        auto load_zb = [&](int first) {
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                const uint16_t *src = zrow[t] + ((int64_t)ch * 2 * 16 + first) * 256;
+#pragma unroll
+                for (int j = 0; j < ZB; ++j) zb[t][j] = *reinterpret_cast<const gv_u32x4_t *>(src + j * 256);
+            }
+        };
+        load_zb(0);
+        if (ch + GV_WAVES < n_chunks) {                         // the next chunk's packed bytes
+            const uint8_t *src = M.packed + (int64_t)(ch + GV_WAVES) * (16 * BITS);
+#pragma unroll
+            for (int i = 0; i < BITS; ++i) v[i] = *reinterpret_cast<const u32x4_a4_t *>(src + src_off(i));
+        }
+#pragma unroll
+        for (int step = 0; step < 16; ++step) {                 // instruction of the chunk: pairs 4 step .. 4 step + 3 of the lane's 64
+            if (ZB == 8 && step == 8) load_zb(8);
+#pragma unroll
+            for (int T = 0; T < 2; ++T) {
+                gv_u32x4_t a;
+#pragma unroll
+                for (int f = 0; f < 4; ++f)
+                    a[f] = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(cbh) + gm_field_x4<BITS>(w[T], 4 * step + f));
+                const gv_bf16x8_t av = __builtin_bit_cast(gv_bf16x8_t, a);
+#pragma unroll
+                for (int t = 0; t < MT; ++t)
+                    acc[T][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(gv_bf16x8_t, zb[t][step % ZB]), acc[T][t], 0, 0, 0);
+            }
+        }
+    }
+
+    // the four waves' tiles, summed in wave order by wave 0 (the buffer overlies the packed tiles: everybody is done with those)
+    __syncthreads();
+    if (wid > 0) {
+        float *dst = red + (size_t)(wid - 1) * (2 * MT * 16 * WAVE);
+#pragma unroll
+        for (int T = 0; T < 2; ++T)
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) dst[((T * MT + t) * 16 + i) * WAVE + lane] = acc[T][t][i];
+    }
+    __syncthreads();
+    if (wid == 0) {
+#pragma unroll
+        for (int T = 0; T < 2; ++T)
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                const int tok = 32 * t + r;                     // the accumulator's column is the activation row
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    float s = acc[T][t][i];
+#pragma unroll
+                    for (int w2 = 0; w2 < GV_WAVES - 1; ++w2) s += red[(size_t)w2 * (2 * MT * 16 * WAVE) + ((T * MT + t) * 16 + i) * WAVE + lane];
+                    const int row = row0 + 32 * T + 8 * (i >> 2) + 4 * h + (i & 3);   // accumulator i of half h: tile row 8 (i / 4) + 4 h + i % 4
+                    if (tok < m && row <= last_row) M.Y[(int64_t)tok * M.ldy + row] = M.norms[row] * s;
+                }
+            }
+    }
+}
+
 bool matmul_supported(const Problem &p, int m) {
     const int unit = p.block > 16 ? p.block : 16;
     if (p.d_in % unit || p.block < 64) return false;
     if (p.bits != 7 && p.bits != 8 && p.bits != 11) return false;
-    return m >= 1 && m <= GV_MAX_M;
+    if (m > GV_MAX_M) return m <= GM_MAX_M && p.d_in % GM_CHUNK == 0;      // the matrix-core kernel walks 256-column chunks
+    return m >= 1;
 }
 
 size_t matmul_workspace_bytes(int d_in, int d_out, int m) {
     (void)d_out;
-    const size_t bytes = (size_t)m * d_in * sizeof(float);     // the rotated activations
+    // the rotated activations: fp32 rows, or (matrix-core kernel) bf16 rows padded to a multiple of 32 rows
+    const size_t bytes = m <= GV_MAX_M ? (size_t)m * d_in * sizeof(float) : (size_t)((m + 31) / 32 * 32) * d_in * sizeof(uint16_t);
     return (bytes + 15) / 16 * 16;
 }
 
@@ -351,6 +563,18 @@ static hipError_t launch_qgemv(const GemvBatch &bt, hipStream_t stream) {
     else if (bt.m <= 4) QAMW_GV(4);
     else QAMW_GV(8);
 #undef QAMW_GV
+    return hipGetLastError();
+}
+
+template <int BITS>
+static hipError_t launch_qgemm(const GemvBatch &bt, hipStream_t stream) {
+    const unsigned blocks = (unsigned)bt.grp_begin[bt.n];
+    const int mt = (bt.m + 31) / 32;
+    const size_t red_bytes = (size_t)(GV_WAVES - 1) * 2 * mt * 16 * WAVE * sizeof(float);
+    const size_t tile_bytes = (size_t)GV_WAVES * GM_ROWS * (16 * BITS + 8);
+    const size_t lds = (size_t)bt.K * sizeof(uint32_t) + (red_bytes > tile_bytes ? red_bytes : tile_bytes);
+    if (mt == 1) hipLaunchKernelGGL((k_qgemm<BITS, 1>), dim3(blocks), dim3(GV_THREADS), lds, stream, bt);
+    else hipLaunchKernelGGL((k_qgemm<BITS, 2>), dim3(blocks), dim3(GV_THREADS), lds, stream, bt);
     return hipGetLastError();
 }
 
@@ -392,9 +616,13 @@ hipError_t launch_matmul_batch(const MatmulItem *items, int n, int xdtype, int m
         if (groups_per_wg > GV_MAX_ROWS_PER_WG / GV_RG) groups_per_wg = GV_MAX_ROWS_PER_WG / GV_RG;
         while (groups_per_wg > 1 && (M.d_out + groups_per_wg * GV_RG - 1) / (groups_per_wg * GV_RG) < GV_MIN_WGS) groups_per_wg >>= 1;
         M.rows_per_wg = groups_per_wg * GV_RG;
+        if (m > GV_MAX_M) {                                     // matrix-core kernel: 64 rows per workgroup
+            if ((int64_t)M.d_out * M.row_bytes > 0x7fffffff) return hipErrorNotSupported;   // 32-bit byte offsets into the packed matrix
+            M.rows_per_wg = GM_ROWS;
+        }
         bt.rot_begin[i] = (int)rot;
         bt.grp_begin[i] = (int)groups;
-        rot += (int64_t)m * M.n_slabs;
+        rot += (int64_t)(m > GV_MAX_M ? (m + 31) / 32 * 32 : m) * M.n_slabs;
         groups += (M.d_out + M.rows_per_wg - 1) / M.rows_per_wg;
         if (groups > 0x3fffffff || rot > 0x3fffffff) return hipErrorNotSupported;
     }
@@ -408,8 +636,14 @@ hipError_t launch_matmul_batch(const MatmulItem *items, int n, int xdtype, int m
     bt.K = p.K;
     bt.inv_sqrt_block = p.inv_sqrt_block;
     bt.codebook = p.codebook;
+    bt.z_bf16 = m > GV_MAX_M ? 1 : 0;
     hipError_t e = xdtype == 0 ? launch_rotate<0>(bt, p.block, p.stream) : launch_rotate<1>(bt, p.block, p.stream);
     if (e != hipSuccess) return e;
+    if (m > GV_MAX_M) {
+        if (p.bits == 11) return launch_qgemm<11>(bt, p.stream);
+        if (p.bits == 8) return launch_qgemm<8>(bt, p.stream);
+        return launch_qgemm<7>(bt, p.stream);
+    }
     if (p.bits == 11) e = launch_qgemv<11>(bt, p.stream);
     else if (p.bits == 8) e = launch_qgemv<8>(bt, p.stream);
     else e = launch_qgemv<7>(bt, p.stream);

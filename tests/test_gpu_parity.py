@@ -445,10 +445,79 @@ def test_fused_matmul_matches_oracle(orc, codebooks, seed, d_out, d_in, bits, bl
     assert np.array_equal(Y2.cpu().numpy(), Y) and bool((out2[:, d_out:] == -3.0).all())
 
 
-def test_fused_matmul_batch_equals_single_calls(orc, codebooks):
-    """Several independent products in one call give, bit for bit, what one call per matrix gives."""
-    say("[matmul batch]")
-    bits, block, m = 11, 128, 3
+GEMM_CASES = [
+    # seed d_out d_in bits block m xdtype
+    (51, 70, 2048, 11, 128, 9, "f32"),        # a ragged last workgroup (70 = 64 + 6 rows), one token tile
+    (52, 64, 1024, 7, 256, 32, "bf16"),       # one chunk per wave
+    (53, 33, 5632, 11, 512, 40, "f32"),       # two token tiles, 22 chunks over 4 waves
+    (54, 130, 768, 8, 256, 64, "bf16"),       # fewer chunks (3) than waves
+    (55, 96, 11008, 11, 128, 17, "plain"),    # no scales, signs or sigma; 43 chunks
+]
+
+
+@pytest.mark.parametrize("seed,d_out,d_in,bits,block,m,xdtype", GEMM_CASES)
+def test_fused_matmul_on_the_matrix_cores(orc, codebooks, seed, d_out, d_in, bits, block, m, xdtype):
+    """More than 8 activation rows: Y[t][i] = r_i sum_k <bf16(c[idx_ik]), bf16(z_tk)>, fp32 accumulation, with
+    z = sigma (.) F S (x / s).  Checked against that definition evaluated in fp64 (z from the oracle's explicit-matrix
+    rotation, operands rounded to bf16 by the oracle's rounding): bar 1e-4 ||z_t|| ||c-row_i|| r_i (observed 3e-6), which absorbs
+    the few z that round the other way because the kernel forms them in fp32.  And against the exact product of
+    the decoded matrix: bar 2^-9 of the same scale (bf16 operands; observed 3e-4)."""
+    say(f"[gemm] seed={seed} {d_out}x{d_in} B={bits} b={block} m={m} x={xdtype}")
+    plain = xdtype == "plain"
+    case = Case(orc, seed, d_out, d_in, bits, block, codebook=codebooks[bits], scale=not plain, signs=not plain,
+                sigma=None if plain else "calibrated")
+    ref = case.oracle_encode(orc)
+    idx, norms = ref["idx"], ref["norms"].astype(np.float32)
+    norms[min(3, d_out - 1)] = 0.0
+    rng = np.random.default_rng(seed)
+    X = (rng.standard_normal((m, d_in)) * rng.lognormal(0, 1, d_in)[None, :]).astype(np.float32)
+    Xt = torch.from_numpy(X).cuda()
+    if xdtype == "bf16":
+        Xt = Xt.to(torch.bfloat16)
+        X = Xt.float().cpu().numpy()
+    # the rotated-domain operands in fp64
+    s = np.ones(d_in) if case.s is None else (1.0 / case.s.astype(np.float32)).astype(np.float64)      # times fl32(1/s_j)
+    sigma = np.full(d_in // 2, np.float32(1.0 / np.sqrt(d_in)), dtype=np.float64) if case.sigma is None else case.sigma.astype(np.float64)
+    z = np.stack([orc.rotate_fwd_truth(X[t].astype(np.float64) * s, block, signs=case.sg) for t in range(m)])
+    z = z * np.repeat(sigma, 2)[None, :]
+    cb = np.asarray(codebooks[bits], dtype=np.float64)
+    rows = cb[idx].reshape(d_out, d_in)                          # row i: its codewords, pair after pair
+    exact = (z @ rows.T) * norms[None, :].astype(np.float64)
+    zb = orc.bf16_bits_to_f32(orc.bf16_rne(z.astype(np.float32))).astype(np.float64)
+    cbb = orc.bf16_bits_to_f32(orc.bf16_rne(cb.astype(np.float32))).astype(np.float64)
+    rows_b = cbb[idx].reshape(d_out, d_in)
+    want = (zb @ rows_b.T) * norms[None, :].astype(np.float64)
+    # the exact product is the decoded matrix times X (the identity the vector kernel's test rests on)
+    Wt = case.oracle_decode(orc, idx, norms, mode=orc.MODE_TRUTH)["w"]
+    direct = X.astype(np.float64) @ Wt.T
+    scale = np.linalg.norm(z, axis=1)[:, None] * (np.linalg.norm(rows, axis=1) * norms)[None, :]
+    assert np.all(np.abs(exact - direct) <= 1e-6 * scale + 1e-30)
+
+    pk = torch.from_numpy(orc.pack(idx, bits)).cuda()
+    nr = torch.from_numpy(norms).cuda()
+    Y = qamw.matmul(Xt, pk, nr, case.cb_dev, bits, block, chan_scale=case.s_dev, signs=case.sg_dev, pair_sigma=case.sigma_dev)
+    torch.cuda.synchronize()
+    Y = Y.cpu().numpy().astype(np.float64)
+    e1 = np.abs(Y - want) / (scale + 1e-300)
+    e2 = np.abs(Y - exact) / (scale + 1e-300)
+    say(f"    max error / scale: vs bf16-operand definition {float(e1.max()):.2e}, vs exact {float(e2.max()):.2e}")
+    assert np.all(np.abs(Y - want) <= 1e-4 * scale + 1e-30)
+    assert np.all(np.abs(Y - exact) <= 2.0 ** -9 * scale + 1e-30)
+    assert np.all(Y[:, min(3, d_out - 1)] == 0.0)
+    # deterministic, and nothing written beyond the rows
+    out2 = torch.full((m, d_out + 5), -3.0, device="cuda")
+    Y2 = qamw.matmul(Xt, pk, nr, case.cb_dev, bits, block, chan_scale=case.s_dev, signs=case.sg_dev, pair_sigma=case.sigma_dev,
+                     out=out2[:, :d_out])
+    torch.cuda.synchronize()
+    assert np.array_equal(Y2.cpu().numpy().astype(np.float64), Y) and bool((out2[:, d_out:] == -3.0).all())
+
+
+@pytest.mark.parametrize("m", [3, 20])
+def test_fused_matmul_batch_equals_single_calls(orc, codebooks, m):
+    """Several independent products in one call give, bit for bit, what one call per matrix gives (vector kernel
+    for 3 activation rows, matrix-core kernel for 20)."""
+    say(f"[matmul batch] m={m}")
+    bits, block = 11, 128
     shapes = [(40, 2048), (17, 5632), (64, 1024), (33, 2048)]
     entries, singles = [], []
     for i, (d_out, d_in) in enumerate(shapes):
