@@ -151,7 +151,7 @@ def main():
     ap.add_argument("--decode-passes", type=int, default=10,
                     help="extra decode-only passes over the whole weight set after the timed steps (median and best reported)")
     ap.add_argument("--matmul", type=int, default=0, metavar="M",
-                    help="also time the fused dequantise-and-multiply with M activation rows (1..8) over the whole set")
+                    help="also time the fused dequantise-and-multiply with M activation rows (1..64; more than 8 run on the matrix cores) over the whole set")
     ap.add_argument("--polar", action="store_true", help="also time the polar-baseline encoder at the same bits per pair")
     ap.add_argument("--no-pruned", action="store_true", help="skip the pruned-search encoder leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
