@@ -288,11 +288,12 @@ def test_pruned_search_stress(orc, codebooks, kind):
         assert overflow > 0 and n_scans > 0                  # cells near the cluster list more than a record holds
 
 
-def test_pruned_encode_full_size_matrix_sampled_rows(orc, codebooks):
-    """One matrix of the 7B configuration at full size, in the launch the bench times: every row equals the
-    whole-codebook encoder's, sampled rows equal the oracle's."""
-    d_out, d_in, bits, block = 4096, 11008, 11, 128
-    say(f"[pruned full] {d_out}x{d_in}")
+@pytest.mark.parametrize("bits,block", [(11, 128), (7, 256)])
+def test_pruned_encode_full_size_matrix_sampled_rows(orc, codebooks, bits, block):
+    """One matrix of the 7B configurations (K = 2048 and K = 128) at full size, in the launch the bench times: every
+    row equals the whole-codebook encoder's, sampled rows equal the oracle's."""
+    d_out, d_in = 4096, 11008
+    say(f"[pruned full] {d_out}x{d_in} B={bits} b={block}")
     W = synth.weight_device(991, d_out, d_in, 0.5, "bf16")
     cb = codebooks[bits]
     cb_dev = torch.from_numpy(cb).to("cuda")
