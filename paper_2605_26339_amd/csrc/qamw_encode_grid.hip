@@ -65,16 +65,7 @@ __global__ __launch_bounds__(GF_THREADS) void k_encode_grid(const void *__restri
     rotated_unit_row<DTYPE, B>(x, W, (int64_t)row * ldw, c, norms[row], p, ls);
     {
         float g[8];
-        if (p.pair_sigma) {
-            const float4 *g4 = reinterpret_cast<const float4 *>(p.pair_sigma + (c >> 1));
-            float4 a = g4[0], b = g4[1];
-            const float sg8[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-#pragma unroll
-            for (int k = 0; k < 8; ++k) g[k] = 1.0f / sg8[k];                     // IEEE division
-        } else {
-#pragma unroll
-            for (int k = 0; k < 8; ++k) g[k] = p.g_default;
-        }
+        load_pair_gains(g, p, c);
 #pragma unroll
         for (int e = 0; e < 16; ++e) x[e] = x[e] * g[e >> 1];
     }
@@ -148,17 +139,7 @@ __global__ __launch_bounds__(GF_THREADS) void k_encode_grid(const void *__restri
 
     // ---------------- pack: the lane's 8 fields are exactly `bits` bytes, byte aligned in the row
     if (active) {
-        const int bits = p.bits;
-        uint8_t *dst = packed + (int64_t)row * p.row_bytes + (int64_t)(c >> 4) * bits;
-        unsigned __int128 acc = 0;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) acc |= (unsigned __int128)idx[k] << (k * bits);
-        for (int t = 0; t < bits; ++t) dst[t] = (uint8_t)(acc >> (8 * t));
-        if (col0 + 16 == p.d_in) {                              // last lane of the row zeroes the padding
-            const int64_t used = (int64_t)(p.d_in >> 4) * bits;
-            uint8_t *rowp = packed + (int64_t)row * p.row_bytes;
-            for (int64_t t = used; t < p.row_bytes; ++t) rowp[t] = 0;
-        }
+        store_packed_fields(packed, row, c, col0, idx, p);
     }
 }
 
@@ -251,16 +232,7 @@ __global__ __launch_bounds__(GL_THREADS) void k_encode_grid_lds(const void *__re
         rotated_unit_row_from<DTYPE, B>(x, raw, c, norm, p, ls);
         {
             float g[8];
-            if (p.pair_sigma) {
-                const float4 *g4 = reinterpret_cast<const float4 *>(p.pair_sigma + (c >> 1));
-                float4 a = g4[0], b = g4[1];
-                const float sg8[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-#pragma unroll
-                for (int k = 0; k < 8; ++k) g[k] = 1.0f / sg8[k];                 // IEEE division
-            } else {
-#pragma unroll
-                for (int k = 0; k < 8; ++k) g[k] = p.g_default;
-            }
+            load_pair_gains(g, p, c);
 #pragma unroll
             for (int e = 0; e < 16; ++e) x[e] = x[e] * g[e >> 1];
         }
@@ -379,17 +351,7 @@ __global__ __launch_bounds__(GL_THREADS) void k_encode_grid_lds(const void *__re
 
         // ---------------- pack: the lane's 8 fields are exactly `bits` bytes, byte aligned in the row
         if (active) {
-            const int bits = p.bits;
-            uint8_t *dst = packed + (int64_t)row * p.row_bytes + (int64_t)(c >> 4) * bits;
-            unsigned __int128 acc = 0;
-#pragma unroll
-            for (int k = 0; k < 8; ++k) acc |= (unsigned __int128)idx[k] << (k * bits);
-            for (int t = 0; t < bits; ++t) dst[t] = (uint8_t)(acc >> (8 * t));
-            if (col0 + 16 == p.d_in) {                          // last lane of the row zeroes the padding
-                const int64_t used = (int64_t)(p.d_in >> 4) * bits;
-                uint8_t *rowp = packed + (int64_t)row * p.row_bytes;
-                for (int64_t t = used; t < p.row_bytes; ++t) rowp[t] = 0;
-            }
+            store_packed_fields(packed, row, c, col0, idx, p);
         }
     }
 }

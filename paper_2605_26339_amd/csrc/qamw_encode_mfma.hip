@@ -110,16 +110,7 @@ __global__ __launch_bounds__(MF_THREADS) void k_encode_mfma(const void *__restri
         float x[16];
         rotated_unit_row<DTYPE, B>(x, W, (int64_t)row * ldw, c, norms[row], p, ls);
         float g[8];
-        if (p.pair_sigma) {
-            const float4 *g4 = reinterpret_cast<const float4 *>(p.pair_sigma + (c >> 1));
-            float4 a = g4[0], b = g4[1];
-            const float sg8[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-#pragma unroll
-            for (int k = 0; k < 8; ++k) g[k] = 1.0f / sg8[k];                     // IEEE division
-        } else {
-#pragma unroll
-            for (int k = 0; k < 8; ++k) g[k] = p.g_default;
-        }
+        load_pair_gains(g, p, c);
         float4 *dst = reinterpret_cast<float4 *>(pts + 8 * pos);
 #pragma unroll
         for (int k = 0; k < 8; k += 2)
@@ -267,20 +258,10 @@ __global__ __launch_bounds__(MF_THREADS) void k_encode_mfma(const void *__restri
 
     // ---------------- pack: the lane's 8 fields are exactly `bits` bytes, byte aligned in the row
     if (active) {
-        const int bits = p.bits;
         const uint4 iv = *reinterpret_cast<const uint4 *>(idxl + 8 * pos);
         const unsigned idx[8] = {iv.x & 0xffffu, iv.x >> 16, iv.y & 0xffffu, iv.y >> 16,
                                  iv.z & 0xffffu, iv.z >> 16, iv.w & 0xffffu, iv.w >> 16};
-        uint8_t *dst = packed + (int64_t)row * p.row_bytes + (int64_t)(c >> 4) * bits;
-        unsigned __int128 acc = 0;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) acc |= (unsigned __int128)idx[k] << (k * bits);
-        for (int t = 0; t < bits; ++t) dst[t] = (uint8_t)(acc >> (8 * t));
-        if (col0 + 16 == p.d_in) {                              // last lane of the row zeroes the padding
-            const int64_t used = (int64_t)(p.d_in >> 4) * bits;
-            uint8_t *rowp = packed + (int64_t)row * p.row_bytes;
-            for (int64_t t = used; t < p.row_bytes; ++t) rowp[t] = 0;
-        }
+        store_packed_fields(packed, row, c, col0, idx, p);
     }
 }
 

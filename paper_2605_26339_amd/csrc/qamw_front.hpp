@@ -104,6 +104,39 @@ __device__ __forceinline__ void rotated_unit_row(float (&y)[16], const void *__r
     rotated_unit_row_from<DTYPE, B>(y, raw, c, r, p, ls);
 }
 
+// The lane's 8 pair gains g_k = 1 / sigma_k (IEEE division), or sqrt(d_in) when no pair scales are given; c = first of
+// the lane's 16 columns.
+__device__ __forceinline__ void load_pair_gains(float (&g)[8], const Problem &p, int c) {
+    if (p.pair_sigma) {
+        const float4 *g4 = reinterpret_cast<const float4 *>(p.pair_sigma + (c >> 1));
+        const float4 a = g4[0], b = g4[1];
+        const float sg8[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int k = 0; k < 8; ++k) g[k] = 1.0f / sg8[k];                         // IEEE division
+    } else {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) g[k] = p.g_default;
+    }
+}
+
+// Writes the lane's 8 indices into the row's bit stream: 8 fields of p.bits bits are exactly p.bits bytes, byte aligned
+// at byte (c / 16) * bits of the row.  The lane that holds the row's last 16 columns (col0 + 16 == d_in) zeroes the
+// padding bytes of the row.
+__device__ __forceinline__ void store_packed_fields(uint8_t *__restrict__ packed, int row, int c, int col0,
+                                                    const unsigned (&idx)[8], const Problem &p) {
+    const int bits = p.bits;
+    uint8_t *dst = packed + (int64_t)row * p.row_bytes + (int64_t)(c >> 4) * bits;
+    unsigned __int128 acc = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc |= (unsigned __int128)idx[k] << (k * bits);
+    for (int t = 0; t < bits; ++t) dst[t] = (uint8_t)(acc >> (8 * t));
+    if (col0 + 16 == p.d_in) {
+        const int64_t used = (int64_t)(p.d_in >> 4) * bits;
+        uint8_t *rowp = packed + (int64_t)row * p.row_bytes;
+        for (int64_t t = used; t < p.row_bytes; ++t) rowp[t] = 0;
+    }
+}
+
 // Host-side check of what the vector loads above assume.
 inline bool front_alignment_ok(const void *W, int dtype, int64_t ldw, const Problem &p) {
     const int64_t row_align = dtype == 0 ? 4 : 8;
