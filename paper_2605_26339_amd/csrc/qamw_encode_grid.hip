@@ -29,11 +29,6 @@ constexpr int GF_WAVES = GF_THREADS / WAVE;
 constexpr int GSLAB = 1024;
 constexpr float GBIG = 3.0e38f;
 
-__device__ __forceinline__ float gdist2(float x0, float x1, float2 c) {
-    float e0 = x0 - c.x, e1 = x1 - c.y;
-    return __builtin_fmaf(e1, e1, e0 * e0);
-}
-
 template <int DTYPE, int B>
 __global__ __launch_bounds__(GF_THREADS) void k_encode_grid(const void *__restrict__ W, int64_t ldw, Problem p,
                                                             const uint32_t *__restrict__ table, int G,
@@ -95,7 +90,7 @@ __global__ __launch_bounds__(GF_THREADS) void k_encode_grid(const void *__restri
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const unsigned ci = cand[j] & kmask;                // (the overflow mark stays inside the codebook)
-            const float dd = gdist2(x0, x1, gcb[ci]);
+            const float dd = exact_dist2(x0, x1, gcb[ci]);
             if (dd < bd) {
                 bd = dd;
                 bi = ci;
@@ -114,25 +109,7 @@ __global__ __launch_bounds__(GF_THREADS) void k_encode_grid(const void *__restri
             const int src = __ffsll((long long)mask) - 1;
             mask &= mask - 1;
             const float x0 = __shfl(x[2 * k], src, WAVE), x1 = __shfl(x[2 * k + 1], src, WAVE);
-            float bd = GBIG;
-            int bi = 0x7fffffff;
-            for (int j = lane; j < K; j += WAVE) {
-                const float dd = gdist2(x0, x1, gcb[j]);
-                if (dd < bd) {
-                    bd = dd;
-                    bi = j;
-                }
-            }
-#pragma unroll
-            for (int m = 1; m < WAVE; m <<= 1) {
-                const float od = __shfl_xor(bd, m, WAVE);
-                const int oi = __shfl_xor(bi, m, WAVE);
-                if (od < bd || (od == bd && oi < bi)) {
-                    bd = od;
-                    bi = oi;
-                }
-            }
-            if (bi == 0x7fffffff) bi = 0;                       // every distance NaN: as the plain scan, index 0
+            const int bi = wave_exact_scan(x0, x1, gcb, K, lane);
             if (lane == src) idx[k] = (unsigned)bi;
         }
     }
@@ -281,7 +258,7 @@ __global__ __launch_bounds__(GL_THREADS) void k_encode_grid_lds(const void *__re
 #pragma unroll
             for (int j = 0; j < 5; ++j) {
                 const unsigned ci = cand[j] & kmask;
-                const float dd = gdist2(x0, x1, gcb[ci]);
+                const float dd = exact_dist2(x0, x1, gcb[ci]);
                 if (dd < bd) {
                     bd = dd;
                     bi = ci;
@@ -305,7 +282,7 @@ __global__ __launch_bounds__(GL_THREADS) void k_encode_grid_lds(const void *__re
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const unsigned ci = cand[j] & kmask;
-                const float dd = gdist2(gx[s].x, gx[s].y, gcb[ci]);
+                const float dd = exact_dist2(gx[s].x, gx[s].y, gcb[ci]);
                 if (dd < bd) {
                     bd = dd;
                     bi = ci;
@@ -326,25 +303,7 @@ __global__ __launch_bounds__(GL_THREADS) void k_encode_grid_lds(const void *__re
                 const int src = __ffsll((long long)mask) - 1;
                 mask &= mask - 1;
                 const float x0 = __shfl(x[2 * k], src, WAVE), x1 = __shfl(x[2 * k + 1], src, WAVE);
-                float bd = GBIG;
-                int bi = 0x7fffffff;
-                for (int j = lane; j < K; j += WAVE) {
-                    const float dd = gdist2(x0, x1, gcb[j]);
-                    if (dd < bd) {
-                        bd = dd;
-                        bi = j;
-                    }
-                }
-#pragma unroll
-                for (int m = 1; m < WAVE; m <<= 1) {
-                    const float od = __shfl_xor(bd, m, WAVE);
-                    const int oi = __shfl_xor(bi, m, WAVE);
-                    if (od < bd || (od == bd && oi < bi)) {
-                        bd = od;
-                        bi = oi;
-                    }
-                }
-                if (bi == 0x7fffffff) bi = 0;                   // every distance NaN: as the plain scan, index 0
+                const int bi = wave_exact_scan(x0, x1, gcb, K, lane);
                 if (lane == src) idx[k] = (unsigned)bi;
             }
         }

@@ -52,11 +52,6 @@ __device__ __forceinline__ void split3(float x, uint32_t &h, uint32_t &m, uint32
 // two bf16 (given as fp32 bit patterns with a zero low half) into one dword: `even` in the low half
 __device__ __forceinline__ uint32_t pack2(uint32_t even, uint32_t odd) { return (even >> 16) | odd; }
 
-__device__ __forceinline__ float mdist2(float x0, float x1, float2 c) {
-    float e0 = x0 - c.x, e1 = x1 - c.y;
-    return __builtin_fmaf(e1, e1, e0 * e0);
-}
-
 // CH: 32-codeword blocks per chunk.  Two halve the tracking work of the main loop; one halves the exact distances
 // of the decision stage (8 instead of 16 per lane and point), which is what matters for a small codebook.
 template <int DTYPE, int B, int CH>
@@ -208,7 +203,7 @@ __global__ __launch_bounds__(MF_THREADS) void k_encode_mfma(const void *__restri
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
                         const int ci = (cbb + u) * 32 + 8 * (2 * hs + qq) + 4 * hb + t;
-                        const float dd = mdist2(x.x, x.y, c01[ci]);
+                        const float dd = exact_dist2(x.x, x.y, c01[ci]);
                         if (dd < bd) {
                             bd = dd;
                             bi = ci;
@@ -232,24 +227,7 @@ __global__ __launch_bounds__(MF_THREADS) void k_encode_mfma(const void *__restri
                 const int src = __ffsll((long long)mask) - 1;      // a lane below 32: point src of block pbg
                 mask &= mask - 1;
                 const float2 x = pts[32 * pbg + src];
-                float bd = MBIG;
-                int bi = 0x7fffffff;
-                for (int k = lane; k < K; k += WAVE) {
-                    float dd = mdist2(x.x, x.y, c01[k]);
-                    if (dd < bd) {
-                        bd = dd;
-                        bi = k;
-                    }
-                }
-#pragma unroll
-                for (int m = 1; m < WAVE; m <<= 1) {
-                    float od = __shfl_xor(bd, m, WAVE);
-                    int oi = __shfl_xor(bi, m, WAVE);
-                    if (od < bd || (od == bd && oi < bi)) {
-                        bd = od;
-                        bi = oi;
-                    }
-                }
+                const int bi = wave_exact_scan(x.x, x.y, c01, K, lane);
                 if (lane == src) idxl[32 * pbg + src] = (uint16_t)bi;
             }
         }

@@ -104,6 +104,37 @@ __device__ __forceinline__ void rotated_unit_row(float (&y)[16], const void *__r
     rotated_unit_row_from<DTYPE, B>(y, raw, c, r, p, ls);
 }
 
+// Exact squared distance as every encoder decides with it: fma(e1, e1, e0 * e0), e = x - c.
+__device__ __forceinline__ float exact_dist2(float x0, float x1, float2 c) {
+    const float e0 = x0 - c.x, e1 = x1 - c.y;
+    return __builtin_fmaf(e1, e1, e0 * e0);
+}
+
+// The nearest of the K codewords in LDS to the point (x0, x1) (the same in all lanes), found by the whole wave: lane l
+// scans the codewords l, l + 64, ..., then a lexicographic (distance, index) reduction over the lanes; the lowest index
+// wins a tie.  Every lane returns the index (0 if every distance is NaN).
+__device__ __forceinline__ int wave_exact_scan(float x0, float x1, const float2 *cb_lds, int K, int lane) {
+    float bd = 3.0e38f;
+    int bi = 0x7fffffff;
+    for (int k = lane; k < K; k += WAVE) {
+        const float dd = exact_dist2(x0, x1, cb_lds[k]);
+        if (dd < bd) {
+            bd = dd;
+            bi = k;
+        }
+    }
+#pragma unroll
+    for (int m = 1; m < WAVE; m <<= 1) {
+        const float od = __shfl_xor(bd, m, WAVE);
+        const int oi = __shfl_xor(bi, m, WAVE);
+        if (od < bd || (od == bd && oi < bi)) {
+            bd = od;
+            bi = oi;
+        }
+    }
+    return bi == 0x7fffffff ? 0 : bi;
+}
+
 // The lane's 8 pair gains g_k = 1 / sigma_k (IEEE division), or sqrt(d_in) when no pair scales are given; c = first of
 // the lane's 16 columns.
 __device__ __forceinline__ void load_pair_gains(float (&g)[8], const Problem &p, int c) {
