@@ -22,6 +22,7 @@
 // the 4 waves' totals are summed in a fixed order, times r_i, and stored.  The row count per
 // workgroup is chosen per matrix so that every wave of a launch walks about the same number of
 // (slab, row group) steps.
+#include <algorithm>
 #include <cmath>
 
 #include "qamw_common.hpp"
@@ -586,23 +587,31 @@ hipError_t launch_matmul_batch(const MatmulItem *items, int n, int xdtype, int m
     GemvBatch bt;
     int64_t rot = 0, groups = 0;
     char *ws = static_cast<char *>(workspace);
+    // Matrix-core kernel: the products with the longest rows go first in the grid.  Their workgroups take longest (one
+    // workgroup walks whole rows); started last, they would run on alone after everything else has finished.  The
+    // order inside a launch changes no result.
+    int order[QAMW_MATMUL_MAX_BATCH];
+    for (int i = 0; i < n; ++i) order[i] = i;
+    if (m > GV_MAX_M)
+        std::stable_sort(order, order + n, [&](int a, int b) { return items[a].d_in > items[b].d_in; });
     for (int i = 0; i < n; ++i) {
+        const MatmulItem &it = items[order[i]];
         Problem q = p;
-        q.d_in = items[i].d_in;
-        q.d_out = items[i].d_out;
-        if (!matmul_supported(q, m) || (reinterpret_cast<uintptr_t>(items[i].packed) & 3)) return hipErrorNotSupported;
+        q.d_in = it.d_in;
+        q.d_out = it.d_out;
+        if (!matmul_supported(q, m) || (reinterpret_cast<uintptr_t>(it.packed) & 3)) return hipErrorNotSupported;
         GemvMat &M = bt.mat[i];
-        M.X = items[i].X;
-        M.packed = items[i].packed;
-        M.norms = items[i].norms;
-        M.chan_scale = items[i].chan_scale;
-        M.pair_sigma = items[i].pair_sigma;
-        M.signs = items[i].signs;
-        M.Y = items[i].Y;
-        M.ldx = items[i].ldx;
-        M.ldy = items[i].ldy;
-        M.d_out = items[i].d_out;
-        M.d_in = items[i].d_in;
+        M.X = it.X;
+        M.packed = it.packed;
+        M.norms = it.norms;
+        M.chan_scale = it.chan_scale;
+        M.pair_sigma = it.pair_sigma;
+        M.signs = it.signs;
+        M.Y = it.Y;
+        M.ldx = it.ldx;
+        M.ldy = it.ldy;
+        M.d_out = it.d_out;
+        M.d_in = it.d_in;
         M.n_slabs = (M.d_in + GV_SLAB - 1) / GV_SLAB;
         M.sigma_default = (float)(1.0 / std::sqrt((double)M.d_in));
         M.row_bytes = (((int64_t)(M.d_in / 2) * p.bits + 31) / 32) * 4;

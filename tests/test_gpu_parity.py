@@ -453,6 +453,7 @@ GEMM_CASES = [
     (53, 33, 5632, 11, 512, 40, "f32"),       # two token tiles, 22 chunks over 4 waves
     (54, 130, 768, 8, 256, 64, "bf16"),       # fewer chunks (3) than waves
     (55, 96, 11008, 11, 128, 17, "plain"),    # no scales, signs or sigma; 43 chunks
+    (56, 200, 8192, 7, 128, 50, "bf16"),      # 32 chunks, four row groups (the last of 8 rows), two token tiles
 ]
 
 
@@ -532,10 +533,13 @@ def test_fused_matmul_batch_equals_single_calls(orc, codebooks, m):
         cb = case.cb_dev
     items = qamw.make_matmul_items(entries)
     ws = torch.empty(items[4], dtype=torch.uint8, device="cuda")
-    qamw.matmul_batch(items, cb, bits, block, ws)
-    torch.cuda.synchronize()
-    for e, ref in zip(entries, singles):
-        assert torch.equal(e[6], ref)
+    for again in range(2):                                     # the second call finds the first one's workspace contents
+        for e in entries:
+            e[6].fill_(-1.0)
+        qamw.matmul_batch(items, cb, bits, block, ws)
+        torch.cuda.synchronize()
+        for e, ref in zip(entries, singles):
+            assert torch.equal(e[6], ref)
 
 
 def test_config0_full_matrix(orc, codebooks):
