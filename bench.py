@@ -233,15 +233,25 @@ def main():
         # them depend on each other and would go in separate calls)
         mm_batches = [qamw.make_matmul_items([(xs[m["d_in"]], m["packed"], m["norms"], m["s"], m["sg"], m["sigma"], y)
                                               for m, y in zip(mats[i:i + per_layer], ys)]) for i in range(0, len(mats), per_layer)]
-        ws_mm = torch.empty(max(b[4] for b in mm_batches), dtype=torch.uint8, device=dev)
+        # ... and as a forward pass has to issue them: one call per activation site (the products that share an
+        # input: q/k/v, o, gate/up, down), each call depending on the one before
+        site_batches = []
+        for i in range(0, len(mats), per_layer):
+            sites = []
+            for (_, _, _, site), m, y in zip(wl.matrices, mats[i:i + per_layer], ys):
+                if not sites or sites[-1][0] != site:
+                    sites.append((site, []))
+                sites[-1][1].append((xs[m["d_in"]], m["packed"], m["norms"], m["s"], m["sg"], m["sigma"], y))
+            site_batches += [qamw.make_matmul_items(entries) for _, entries in sites]
+        ws_mm = torch.empty(max(b[4] for b in mm_batches + site_batches), dtype=torch.uint8, device=dev)
         times = {}
-        for kind in ("fused", "bf16"):
+        for kind in ("fused", "by_site", "bf16"):
             best = []
             for rep in range(1 + 5):
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
-                if kind == "fused":
-                    for b in mm_batches:
+                if kind != "bf16":
+                    for b in (mm_batches if kind == "fused" else site_batches):
                         qamw.matmul_batch(b, cb, wl.bits, wl.block, ws_mm)
                 else:
                     for m in mats:
@@ -257,9 +267,10 @@ def main():
         fused = {"rows": mm, "ms_per_pass": times["fused"], "gb_per_s": fused_bytes / (times["fused"] * 1e-3) / 1e9,
                  "frac_of_hbm_peak": fused_bytes / (times["fused"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
                  "algorithmic_bytes_per_pass": fused_bytes,
+                 "ms_per_pass_one_call_per_site": times["by_site"], "calls_per_pass_by_site": len(site_batches),
                  "bf16_matmul_ms_per_pass": times["bf16"], "bf16_matmul_gb_per_s": bf16_bytes / (times["bf16"] * 1e-3) / 1e9,
                  "speedup_vs_bf16_matmul": times["bf16"] / times["fused"],
-                 "note": "median of 5 passes over the whole set, one qamw_matmul_batch call per layer; the bf16 leg is torch.matmul on the decoded matrices, one call per matrix"}
+                 "note": "median of 5 passes over the whole set, one qamw_matmul_batch call per layer (ms_per_pass) or one per activation site, the products that share an input (ms_per_pass_one_call_per_site); the bf16 leg is torch.matmul on the decoded matrices, one call per matrix"}
 
     # the polar baseline at the same rate (amplitude bits + phase bits = B): one encode pass over the set
     polar = None

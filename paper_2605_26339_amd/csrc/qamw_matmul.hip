@@ -20,8 +20,9 @@
 // trades half of the live sums with the lane whose number differs in one bit, so 8 sums per lane end
 // as one row total per lane) adds the group's totals to the wave's running totals in LDS; at the end
 // the 4 waves' totals are summed in a fixed order, times r_i, and stored.  The row count per
-// workgroup is chosen per matrix so that every wave of a launch walks about the same number of
-// (slab, row group) steps.
+// workgroup is chosen per matrix so that every wave of a launch walks about the same, small number of
+// (slab, row group) steps (about 4): a product alone in a launch -- as a forward pass issues most of them --
+// takes as long as one wave's chain of dependent loads.
 #include <algorithm>
 #include <cmath>
 
@@ -35,12 +36,14 @@ constexpr int GV_THREADS = 256;
 constexpr int GV_WAVES = GV_THREADS / WAVE;
 constexpr int GV_SLAB = 1024;
 constexpr int GV_RG = 8;                // rows per group: requested together, accumulated together
-constexpr int GV_STEPS_PER_WG = 32;     // target number of (slab, 8-row group) steps per workgroup: 8 per wave
-constexpr int GV_MIN_WGS = 64;          // a matrix is cut into at least this many workgroups when it has the rows
+constexpr int GV_STEPS_PER_WG = 16;     // target number of (slab, 8-row group) steps per workgroup: 4 per wave
+constexpr int GV_MIN_WGS = 256;         // a matrix is cut into at least this many workgroups when it has the rows
 constexpr int GV_MAX_ROWS_PER_WG = 64;
 constexpr int GV_MAX_M = 8;                // activation rows of the vector-ALU kernel
 constexpr int GM_MAX_M = 64;               // ... of the matrix-core kernel (QAMW_MATMUL_MAX_ROWS of the public header)
-constexpr int GM_ROWS = 64;                // weight rows of a workgroup: two 32-row tiles
+constexpr int GM_ROWS = 32;                // weight rows of a workgroup: one tile of the matrix instruction
+constexpr int GM_WAVES = 8;                // waves of a workgroup: each takes every eighth chunk of the rows
+constexpr int GM_THREADS = GM_WAVES * WAVE;
 constexpr int GM_CHUNK = 256;              // columns of one step of a wave: 2 halves x 16 instructions x 8 columns
 
 typedef uint32_t gv_u32x4_t __attribute__((ext_vector_type(4)));
@@ -360,11 +363,13 @@ __global__ __launch_bounds__(GV_THREADS) void k_qgemv(GemvBatch bt) {
 // v_mfma_f32_32x32x16_bf16 with A = 32 weight rows x 16 columns, B = 16 columns x 32 activation rows: lane
 // (r, h) supplies row r's 8 columns of half h to A -- exactly 4 pairs, i.e. 4 codewords, each one 32-bit
 // LDS gather of (bf16 c0, bf16 c1) -- and activation row r's same 8 columns to B (16 bytes of z).
-// A workgroup of 4 waves owns 64 weight rows (two tiles); the 256-column chunks of the rows are dealt to
-// the waves in equal consecutive shares; within a chunk half h of the wave covers columns 128h .. 128h+127,
-// so a lane walks 64 consecutive pairs of its row: 8*BITS consecutive bytes, loaded as BITS 8-byte words
-// and unpacked at compile-time bit offsets.  No LDS staging of weights or activations and no barrier inside
-// the loop; the four waves' tiles are summed through LDS in wave order at the end.
+// A workgroup of 8 waves owns 32 weight rows (one tile); the 256-column chunks of the rows are dealt to the
+// waves round-robin; within a chunk half h of the wave covers columns 128h .. 128h+127, so a lane walks 64
+// consecutive pairs of its row: 8*BITS consecutive bytes, read as BITS 8-byte words from the wave's LDS copy
+// of the chunk and unpacked at compile-time bit offsets.  No barrier inside the loop; the eight waves' tiles
+// are summed through LDS in wave order at the end.  The shape follows from what bounds a launch: the chain of
+// dependent chunk loads of its longest workgroup (a wave has one chunk in flight), so short chains -- many
+// waves per row, few rows per workgroup -- beat shared operands; 128 registers keep 16 waves on a CU.
 template <int BITS> __device__ __forceinline__ uint32_t gm_field_x4(const uint32_t (&w)[2 * BITS], int i) {
     // 4 * (field i of the lane's 64-field stream): the byte offset of the codeword in the bf16 table
     const int bit = i * BITS, word = bit >> 5, off = bit & 31;
@@ -373,12 +378,12 @@ template <int BITS> __device__ __forceinline__ uint32_t gm_field_x4(const uint32
 }
 
 template <int BITS, int MT>
-__global__ __launch_bounds__(GV_THREADS) __attribute__((amdgpu_waves_per_eu(2, 8)))   // two workgroups per CU: at most 256 registers
+__global__ __launch_bounds__(GM_THREADS) __attribute__((amdgpu_waves_per_eu(4, 8)))   // two workgroups per CU: at most 128 registers
 void k_qgemm(GemvBatch bt) {
     extern __shared__ __align__(16) uint32_t gm_lds[];
     uint32_t *cbh = gm_lds;                                     // K codewords as (bf16 c0) | (bf16 c1) << 16
-    // after the codebook: per wave a 64-row tile of packed bytes (pitch GM_PITCH<BITS>) during the loop, and, after
-    // it, the partial tiles of waves 1..3: [3 waves][2 tiles][MT][16][64 lanes]
+    // after the codebook: per wave a 32-row tile of packed bytes (pitch PITCH) during the loop, and, after it, the
+    // partial tiles of waves 1..7: [7 waves][MT][16][64 lanes]
     float *red = reinterpret_cast<float *>(gm_lds + bt.K);
     constexpr int PITCH = 16 * BITS + 8;                        // bytes; an odd number of 8-byte words: the lanes' 8-byte reads spread over all banks
     const int lane = threadIdx.x & (WAVE - 1);
@@ -397,7 +402,7 @@ void k_qgemm(GemvBatch bt) {
 
     {   // stage the codebook, rounded to bf16
         const float2 *cbk = reinterpret_cast<const float2 *>(bt.codebook);
-        for (int i = threadIdx.x; i < bt.K; i += GV_THREADS) {
+        for (int i = threadIdx.x; i < bt.K; i += GM_THREADS) {
             const float2 c = cbk[i];
             const gv_f32x2_t v = {c.x, c.y};
             cbh[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, gv_bf16x2_t));
@@ -405,11 +410,12 @@ void k_qgemm(GemvBatch bt) {
         __syncthreads();
     }
 
-
-    // The chunk's packed bytes of the workgroup's 64 rows -- BITS 16-byte pieces per row -- are loaded with consecutive
-    // lanes on consecutive pieces (piece 64 i + lane of the row-major 64 x BITS array) and laid down in LDS row by row.
-    // Rows past the end of the matrix re-read the last row (their results are not stored).
+    // The chunk's packed bytes of the workgroup's 32 rows -- BITS 16-byte pieces per row -- are loaded with consecutive
+    // lanes on consecutive pieces (piece 64 i + lane of the row-major 32 x BITS array) and laid down in LDS row by row.
+    // Rows past the end of the matrix re-read the last row (their results are not stored); the pieces past the tile's
+    // last row (32 BITS is not always a multiple of 64) are loaded from valid addresses and not written to LDS.
     // (the offsets are recomputed where they are used: the vector ALU is idle here and the registers are not)
+    constexpr int TILE_PIECES = GM_ROWS * BITS, PIECES = (TILE_PIECES + 63) / 64;
     auto src_off = [&](int i) {
         const int piece = 64 * i + lane, row = piece / BITS, c16 = piece - row * BITS;
         return min(row0 + row, last_row) * (int)row_bytes + 16 * c16;
@@ -422,47 +428,44 @@ void k_qgemm(GemvBatch bt) {
 #pragma unroll
     for (int t = 0; t < MT; ++t) zrow[t] = Zb + ((int64_t)t * n_chunks * 2 + h) * 16 * 256 + r * 8;   // padded rows exist and are zero
 
-    gv_f32x16_t acc[2][MT];
+    gv_f32x16_t acc[MT];
 #pragma unroll
-    for (int T = 0; T < 2; ++T)
+    for (int t = 0; t < MT; ++t)
 #pragma unroll
-        for (int t = 0; t < MT; ++t)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[T][t][i] = 0.0f;
+        for (int i = 0; i < 16; ++i) acc[t][i] = 0.0f;
 
-    // Wave w takes the chunks w, w + 4, ...: at any time the four waves read neighbouring pieces of the same rows.
-    // The packed bytes of the wave's next chunk and the activations of the current one are requested before the
-    // current chunk's matrix instructions start: with two waves per SIMD (the LDS tiles limit the workgroups per CU)
-    // nothing else would hide the memory round trips.
+    // Wave w takes the chunks w, w + 8, ...: at any time the eight waves read neighbouring pieces of the same rows.
+    // The packed bytes of the wave's next chunk are requested before the current chunk's matrix instructions start.
     typedef gv_u32x4_t u32x4_a4_t __attribute__((aligned(4)));
-    gv_u32x4_t v[BITS];
+    gv_u32x4_t v[PIECES];
     if (wid < n_chunks) {
         const uint8_t *src = M.packed + (int64_t)wid * (16 * BITS);
 #pragma unroll
-        for (int i = 0; i < BITS; ++i) v[i] = *reinterpret_cast<const u32x4_a4_t *>(src + src_off(i));
+        for (int i = 0; i < PIECES; ++i) v[i] = *reinterpret_cast<const u32x4_a4_t *>(src + src_off(i));
     }
 #pragma unroll 1
-    for (int ch = wid; ch < n_chunks; ch += GV_WAVES) {
-        // the chunk's packed bytes go through LDS: written piece by piece, read back as the lane's two 64-pair streams
+    for (int ch = wid; ch < n_chunks; ch += GM_WAVES) {
+        // the chunk's packed bytes go through LDS: written piece by piece, read back as the lane's stream of 64 pairs
 #pragma unroll
-        for (int i = 0; i < BITS; ++i) {
+        for (int i = 0; i < PIECES; ++i) {
+            if (TILE_PIECES % 64 != 0 && 64 * i + lane >= TILE_PIECES) continue;
             gv_u32x2_t *dst = reinterpret_cast<gv_u32x2_t *>(tile + dst_off(i));
             dst[0] = gv_u32x2_t{v[i][0], v[i][1]};
             dst[1] = gv_u32x2_t{v[i][2], v[i][3]};
         }
-        uint32_t w[2][2 * BITS];
-#pragma unroll
-        for (int T = 0; T < 2; ++T) {
-            const gv_u32x2_t *src = reinterpret_cast<const gv_u32x2_t *>(tile + (32 * T + r) * PITCH + 8 * BITS * h);
+        uint32_t w[2 * BITS];
+        {
+            const gv_u32x2_t *src = reinterpret_cast<const gv_u32x2_t *>(tile + r * PITCH + 8 * BITS * h);
 #pragma unroll
             for (int q = 0; q < BITS; ++q) {
                 const gv_u32x2_t x2 = src[q];
-                w[T][2 * q] = x2[0];
-                w[T][2 * q + 1] = x2[1];
+                w[2 * q] = x2[0];
+                w[2 * q + 1] = x2[1];
             }
         }
-        // activations of this chunk: all 16 instructions' worth for one tile of activation rows (MT == 1), else 8 at a time
-        constexpr int ZB = MT == 1 ? 16 : 8;
+        // activations of this chunk, ZB instructions' worth at a time: 8, or 2 with two tiles of activation rows (the
+        // kernel has 128 registers)
+        constexpr int ZB = 8 / (MT * MT);
         gv_u32x4_t zb[MT][ZB];
         auto load_zb = [&](int first) {
 #pragma unroll
@@ -473,55 +476,48 @@ void k_qgemm(GemvBatch bt) {
             }
         };
         load_zb(0);
-        if (ch + GV_WAVES < n_chunks) {                         // the next chunk's packed bytes
-            const uint8_t *src = M.packed + (int64_t)(ch + GV_WAVES) * (16 * BITS);
+        if (ch + GM_WAVES < n_chunks) {                         // the next chunk's packed bytes
+            const uint8_t *src = M.packed + (int64_t)(ch + GM_WAVES) * (16 * BITS);
 #pragma unroll
-            for (int i = 0; i < BITS; ++i) v[i] = *reinterpret_cast<const u32x4_a4_t *>(src + src_off(i));
+            for (int i = 0; i < PIECES; ++i) v[i] = *reinterpret_cast<const u32x4_a4_t *>(src + src_off(i));
         }
 #pragma unroll
         for (int step = 0; step < 16; ++step) {                 // instruction of the chunk: pairs 4 step .. 4 step + 3 of the lane's 64
-            if (ZB == 8 && step == 8) load_zb(8);
+            if (step > 0 && step % ZB == 0) load_zb(step);
+            gv_u32x4_t a;
 #pragma unroll
-            for (int T = 0; T < 2; ++T) {
-                gv_u32x4_t a;
+            for (int f = 0; f < 4; ++f)
+                a[f] = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(cbh) + gm_field_x4<BITS>(w, 4 * step + f));
+            const gv_bf16x8_t av = __builtin_bit_cast(gv_bf16x8_t, a);
 #pragma unroll
-                for (int f = 0; f < 4; ++f)
-                    a[f] = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(cbh) + gm_field_x4<BITS>(w[T], 4 * step + f));
-                const gv_bf16x8_t av = __builtin_bit_cast(gv_bf16x8_t, a);
-#pragma unroll
-                for (int t = 0; t < MT; ++t)
-                    acc[T][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(gv_bf16x8_t, zb[t][step % ZB]), acc[T][t], 0, 0, 0);
-            }
+            for (int t = 0; t < MT; ++t)
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(gv_bf16x8_t, zb[t][step % ZB]), acc[t], 0, 0, 0);
         }
     }
 
-    // the four waves' tiles, summed in wave order by wave 0 (the buffer overlies the packed tiles: everybody is done with those)
+    // the eight waves' tiles, summed in wave order by wave 0 (the buffer overlies the packed tiles: everybody is done with those)
     __syncthreads();
     if (wid > 0) {
-        float *dst = red + (size_t)(wid - 1) * (2 * MT * 16 * WAVE);
+        float *dst = red + (size_t)(wid - 1) * (MT * 16 * WAVE);
 #pragma unroll
-        for (int T = 0; T < 2; ++T)
+        for (int t = 0; t < MT; ++t)
 #pragma unroll
-            for (int t = 0; t < MT; ++t)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) dst[((T * MT + t) * 16 + i) * WAVE + lane] = acc[T][t][i];
+            for (int i = 0; i < 16; ++i) dst[(t * 16 + i) * WAVE + lane] = acc[t][i];
     }
     __syncthreads();
     if (wid == 0) {
 #pragma unroll
-        for (int T = 0; T < 2; ++T)
+        for (int t = 0; t < MT; ++t) {
+            const int tok = 32 * t + r;                         // the accumulator's column is the activation row
 #pragma unroll
-            for (int t = 0; t < MT; ++t) {
-                const int tok = 32 * t + r;                     // the accumulator's column is the activation row
+            for (int i = 0; i < 16; ++i) {
+                float s = acc[t][i];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    float s = acc[T][t][i];
-#pragma unroll
-                    for (int w2 = 0; w2 < GV_WAVES - 1; ++w2) s += red[(size_t)w2 * (2 * MT * 16 * WAVE) + ((T * MT + t) * 16 + i) * WAVE + lane];
-                    const int row = row0 + 32 * T + 8 * (i >> 2) + 4 * h + (i & 3);   // accumulator i of half h: tile row 8 (i / 4) + 4 h + i % 4
-                    if (tok < m && row <= last_row) M.Y[(int64_t)tok * M.ldy + row] = M.norms[row] * s;
-                }
+                for (int w2 = 0; w2 < GM_WAVES - 1; ++w2) s += red[(size_t)w2 * (MT * 16 * WAVE) + (t * 16 + i) * WAVE + lane];
+                const int row = row0 + 8 * (i >> 2) + 4 * h + (i & 3);   // accumulator i of half h: tile row 8 (i / 4) + 4 h + i % 4
+                if (tok < m && row <= last_row) M.Y[(int64_t)tok * M.ldy + row] = M.norms[row] * s;
             }
+        }
     }
 }
 
@@ -571,11 +567,11 @@ template <int BITS>
 static hipError_t launch_qgemm(const GemvBatch &bt, hipStream_t stream) {
     const unsigned blocks = (unsigned)bt.grp_begin[bt.n];
     const int mt = (bt.m + 31) / 32;
-    const size_t red_bytes = (size_t)(GV_WAVES - 1) * 2 * mt * 16 * WAVE * sizeof(float);
-    const size_t tile_bytes = (size_t)GV_WAVES * GM_ROWS * (16 * BITS + 8);
+    const size_t red_bytes = (size_t)(GM_WAVES - 1) * mt * 16 * WAVE * sizeof(float);
+    const size_t tile_bytes = (size_t)GM_WAVES * GM_ROWS * (16 * BITS + 8);
     const size_t lds = (size_t)bt.K * sizeof(uint32_t) + (red_bytes > tile_bytes ? red_bytes : tile_bytes);
-    if (mt == 1) hipLaunchKernelGGL((k_qgemm<BITS, 1>), dim3(blocks), dim3(GV_THREADS), lds, stream, bt);
-    else hipLaunchKernelGGL((k_qgemm<BITS, 2>), dim3(blocks), dim3(GV_THREADS), lds, stream, bt);
+    if (mt == 1) hipLaunchKernelGGL((k_qgemm<BITS, 1>), dim3(blocks), dim3(GM_THREADS), lds, stream, bt);
+    else hipLaunchKernelGGL((k_qgemm<BITS, 2>), dim3(blocks), dim3(GM_THREADS), lds, stream, bt);
     return hipGetLastError();
 }
 
@@ -625,7 +621,7 @@ hipError_t launch_matmul_batch(const MatmulItem *items, int n, int xdtype, int m
         if (groups_per_wg > GV_MAX_ROWS_PER_WG / GV_RG) groups_per_wg = GV_MAX_ROWS_PER_WG / GV_RG;
         while (groups_per_wg > 1 && (M.d_out + groups_per_wg * GV_RG - 1) / (groups_per_wg * GV_RG) < GV_MIN_WGS) groups_per_wg >>= 1;
         M.rows_per_wg = groups_per_wg * GV_RG;
-        if (m > GV_MAX_M) {                                     // matrix-core kernel: 64 rows per workgroup
+        if (m > GV_MAX_M) {                                     // matrix-core kernel: one 32-row tile per workgroup
             if ((int64_t)M.d_out * M.row_bytes > 0x7fffffff) return hipErrorNotSupported;   // 32-bit byte offsets into the packed matrix
             M.rows_per_wg = GM_ROWS;
         }

@@ -448,10 +448,10 @@ def test_fused_matmul_matches_oracle(orc, codebooks, seed, d_out, d_in, bits, bl
 
 GEMM_CASES = [
     # seed d_out d_in bits block m xdtype
-    (51, 70, 2048, 11, 128, 9, "f32"),        # a ragged last workgroup (70 = 64 + 6 rows), one token tile
-    (52, 64, 1024, 7, 256, 32, "bf16"),       # one chunk per wave
-    (53, 33, 5632, 11, 512, 40, "f32"),       # two token tiles, 22 chunks over 4 waves
-    (54, 130, 768, 8, 256, 64, "bf16"),       # fewer chunks (3) than waves
+    (51, 70, 2048, 11, 128, 9, "f32"),        # a ragged last workgroup (70 = 2 x 32 + 6 rows), one token tile, one chunk per wave
+    (52, 64, 1024, 7, 256, 32, "bf16"),       # fewer chunks (4) than waves
+    (53, 33, 5632, 11, 512, 40, "f32"),       # two token tiles, 22 chunks over 8 waves, a last workgroup of one row
+    (54, 130, 768, 8, 256, 64, "bf16"),       # 3 chunks
     (55, 96, 11008, 11, 128, 17, "plain"),    # no scales, signs or sigma; 43 chunks
     (56, 200, 8192, 7, 128, 50, "bf16"),      # 32 chunks, four row groups (the last of 8 rows), two token tiles
 ]
