@@ -152,6 +152,8 @@ def main():
                     help="extra decode-only passes over the whole weight set after the timed steps (median and best reported)")
     ap.add_argument("--matmul", type=int, default=0, metavar="M",
                     help="also time the fused dequantise-and-multiply with M activation rows (1..64; more than 8 run on the matrix cores) over the whole set")
+    ap.add_argument("--matmul-path", type=int, default=0, choices=(0, 1, 2),
+                    help="qamw_set_kernel_path() value during the fused-matmul leg (1 / 2: activations rotated by their own launch / inside the product kernel)")
     ap.add_argument("--polar", action="store_true", help="also time the polar-baseline encoder at the same bits per pair")
     ap.add_argument("--no-pruned", action="store_true", help="skip the pruned-search encoder leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -245,6 +247,7 @@ def main():
             site_batches += [qamw.make_matmul_items(entries) for _, entries in sites]
         ws_mm = torch.empty(max(b[4] for b in mm_batches + site_batches), dtype=torch.uint8, device=dev)
         times = {}
+        prev_path = qamw.set_kernel_path(args.matmul_path)
         for kind in ("fused", "by_site", "bf16"):
             best = []
             for rep in range(1 + 5):
@@ -261,6 +264,7 @@ def main():
                 if rep:
                     best.append(e0.elapsed_time(e1))
             times[kind] = sorted(best)[len(best) // 2]
+        qamw.set_kernel_path(prev_path)
         pairs_set = sum(m["d_out"] * m["d_in"] // 2 for m in mats)
         fused_bytes = pairs_set * wl.bits / 8.0 + sum(4 * m["d_out"] + mm * (2 * m["d_in"] + 4 * m["d_out"]) for m in mats)
         bf16_bytes = pairs_set * 4.0 + sum(mm * 2 * (m["d_in"] + m["d_out"]) for m in mats)

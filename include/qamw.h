@@ -322,7 +322,9 @@ int qamw_matmul_batch(const qamw_matmul_item *items, int n_items, int x_dtype, i
  * allows, otherwise the general ones), 1 = always the general kernels, 2 = as 0 but the encoder's
  * shortlist runs on the vector ALU instead of the matrix cores.  All three give the same indices.
  * qamw_encode_pruned: 0 = chosen by the amount of work, 1 = every cell record read from global memory,
- * 2 = the central cells in LDS whatever the size.
+ * 2 = the central cells in LDS whatever the size.  qamw_matmul / qamw_matmul_batch with one or two
+ * activation rows: 0 = chosen by the size of the launch, 1 = activations rotated by a launch of their
+ * own, 2 = rotated inside the product kernel; the results are the same, bit for bit.
  * Process-wide, for tests and measurements; returns the previous value (also for a value out of
  * range, which changes nothing). */
 int qamw_set_kernel_path(int path);

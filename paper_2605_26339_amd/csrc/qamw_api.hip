@@ -279,7 +279,7 @@ static int matmul_batch_impl(const qamw_matmul_item *items, int n_items, int x_d
     if (workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15)) return QAMW_ERR_INVALID_ARG;
     if (!supported) return QAMW_ERR_UNSUPPORTED;
     qamw::Problem p = make_problem(items[0].d_out, items[0].d_in, nullptr, nullptr, nullptr, codebook, bits, hadamard_block, stream);
-    hipError_t e = qamw::launch_matmul_batch(its, n_items, x_dtype, m, p, workspace);
+    hipError_t e = qamw::launch_matmul_batch(its, n_items, x_dtype, m, p, workspace, g_kernel_path.load());
     if (e == hipErrorNotSupported) return QAMW_ERR_UNSUPPORTED;
     return e == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
 }

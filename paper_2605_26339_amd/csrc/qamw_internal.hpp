@@ -79,7 +79,7 @@ struct MatmulItem {
     int64_t ldy;
     int d_out, d_in;
 };
-hipError_t launch_matmul_batch(const MatmulItem *items, int n, int xdtype, int m, const Problem &p, void *workspace);
+hipError_t launch_matmul_batch(const MatmulItem *items, int n, int xdtype, int m, const Problem &p, void *workspace, int variant);
 size_t lloyd_workspace_bytes(int K);
 hipError_t run_lloyd(const float *samples, long long n, int K, float *codebook, int max_iters, double tol, void *workspace,
                      double *mse_out, int *iters_out, hipStream_t stream);

@@ -39,6 +39,7 @@ constexpr int GV_RG = 8;                // rows per group: requested together, a
 constexpr int GV_STEPS_PER_WG = 16;     // target number of (slab, 8-row group) steps per workgroup: 4 per wave
 constexpr int GV_MIN_WGS = 256;         // a matrix is cut into at least this many workgroups when it has the rows
 constexpr int GV_MAX_ROWS_PER_WG = 64;
+constexpr int GV_SELF_ROTATE_MAX_WGS = 1024;   // launches of at most this many workgroups (and one or two activation rows) skip k_rotate_x
 constexpr int GV_MAX_M = 8;                // activation rows of the vector-ALU kernel
 constexpr int GM_MAX_M = 64;               // ... of the matrix-core kernel (QAMW_MATMUL_MAX_ROWS of the public header)
 constexpr int GM_ROWS = 32;                // weight rows of a workgroup: one tile of the matrix instruction
@@ -72,6 +73,7 @@ struct GemvBatch {
     int rot_begin[QAMW_MATMUL_MAX_BATCH + 1];
     int grp_begin[QAMW_MATMUL_MAX_BATCH + 1];
     int n, m, K;
+    int xdtype;                            // element type of X: 0 fp32, 1 bf16
     int z_bf16;                            // 1: k_rotate_x writes bf16 rows, padded with zero rows to a multiple of 32 (matrix-core kernel)
     float inv_sqrt_block;
     const float *codebook;
@@ -88,6 +90,36 @@ __device__ __forceinline__ int gv_find(const int *begin, int n, int u) {
 __device__ __forceinline__ int64_t gm_z_offset(int tok, int col, int d_in) {
     const int tile = tok >> 5, r = tok & 31, ch = col >> 8, within = col & 255, h = within >> 7, j = (within & 127) >> 3;
     return ((((int64_t)tile * (d_in >> 8) + ch) * 2 + h) * 16 + j) * 256 + r * 8;
+}
+
+// z = sigma (.) F S (x / s) of activation row tok for one 1024-column slab: lane l returns the 16 columns of sub-block
+// slab_pos(l) (the order of the register transform); all 64 lanes of the wave call it together.  Lanes past the end of
+// the row work on columns 0..15 (their blocks hold no lane that counts) and return values nobody uses.
+template <int XDTYPE, int B>
+__device__ __forceinline__ void gv_rotate_slab(float (&y)[16], const GemvBatch &bt, const GemvMat &M, int tok, int slab, int lane) {
+    const float *chan_scale = M.chan_scale, *pair_sigma = M.pair_sigma;
+    const int8_t *signs = M.signs;
+    const LaneSigns<B> ls(lane);
+    const int pos = slab_pos(lane);
+    const int col0 = slab * GV_SLAB + 16 * pos;
+    const int c = col0 < M.d_in ? col0 : 0;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = Elem<XDTYPE>::load(M.X, (int64_t)tok * M.ldx + c + e);
+    if (chan_scale) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) y[e] = y[e] * (1.0f / chan_scale[c + e]);    // times fl32(1/s_j), as the decoder does
+    }
+    if (signs) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) y[e] = (signs[c + e] < 0) ? -y[e] : y[e];
+    }
+    fwht_wave<B>(y, ls);
+    const float sigma_default = M.sigma_default;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const float sg = pair_sigma ? pair_sigma[(c + e) >> 1] : sigma_default;
+        y[e] = ((y[e] * ls.parity) * bt.inv_sqrt_block) * sg;
+    }
 }
 
 // z = sigma (.) F S (x / s) for every activation row: fp32, row-major [m][d_in], or bf16 in the order above.
@@ -112,31 +144,11 @@ __global__ __launch_bounds__(GV_THREADS) void k_rotate_x(GemvBatch bt) {
         }
         return;
     }
-    const float *chan_scale = M.chan_scale, *pair_sigma = M.pair_sigma;
-    const int8_t *signs = M.signs;
-    const LaneSigns<B> ls(lane);
-    const int pos = slab_pos(lane);
-    const int col0 = slab * GV_SLAB + 16 * pos;
+    const int col0 = slab * GV_SLAB + 16 * slab_pos(lane);
     const bool active = col0 < d_in;
     const int c = active ? col0 : 0;
     float y[16];
-#pragma unroll
-    for (int e = 0; e < 16; ++e) y[e] = Elem<XDTYPE>::load(M.X, (int64_t)tok * M.ldx + c + e);
-    if (chan_scale) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) y[e] = y[e] * (1.0f / chan_scale[c + e]);    // times fl32(1/s_j), as the decoder does
-    }
-    if (signs) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) y[e] = (signs[c + e] < 0) ? -y[e] : y[e];
-    }
-    fwht_wave<B>(y, ls);
-    const float sigma_default = M.sigma_default;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-        const float sg = pair_sigma ? pair_sigma[(c + e) >> 1] : sigma_default;
-        y[e] = ((y[e] * ls.parity) * bt.inv_sqrt_block) * sg;
-    }
+    gv_rotate_slab<XDTYPE, B>(y, bt, M, tok, slab, lane);
     if (active && !bt.z_bf16) {
         float4 *dst = reinterpret_cast<float4 *>(M.Z + (int64_t)tok * d_in + c);
 #pragma unroll
@@ -205,8 +217,11 @@ template <int N> __device__ __forceinline__ void gv_reduce_rows(float (&a)[N], i
     gv_reduce_step<N, (N > 16 ? N / 32 : 1), 0>(a, lane);
 }
 
-// Y[t][row] = r_row * sum over the row's pairs of <c[idx], z_t>
-template <int BITS, int MT>
+// Y[t][row] = r_row * sum over the row's pairs of <c[idx], z_t>.  RB == 0: z comes from the workspace (k_rotate_x ran
+// before).  RB > 0 (the block size): every wave rotates the slabs it needs itself, with the same arithmetic, and moves
+// the result from the transform's lane order to the natural one -- the same z in the same lanes, so the same Y, bit for
+// bit, without the first launch; for launches so small that a second launch costs more than the repeated rotations.
+template <int BITS, int MT, int RB>
 __global__ __launch_bounds__(GV_THREADS) void k_qgemv(GemvBatch bt) {
     constexpr int RG = MT == 8 ? 4 : GV_RG, UR = GV_MAX_ROWS_PER_WG;
     extern __shared__ __align__(16) float gv_lds[];
@@ -255,12 +270,31 @@ __global__ __launch_bounds__(GV_THREADS) void k_qgemv(GemvBatch bt) {
             }
         }
     };
+    // the lane whose transform sub-block is this lane's natural one (slab_pos permutes inside groups of 16 lanes)
+    int z_from = 0;
+    if (RB > 0) {
+#pragma unroll
+        for (int l = 0; l < 16; ++l) z_from = (slab_pos(l) == (lane & 15)) ? l : z_from;
+        z_from = ((lane & ~15) | z_from) << 2;
+    }
     auto load_z = [&](int slab, float (&z)[MT][16]) {           // the slab's rotated activations, zero for missing rows of X and idle lanes
         const bool active = slab * GV_SLAB + 16 * lane < d_in;
         const int c = lane_col(slab);
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
             const bool have = active && t < m;
+            if (RB > 0) {
+                float y[16];
+                constexpr int B = RB > 0 ? RB : 64;
+                if (bt.xdtype == 0) gv_rotate_slab<0, B>(y, bt, M, t < m ? t : 0, slab, lane);
+                else gv_rotate_slab<1, B>(y, bt, M, t < m ? t : 0, slab, lane);
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const float v = __int_as_float(__builtin_amdgcn_ds_bpermute(z_from, __float_as_int(y[e])));
+                    z[t][e] = have ? v : 0.0f;
+                }
+                continue;
+            }
             const float4 *src = reinterpret_cast<const float4 *>(Z + (int64_t)(t < m ? t : 0) * d_in + c);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -549,18 +583,32 @@ static hipError_t launch_rotate(const GemvBatch &bt, int block, hipStream_t stre
     return hipGetLastError();
 }
 
-template <int BITS>
-static hipError_t launch_qgemv(const GemvBatch &bt, hipStream_t stream) {
+template <int BITS, int RB>
+static hipError_t launch_qgemv_rb(const GemvBatch &bt, hipStream_t stream) {
     const unsigned blocks = (unsigned)bt.grp_begin[bt.n];
 #define QAMW_GV(MM)                                                                                                  \
-    hipLaunchKernelGGL((k_qgemv<BITS, MM>), dim3(blocks), dim3(GV_THREADS),                                            \
+    hipLaunchKernelGGL((k_qgemv<BITS, MM, RB>), dim3(blocks), dim3(GV_THREADS),                                        \
                        ((size_t)bt.K * 2 + (size_t)GV_WAVES * GV_MAX_ROWS_PER_WG * MM) * sizeof(float), stream, bt)
     if (bt.m == 1) QAMW_GV(1);
     else if (bt.m == 2) QAMW_GV(2);
+    else if constexpr (RB > 0) return hipErrorNotSupported;     // the self-rotating kernels exist for one and two rows
     else if (bt.m <= 4) QAMW_GV(4);
     else QAMW_GV(8);
 #undef QAMW_GV
     return hipGetLastError();
+}
+// rotate_block: 0, or the block size when the product kernel is to rotate the activations itself
+template <int BITS>
+static hipError_t launch_qgemv(const GemvBatch &bt, int rotate_block, hipStream_t stream) {
+    switch (rotate_block) {
+        case 0: return launch_qgemv_rb<BITS, 0>(bt, stream);
+        case 64: return launch_qgemv_rb<BITS, 64>(bt, stream);
+        case 128: return launch_qgemv_rb<BITS, 128>(bt, stream);
+        case 256: return launch_qgemv_rb<BITS, 256>(bt, stream);
+        case 512: return launch_qgemv_rb<BITS, 512>(bt, stream);
+        case 1024: return launch_qgemv_rb<BITS, 1024>(bt, stream);
+        default: return hipErrorNotSupported;
+    }
 }
 
 template <int BITS>
@@ -577,8 +625,9 @@ static hipError_t launch_qgemm(const GemvBatch &bt, hipStream_t stream) {
 
 // Y_i = X_i W_i^T for n <= QAMW_MATMUL_MAX_BATCH matrices that share codebook, bits, block, m and the element type
 // of X.  workspace: the sum of matmul_workspace_bytes() over the items, 16-byte aligned.
-// Returns hipErrorNotSupported (nothing launched) outside the supported shapes.
-hipError_t launch_matmul_batch(const MatmulItem *items, int n, int xdtype, int m, const Problem &p, void *workspace) {
+// Returns hipErrorNotSupported (nothing launched) outside the supported shapes.  variant: 0, or 1 / 2 to force the
+// two-launch / the self-rotating form of the vector kernel.
+hipError_t launch_matmul_batch(const MatmulItem *items, int n, int xdtype, int m, const Problem &p, void *workspace, int variant) {
     if (n < 1 || n > QAMW_MATMUL_MAX_BATCH) return hipErrorNotSupported;
     GemvBatch bt;
     int64_t rot = 0, groups = 0;
@@ -642,16 +691,23 @@ hipError_t launch_matmul_batch(const MatmulItem *items, int n, int xdtype, int m
     bt.inv_sqrt_block = p.inv_sqrt_block;
     bt.codebook = p.codebook;
     bt.z_bf16 = m > GV_MAX_M ? 1 : 0;
-    hipError_t e = xdtype == 0 ? launch_rotate<0>(bt, p.block, p.stream) : launch_rotate<1>(bt, p.block, p.stream);
+    bt.xdtype = xdtype;
+    // One or two activation rows in a small launch (a forward pass issues one product, or the few that share an input,
+    // per call): the product kernel rotates the activations itself.  Same results, one launch less.
+    // (variant 1: never, 2: whenever there are one or two rows -- for tests and measurements)
+    const bool self_rotate = m <= 2 && variant != 1 && (variant == 2 || groups <= GV_SELF_ROTATE_MAX_WGS);
+    hipError_t e = hipSuccess;
+    if (!self_rotate) e = xdtype == 0 ? launch_rotate<0>(bt, p.block, p.stream) : launch_rotate<1>(bt, p.block, p.stream);
     if (e != hipSuccess) return e;
     if (m > GV_MAX_M) {
         if (p.bits == 11) return launch_qgemm<11>(bt, p.stream);
         if (p.bits == 8) return launch_qgemm<8>(bt, p.stream);
         return launch_qgemm<7>(bt, p.stream);
     }
-    if (p.bits == 11) e = launch_qgemv<11>(bt, p.stream);
-    else if (p.bits == 8) e = launch_qgemv<8>(bt, p.stream);
-    else e = launch_qgemv<7>(bt, p.stream);
+    const int rb = self_rotate ? p.block : 0;
+    if (p.bits == 11) e = launch_qgemv<11>(bt, rb, p.stream);
+    else if (p.bits == 8) e = launch_qgemv<8>(bt, rb, p.stream);
+    else e = launch_qgemv<7>(bt, rb, p.stream);
     return e;
 }
 

@@ -406,6 +406,9 @@ MATMUL_CASES = [
     (95, 5, 4096, 7, 1024, 4, "f32"),
     (96, 48, 4096, 11, 128, 5, "bf16"),
     (97, 21, 3072, 11, 256, 2, "plain"),       # no channel scale, no sign mask, default pair scale; fp32 X
+    (98, 40, 5632, 11, 512, 1, "bf16"),        # one row, ragged slab, 512-column blocks
+    (99, 9, 4096, 7, 1024, 2, "bf16"),         # two rows, blocks as wide as a slab
+    (100, 33, 1600, 8, 64, 1, "f32"),          # 64-column blocks, a slab of 576 columns
 ]
 
 
@@ -444,6 +447,18 @@ def test_fused_matmul_matches_oracle(orc, codebooks, seed, d_out, d_in, bits, bl
                      out=out2[:, :d_out])
     torch.cuda.synchronize()
     assert np.array_equal(Y2.cpu().numpy(), Y) and bool((out2[:, d_out:] == -3.0).all())
+    # one or two activation rows: rotated by a launch of its own (path 1) or inside the product kernel (path 2)
+    # the product is the same, bit for bit
+    if m <= 2:
+        for path in (1, 2):
+            prev = qamw.set_kernel_path(path)
+            try:
+                Yp = qamw.matmul(Xt, pk, nr, case.cb_dev, bits, block, chan_scale=case.s_dev, signs=case.sg_dev,
+                                 pair_sigma=case.sigma_dev)
+                torch.cuda.synchronize()
+            finally:
+                qamw.set_kernel_path(prev)
+            assert np.array_equal(Yp.cpu().numpy(), Y), f"kernel path {path}"
 
 
 GEMM_CASES = [
@@ -514,10 +529,10 @@ def test_fused_matmul_on_the_matrix_cores(orc, codebooks, seed, d_out, d_in, bit
     assert np.array_equal(Y2.cpu().numpy().astype(np.float64), Y) and bool((out2[:, d_out:] == -3.0).all())
 
 
-@pytest.mark.parametrize("m", [3, 20])
+@pytest.mark.parametrize("m", [1, 3, 20])
 def test_fused_matmul_batch_equals_single_calls(orc, codebooks, m):
     """Several independent products in one call give, bit for bit, what one call per matrix gives (vector kernel
-    for 3 activation rows, matrix-core kernel for 20)."""
+    for 1 and 3 activation rows, matrix-core kernel for 20)."""
     say(f"[matmul batch] m={m}")
     bits, block = 11, 128
     shapes = [(40, 2048), (17, 5632), (64, 1024), (33, 2048)]
