@@ -6,11 +6,13 @@ already resident in HBM: for every matrix, pair-scale calibration (Eq. 1) and en
 rotation, nearest codeword, bit-pack), then decode of every layer to bf16 (one launch per layer).  Rank 0 prints one JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--layers L]
-                    [--decode-passes N] [--matmul M] [--polar] [--no-pruned] [--no-cpu-baseline]
+                    [--decode-passes N] [--matmul M [--matmul-calls both|layer|site] [--matmul-path P]]
+                    [--polar] [--no-pruned] [--no-cpu-baseline]
 
 Beside the step: N decode-only passes over the set, one encode pass with the pruned nearest-codeword search
 (`pruned_search`; same indices, not part of `value` or of a roofline fraction), and on request the fused
-dequantise-and-multiply for M activation rows (`fused_matmul`) and the polar baseline (`polar_baseline`).
+dequantise-and-multiply for M activation rows (`fused_matmul`: one call per layer, its products as if independent,
+and one call per activation site, as a forward pass issues them) and the polar baseline (`polar_baseline`).
 
 Timing uses HIP events recorded on the stream the kernels are launched on.
 """
@@ -152,6 +154,8 @@ def main():
                     help="extra decode-only passes over the whole weight set after the timed steps (median and best reported)")
     ap.add_argument("--matmul", type=int, default=0, metavar="M",
                     help="also time the fused dequantise-and-multiply with M activation rows (1..64; more than 8 run on the matrix cores) over the whole set")
+    ap.add_argument("--matmul-calls", default="both", choices=("both", "layer", "site"),
+                    help="fused-matmul leg: one call per layer, one per activation site, or both (default)")
     ap.add_argument("--matmul-path", type=int, default=0, choices=(0, 1, 2),
                     help="qamw_set_kernel_path() value during the fused-matmul leg (1 / 2: activations rotated by their own launch / inside the product kernel)")
     ap.add_argument("--polar", action="store_true", help="also time the polar-baseline encoder at the same bits per pair")
@@ -249,6 +253,9 @@ def main():
         times = {}
         prev_path = qamw.set_kernel_path(args.matmul_path)
         for kind in ("fused", "by_site", "bf16"):
+            if (kind == "fused" and args.matmul_calls == "site") or (kind == "by_site" and args.matmul_calls == "layer"):
+                times[kind] = None
+                continue
             best = []
             for rep in range(1 + 5):
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -268,12 +275,15 @@ def main():
         pairs_set = sum(m["d_out"] * m["d_in"] // 2 for m in mats)
         fused_bytes = pairs_set * wl.bits / 8.0 + sum(4 * m["d_out"] + mm * (2 * m["d_in"] + 4 * m["d_out"]) for m in mats)
         bf16_bytes = pairs_set * 4.0 + sum(mm * 2 * (m["d_in"] + m["d_out"]) for m in mats)
-        fused = {"rows": mm, "ms_per_pass": times["fused"], "gb_per_s": fused_bytes / (times["fused"] * 1e-3) / 1e9,
-                 "frac_of_hbm_peak": fused_bytes / (times["fused"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        rate = lambda ms: ms and fused_bytes / (ms * 1e-3) / 1e9
+        fused = {"rows": mm, "ms_per_pass": times["fused"], "gb_per_s": rate(times["fused"]),
+                 "frac_of_hbm_peak": times["fused"] and rate(times["fused"]) / PEAK_HBM_GBS,
                  "algorithmic_bytes_per_pass": fused_bytes,
-                 "ms_per_pass_one_call_per_site": times["by_site"], "calls_per_pass_by_site": len(site_batches),
+                 "ms_per_pass_one_call_per_site": times["by_site"], "gb_per_s_one_call_per_site": rate(times["by_site"]),
+                 "calls_per_pass_by_site": len(site_batches),
                  "bf16_matmul_ms_per_pass": times["bf16"], "bf16_matmul_gb_per_s": bf16_bytes / (times["bf16"] * 1e-3) / 1e9,
-                 "speedup_vs_bf16_matmul": times["bf16"] / times["fused"],
+                 "speedup_vs_bf16_matmul": times["fused"] and times["bf16"] / times["fused"],
+                 "speedup_vs_bf16_matmul_one_call_per_site": times["by_site"] and times["bf16"] / times["by_site"],
                  "note": "median of 5 passes over the whole set, one qamw_matmul_batch call per layer (ms_per_pass) or one per activation site, the products that share an input (ms_per_pass_one_call_per_site); the bf16 leg is torch.matmul on the decoded matrices, one call per matrix"}
 
     # the polar baseline at the same rate (amplitude bits + phase bits = B): one encode pass over the set
