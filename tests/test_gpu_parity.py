@@ -529,6 +529,56 @@ def test_fused_matmul_on_the_matrix_cores(orc, codebooks, seed, d_out, d_in, bit
     assert np.array_equal(Y2.cpu().numpy().astype(np.float64), Y) and bool((out2[:, d_out:] == -3.0).all())
 
 
+def test_fused_matmul_random_shapes(codebooks):
+    """Many shapes, cheaply: random packed indices and row norms (any bytes are a valid code), the product against
+    X times the decoder's own fp32 output (checked against the oracle elsewhere) in fp64.  Bars: 1e-5 ||x|| ||w_i|| for
+    up to 8 activation rows (fp32 arithmetic; the channel scales put part of that into ||x / s|| ||w s||), 2^-8 of the
+    same for more (bf16 operands; no channel scales there, so the rotated operands have these norms).  For one and two
+    rows both forms of the vector kernel must agree bit for bit."""
+    rng = np.random.default_rng(2025)
+    cases = []
+    for i in range(36):
+        bits = int(rng.choice([7, 8, 11]))
+        block = int(rng.choice([64, 128, 256, 512, 1024]))
+        m = int(rng.choice([1, 1, 2, 2, 3, 4, 6, 8, 9, 16, 31, 32, 33, 64]))
+        step = max(block, 256) if m > 8 else block
+        d_in = step * int(rng.integers(1, max(2, 12288 // step)))
+        d_out = int(rng.integers(1, 200))
+        cases.append((bits, block, m, d_out, d_in))
+    for i, (bits, block, m, d_out, d_in) in enumerate(cases):
+        say(f"[matmul random {i}] {d_out}x{d_in} B={bits} b={block} m={m}")
+        g = torch.Generator("cuda").manual_seed(1000 + i)
+        cb = torch.from_numpy(np.asarray(codebooks[bits], dtype=np.float32)).cuda()
+        rb = qamw.packed_row_bytes(d_in, bits)
+        pk = torch.randint(0, 256, (d_out, rb), dtype=torch.uint8, device="cuda", generator=g)
+        nr = torch.rand(d_out, device="cuda", generator=g) + 0.5
+        plain = m > 8
+        s = None if plain else torch.exp(0.5 * torch.randn(d_in, device="cuda", generator=g))
+        sg = None if plain else (torch.randint(0, 2, (d_in,), device="cuda", generator=g) * 2 - 1).to(torch.int8)
+        sigma = None if plain else (torch.rand(d_in // 2, device="cuda", generator=g) + 0.5) / np.sqrt(d_in)
+        X = torch.randn((m, d_in), device="cuda", generator=g)
+        if i % 2:
+            X = X.to(torch.bfloat16)
+        W = qamw.decode(pk, nr, d_in, cb, bits, block, chan_scale=s, signs=sg, pair_sigma=sigma, f32=True).double()
+        Yref = X.double() @ W.t()
+        Y = qamw.matmul(X, pk, nr, cb, bits, block, chan_scale=s, signs=sg, pair_sigma=sigma)
+        torch.cuda.synchronize()
+        scale = X.double().norm(dim=1)[:, None] * W.norm(dim=1)[None, :]
+        bar = (2.0 ** -8 if m > 8 else 1e-5) * scale + 1e-30
+        worst = float(((Y.double() - Yref).abs() / bar).max())
+        say(f"    worst error / bar = {worst:.3f}")
+        assert worst <= 1.0
+        if m <= 2:
+            for path in (1, 2):
+                prev = qamw.set_kernel_path(path)
+                try:
+                    Yp = qamw.matmul(X, pk, nr, cb, bits, block, chan_scale=s, signs=sg, pair_sigma=sigma)
+                    torch.cuda.synchronize()
+                finally:
+                    qamw.set_kernel_path(prev)
+                assert torch.equal(Yp, Y), f"kernel path {path}"
+
+
 @pytest.mark.parametrize("m", [1, 3, 20])
 def test_fused_matmul_batch_equals_single_calls(orc, codebooks, m):
     """Several independent products in one call give, bit for bit, what one call per matrix gives (vector kernel
