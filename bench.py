@@ -10,9 +10,10 @@ rotation, nearest codeword, bit-pack), then decode of every layer to bf16 (one l
                     [--polar] [--no-pruned] [--no-cpu-baseline]
 
 Beside the step: N decode-only passes over the set, one encode pass with the pruned nearest-codeword search
-(`pruned_search`; same indices, not part of `value` or of a roofline fraction), and on request the fused
-dequantise-and-multiply for M activation rows (`fused_matmul`: one call per layer, its products as if independent,
-and one call per activation site, as a forward pass issues them) and the polar baseline (`polar_baseline`).
+(`pruned_search`; same indices, not part of `value` or of a roofline fraction), the fused dequantise-and-multiply
+for M activation rows, 1 by default (`fused_matmul`: one call per layer, its products as if independent, and one call
+per activation site, as a forward pass issues them; `--matmul 0` skips it), and on request the polar baseline
+(`polar_baseline`).
 
 Timing uses HIP events recorded on the stream the kernels are launched on.
 """
@@ -152,8 +153,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="0 = the workload's own layer count")
     ap.add_argument("--decode-passes", type=int, default=10,
                     help="extra decode-only passes over the whole weight set after the timed steps (median and best reported)")
-    ap.add_argument("--matmul", type=int, default=0, metavar="M",
-                    help="also time the fused dequantise-and-multiply with M activation rows (1..64; more than 8 run on the matrix cores) over the whole set")
+    ap.add_argument("--matmul", type=int, default=1, metavar="M",
+                    help="also time the fused dequantise-and-multiply with M activation rows (1..64; more than 8 run on the matrix cores) over the whole set; 0 skips it")
     ap.add_argument("--matmul-calls", default="both", choices=("both", "layer", "site"),
                     help="fused-matmul leg: one call per layer, one per activation site, or both (default)")
     ap.add_argument("--matmul-path", type=int, default=0, choices=(0, 1, 2),
