@@ -131,6 +131,22 @@ int qamw_calibrate_sigma(const void *W, int dtype, int d_out, int d_in, int64_t 
                          int max_rows, void *workspace, size_t workspace_bytes, float *sigma_out,
                          void *stream);
 
+/* qamw_calibrate_sigma for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the workspace,
+ * same kernels, same result bit for bit; the scratch is a static device array of QAMW_STATIC_SCRATCH_BYTES
+ * inside the library (every GPU the library runs on holds it until the process ends).  The call allocates
+ * and frees nothing.  The first call on a device looks up the array's address on that device (no allocation,
+ * but make that first call outside a capture).
+ * Limit: qamw_calibrate_workspace_bytes(d_in, d_out, max_rows) <= QAMW_STATIC_SCRATCH_BYTES, i.e. d_in up to
+ * 16384 at max_rows = 1024; anything larger -> QAMW_ERR_UNSUPPORTED, nothing launched.
+ * All calls on one GPU share the one array: calls that overlap on the same GPU (different streams, or
+ * threads) race and give wrong pair scales; order them on one stream or use qamw_calibrate_sigma with
+ * separate workspaces.  Nothing in the array has to be cleared between calls. */
+enum { QAMW_STATIC_SCRATCH_BYTES = 8 * 1024 * 1024 + 4096 };
+int qamw_calibrate_sigma_static(const void *W, int dtype, int d_out, int d_in, int64_t ldw,
+                                const float *chan_scale, const int8_t *signs, int hadamard_block,
+                                int max_rows, float *sigma_out, void *stream);
+
 /* Encoder of Sec. 3.1 with the channel scaling of Sec. B.2.
  * packed_out: device, d_out * qamw_packed_row_bytes(d_in, bits) bytes, fully overwritten.
  * row_norms_out: device, d_out floats (norm of the SCALED row W D_s). */

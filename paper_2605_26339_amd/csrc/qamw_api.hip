@@ -1,6 +1,7 @@
 // libqamw device entry points: argument validation on the host, then kernel dispatch.
 #include <atomic>
 #include <cmath>
+#include <mutex>
 
 #include "qamw.h"
 #include "qamw_internal.hpp"
@@ -79,17 +80,9 @@ int qamw_calibrate_workspace_bytes(int d_in, int d_out, int max_rows, size_t *by
     return QAMW_OK;
 }
 
-int qamw_calibrate_sigma(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
-                         const int8_t *signs, int hadamard_block, int max_rows, void *workspace,
-                         size_t workspace_bytes, float *sigma_out, void *stream) {
-    if (!W || !workspace || !sigma_out || max_rows < 1) return QAMW_ERR_INVALID_ARG;
-    if (dtype != QAMW_DTYPE_F32 && dtype != QAMW_DTYPE_BF16) return QAMW_ERR_INVALID_ARG;
-    int rc = check_common(d_out, d_in, 1, hadamard_block);
-    if (rc != QAMW_OK) return rc;
-    if (ldw < d_in) return QAMW_ERR_SHAPE;
-    size_t need = 0;
-    qamw_calibrate_workspace_bytes(d_in, d_out, max_rows, &need);
-    if (workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15)) return QAMW_ERR_INVALID_ARG;
+static int calibrate_impl(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
+                          const int8_t *signs, int hadamard_block, int max_rows, void *workspace, float *sigma_out,
+                          void *stream) {
     qamw::Problem p = make_problem(d_out, d_in, chan_scale, signs, nullptr, nullptr, 1, hadamard_block, stream);
     const int n = d_out < max_rows ? d_out : max_rows;
     float *row_norms = static_cast<float *>(workspace);
@@ -101,6 +94,81 @@ int qamw_calibrate_sigma(const void *W, int dtype, int d_out, int d_in, int64_t 
     else
         e = qamw::launch_calibrate_general(W, dtype, ldw, n, p, row_norms, sigma_out);
     return e == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
+}
+
+static int calibrate_check(const void *W, int dtype, int d_out, int d_in, int64_t ldw, int hadamard_block, int max_rows,
+                           const float *sigma_out) {
+    if (!W || !sigma_out || max_rows < 1) return QAMW_ERR_INVALID_ARG;
+    if (dtype != QAMW_DTYPE_F32 && dtype != QAMW_DTYPE_BF16) return QAMW_ERR_INVALID_ARG;
+    int rc = check_common(d_out, d_in, 1, hadamard_block);
+    if (rc != QAMW_OK) return rc;
+    return ldw < d_in ? QAMW_ERR_SHAPE : QAMW_OK;
+}
+
+int qamw_calibrate_sigma(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
+                         const int8_t *signs, int hadamard_block, int max_rows, void *workspace,
+                         size_t workspace_bytes, float *sigma_out, void *stream) {
+    if (!workspace) return QAMW_ERR_INVALID_ARG;
+    int rc = calibrate_check(W, dtype, d_out, d_in, ldw, hadamard_block, max_rows, sigma_out);
+    if (rc != QAMW_OK) return rc;
+    size_t need = 0;
+    qamw_calibrate_workspace_bytes(d_in, d_out, max_rows, &need);
+    if (workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15)) return QAMW_ERR_INVALID_ARG;
+    return calibrate_impl(W, dtype, d_out, d_in, ldw, chan_scale, signs, hadamard_block, max_rows, workspace, sigma_out, stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The calibration for callers that cannot allocate: its scratch is this file-scope device array.
+// Every device the library runs on holds its own copy at its own address; the name below is only
+// the host-side handle of the symbol, the address kernels get is the one hipGetSymbolAddress
+// returns for the current device, looked up once per device and kept.
+// ---------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[QAMW_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device (nullptr + *err on failure).
+void *static_scratch(hipError_t *err) {
+    int dev = -1;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= MAX_DEVICES) {
+        *err = hipErrorInvalidDevice;
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        *err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (*err != hipSuccess || !ptr) {
+            if (*err == hipSuccess) *err = hipErrorInvalidSymbol;
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+int qamw_calibrate_sigma_static(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
+                                const int8_t *signs, int hadamard_block, int max_rows, float *sigma_out, void *stream) {
+    int rc = calibrate_check(W, dtype, d_out, d_in, ldw, hadamard_block, max_rows, sigma_out);
+    if (rc != QAMW_OK) return rc;
+    size_t need = 0;
+    qamw_calibrate_workspace_bytes(d_in, d_out, max_rows, &need);
+    if (need > (size_t)QAMW_STATIC_SCRATCH_BYTES) return QAMW_ERR_UNSUPPORTED;   // beyond the library's own scratch
+    hipError_t e = hipSuccess;
+    void *ws = static_scratch(&e);
+    if (!ws) {
+        (void)hipGetLastError();
+        return QAMW_ERR_DEVICE;
+    }
+    // Nothing in the scratch has to start at zero: the row norms and every partial sum the finishing kernel
+    // reads are written by this call's own kernels before they are read.
+    return calibrate_impl(W, dtype, d_out, d_in, ldw, chan_scale, signs, hadamard_block, max_rows, ws, sigma_out, stream);
 }
 
 static int encode_impl(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,

@@ -22,7 +22,7 @@ EXPORTS = [
     "qamw_decode_f32", "qamw_decode_batch", "qamw_set_kernel_path", "qamw_polar_codebook", "qamw_encode_polar",
     "qamw_matmul_workspace_bytes", "qamw_matmul", "qamw_matmul_batch", "qamw_encode_stats",
     "qamw_normalised_pairs", "qamw_lloyd_workspace_bytes", "qamw_lloyd_device",
-    "qamw_search_grid_size", "qamw_search_grid_build", "qamw_encode_pruned",
+    "qamw_search_grid_size", "qamw_search_grid_build", "qamw_encode_pruned", "qamw_calibrate_sigma_static",
 ]
 
 
@@ -74,6 +74,7 @@ def lib() -> C.CDLL:
         L.qamw_train_codebook.argtypes = [i32, u64, u64, i32, C.c_double, vp, C.POINTER(C.c_double), C.POINTER(i32)]
         L.qamw_calibrate_workspace_bytes.argtypes = [i32, i32, i32, C.POINTER(C.c_size_t)]
         L.qamw_calibrate_sigma.argtypes = [vp, i32, i32, i32, i64, vp, vp, i32, i32, vp, C.c_size_t, vp, vp]
+        L.qamw_calibrate_sigma_static.argtypes = [vp, i32, i32, i32, i64, vp, vp, i32, i32, vp, vp]
         L.qamw_encode.argtypes = [vp, i32, i32, i32, i64, vp, vp, vp, vp, i32, i32, vp, vp, vp]
         L.qamw_encode_stats.argtypes = [vp, i32, i32, i32, i64, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
         L.qamw_decode.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, i64, vp]
@@ -246,6 +247,19 @@ def calibrate_sigma(W, block: int, chan_scale=None, signs=None, max_rows: int = 
     _check(lib().qamw_calibrate_sigma(_ptr(W), _dtype_code(W), d_out, d_in, W.stride(0), _ptr(chan_scale), _ptr(signs),
                                       block, max_rows, _ptr(workspace), workspace.numel(), _ptr(out), _stream(stream)),
            "qamw_calibrate_sigma")
+    return out
+
+
+STATIC_SCRATCH_BYTES = 8 * 1024 * 1024 + 4096
+
+
+def calibrate_sigma_static(W, block: int, out, chan_scale=None, signs=None, max_rows: int = 1024, stream=None):
+    """qamw_calibrate_sigma_static: the pair scales written into `out` (float32 CUDA [d_in/2]) with the library's own
+    static scratch; this wrapper allocates nothing either."""
+    _require_cuda(W, chan_scale, signs, out)
+    d_out, d_in = W.shape
+    _check(lib().qamw_calibrate_sigma_static(_ptr(W), _dtype_code(W), d_out, d_in, W.stride(0), _ptr(chan_scale), _ptr(signs),
+                                             block, max_rows, _ptr(out), _stream(stream)), "qamw_calibrate_sigma_static")
     return out
 
 

@@ -131,6 +131,22 @@ def test_device_entry_points_reject_bad_arguments_before_any_launch():
     assert L.qamw_calibrate_workspace_bytes(256, 8, 1024, None) == qamw.ERR_INVALID_ARG
 
 
+    # the variant with the library's own static scratch: same checks, and the size limit, all before HIP is touched
+    def cal_static(**kw):
+        a = {**good, "max_rows": 1024, **kw}
+        return L.qamw_calibrate_sigma_static(a["W"], a["dtype"], a["d_out"], a["d_in"], a["ldw"], a["s"], a["sg"], a["block"],
+                                             a["max_rows"], a["packed"], a["stream"])
+
+    assert cal_static(W=None) == qamw.ERR_INVALID_ARG
+    assert cal_static(packed=None) == qamw.ERR_INVALID_ARG
+    assert cal_static(max_rows=0) == qamw.ERR_INVALID_ARG
+    assert cal_static(block=3) == qamw.ERR_SHAPE
+    assert cal_static(ldw=10) == qamw.ERR_SHAPE
+    assert cal_static(dtype=2) == qamw.ERR_INVALID_ARG
+    assert qamw.calibrate_workspace_bytes(16384, 4096, 1024) <= qamw.STATIC_SCRATCH_BYTES
+    assert cal_static(d_out=2048, d_in=16512, ldw=16512) == qamw.ERR_UNSUPPORTED   # beyond the static scratch
+
+
 def test_decode_batch_rejects_bad_arguments():
     L = qamw.lib()
     p = 0x1000
