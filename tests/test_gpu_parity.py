@@ -733,9 +733,10 @@ def test_full_size_matrices_sampled_rows(orc, codebooks, wl_name, mat):
     rows = _sampled_rows(d_out, 64, 7)
     rows_t = torch.from_numpy(rows).cuda()
     Wrows = Wd[rows_t].float().cpu().numpy()
-    ref = orc.encode(Wrows, codebooks[wl.bits], wl.bits, wl.block, chan_scale=s, signs=sg, pair_sigma=sigma, threads=16)
+    ref = orc.encode(Wrows, codebooks[wl.bits], wl.bits, wl.block, chan_scale=s, signs=sg, pair_sigma=sigma, want_x=True,
+                     threads=16)
     case = Case.__new__(Case)
-    case.d_in, case.bits = d_in, wl.bits
+    case.d_in, case.bits, case.cb = d_in, wl.bits, codebooks[wl.bits]
     rep = {}
     check_encode(orc, case, packed_d[rows_t].cpu().numpy(), norms_d[rows_t].cpu().numpy(), ref, report=rep)
     say("   ", rep)
@@ -802,6 +803,111 @@ def test_full_layer_in_the_bench_configuration(orc, codebooks):
         say(f"    {m['name']}: decode {rep}, product error / (||x|| ||w||) max {float((err / (bound / 1e-6)).max()):.1e}")
 
 
+def _device_layer(wl, layer, cb_d):
+    """One layer of a workload as bench.py builds and runs it: weights generated on the device, per-matrix calibration
+    and encode, ONE qamw_decode_batch launch for the layer.  Returns a list of dicts (device tensors + host side inputs)."""
+    mats, entries = [], []
+    for name, d_out, d_in, site in wl.matrices:
+        Wd = synth.weight_device(synth.seed_for(wl.config_id, layer, name), d_out, d_in, wl.row_sigma, wl.dtype)
+        s = qamw.channel_scales(synth.act_rms_host(synth.seed_for(wl.config_id, layer, site), d_in), wl.alpha)
+        sg = qamw.sign_mask(synth.seed_for(wl.config_id, layer, "mask-" + site), d_in)
+        s_d, sg_d = torch.from_numpy(s).cuda(), torch.from_numpy(sg).cuda()
+        sigma_d = qamw.calibrate_sigma(Wd, wl.block, chan_scale=s_d, signs=sg_d)
+        packed_d, norms_d = qamw.encode(Wd, cb_d, wl.bits, wl.block, chan_scale=s_d, signs=sg_d, pair_sigma=sigma_d)
+        out_d = torch.empty((d_out, d_in), dtype=torch.bfloat16, device="cuda")
+        mats.append(dict(name=name, d_out=d_out, d_in=d_in, W=Wd, s=s, sg=sg, s_d=s_d, sg_d=sg_d, sigma_d=sigma_d,
+                         packed=packed_d, norms=norms_d, out=out_d))
+        entries.append((packed_d, norms_d, d_in, s_d, sg_d, sigma_d, out_d))
+    qamw.decode_batch(qamw.make_decode_items(entries), cb_d, wl.bits, wl.block)
+    torch.cuda.synchronize()
+    return mats
+
+
+def _stub_case(m, wl, cb, sigma):
+    case = Case.__new__(Case)
+    case.d_in, case.bits, case.block, case.cb, case.s, case.sg, case.sigma = m["d_in"], wl.bits, wl.block, cb, m["s"], m["sg"], sigma
+    return case
+
+
+@pytest.mark.parametrize("layer", range(22))
+def test_c1_every_matrix_every_row(orc, codebooks, layer):
+    """The whole TinyLlama-shaped set, layer by layer, every matrix, EVERY row through the oracle: calibration, encode
+    (indices, norms, packed bytes) and decode (fp32 value and bf16, the layer decoded by one batch launch)."""
+    wl = synth.WORKLOADS["c1_tinyllama_1.1b"]
+    cb = codebooks[wl.bits]
+    cb_d = torch.from_numpy(cb).cuda()
+    say(f"[c1 every row] layer {layer}")
+    for m in _device_layer(wl, layer, cb_d):
+        W = m["W"].float().cpu().numpy()
+        sigma = m["sigma_d"].cpu().numpy()
+        want_sigma = orc.calibrate_sigma(W[:1024], wl.block, chan_scale=m["s"], signs=m["sg"])
+        assert np.allclose(sigma, want_sigma, rtol=1e-6, atol=0)
+        case = _stub_case(m, wl, cb, sigma)
+        ref = orc.encode(W, cb, wl.bits, wl.block, chan_scale=m["s"], signs=m["sg"], pair_sigma=sigma, want_x=True, threads=16)
+        packed, norms = m["packed"].cpu().numpy(), m["norms"].cpu().numpy()
+        rep = {}
+        check_encode(orc, case, packed, norms, ref, report=rep)
+        del ref
+        f32 = qamw.decode(m["packed"], m["norms"], m["d_in"], cb_d, wl.bits, wl.block, chan_scale=m["s_d"], signs=m["sg_d"],
+                          pair_sigma=m["sigma_d"], f32=True).cpu().numpy()
+        got16 = m["out"].cpu().view(torch.int16).numpy().view(np.uint16)
+        drep = check_decode(orc, case, orc.unpack(packed, m["d_in"], wl.bits), norms, got_f32=f32, got_bf16=got16, threads=16)
+        say(f"    {m['name']} {m['d_out']}x{m['d_in']}: {rep} {drep}")
+
+
+@pytest.mark.parametrize("wl_name", ["c2_llama2_7b_b11", "c3_llama2_7b_b7", "c4_llama2_13b_b11"])
+def test_full_layer_decode_every_row(orc, codebooks, wl_name):
+    """One whole layer of each large workload in the benchmark's launch configuration (one decode launch for the
+    layer's seven matrices): EVERY row of every decoded matrix against the oracle, element by element (bf16 within one
+    ulp; the fp32 value before the cast within 1e-5 relative), plus calibration and 64 sampled rows of encode per matrix."""
+    wl = synth.WORKLOADS[wl_name]
+    cb = codebooks[wl.bits]
+    cb_d = torch.from_numpy(cb).cuda()
+    say(f"[every row] {wl_name} layer 0")
+    for m in _device_layer(wl, 0, cb_d):
+        d_out, d_in = m["d_out"], m["d_in"]
+        sigma = m["sigma_d"].cpu().numpy()
+        head = m["W"][:1024].float().cpu().numpy()
+        assert np.allclose(sigma, orc.calibrate_sigma(head, wl.block, chan_scale=m["s"], signs=m["sg"]), rtol=1e-6, atol=0)
+        case = _stub_case(m, wl, cb, sigma)
+        rows = _sampled_rows(d_out, 64, 21)
+        rows_t = torch.from_numpy(rows).cuda()
+        ref = orc.encode(m["W"][rows_t].float().cpu().numpy(), cb, wl.bits, wl.block, chan_scale=m["s"], signs=m["sg"],
+                         pair_sigma=sigma, want_x=True, threads=16)
+        rep = {}
+        check_encode(orc, case, m["packed"][rows_t].cpu().numpy(), m["norms"][rows_t].cpu().numpy(), ref, report=rep)
+        del m["W"]
+        packed, norms = m["packed"].cpu().numpy(), m["norms"].cpu().numpy()
+        idx = orc.unpack(packed, d_in, wl.bits)
+        spec = case.oracle_decode(orc, idx, norms, threads=16)
+        got16 = m["out"].cpu().view(torch.int16).numpy().view(np.uint16)
+        d = np.abs(bf16_order(got16) - bf16_order(spec["bf16"]))
+        assert d.max() <= 1
+        bf_exact = float((d == 0).mean())
+        del d, got16
+        f32 = qamw.decode(m["packed"], m["norms"], d_in, cb_d, wl.bits, wl.block, chan_scale=m["s_d"], signs=m["sg_d"],
+                          pair_sigma=m["sigma_d"], f32=True).cpu().numpy()
+        worst = 0.0
+        for r0 in range(0, d_out, 2048):                      # in row blocks: bounded host memory
+            refw = spec["w"][r0:r0 + 2048]
+            err = np.abs(f32[r0:r0 + 2048].astype(np.float64) - refw)
+            assert np.all(err <= 1e-5 * np.abs(refw) + 1e-37)
+            worst = max(worst, float((err / (np.abs(refw) + 1e-300)).max()))
+        say(f"    {m['name']} {d_out}x{d_in}: all {d_out} rows decoded: bf16 exact {bf_exact:.6f}, fp32 max rel {worst:.2e}; "
+            f"encode (64 rows) {rep}")
+        del spec, f32, idx
+
+
+def _pairs_close_where_norm_is_one_ulp_off(pairs, x_ref, same):
+    """Rows whose norm differs from the oracle's in its last bit: every point within 2e-6 (1 + max |x| of the row) of
+    the oracle's (one ulp of the norm moves u by 2^-23 relative; the butterflies add rounding differences of that size)."""
+    off = ~same
+    if off.any():
+        xr = x_ref[off]
+        tol = 2e-6 * (1.0 + np.abs(xr).max(axis=(1, 2), keepdims=True))
+        assert np.all(np.abs(pairs[off].astype(np.float64) - xr) <= tol)
+
+
 @pytest.mark.parametrize("d_out,d_in,block,dtype,sigma", [(19, 2048, 128, "bf16", "calibrated"), (7, 5632, 512, "f32", None)])
 def test_normalised_pairs_are_the_encoders_points(orc, d_out, d_in, block, dtype, sigma):
     """The pairs written out by the library are, bit for bit, the oracle's fp32-ordered front half."""
@@ -817,6 +923,7 @@ def test_normalised_pairs_are_the_encoders_points(orc, d_out, d_in, block, dtype
     same = got_norms == ref_norms                              # a norm may differ in its last bit (fp64 summation order)
     assert np.abs(got_norms.view(np.int32).astype(np.int64) - ref_norms.view(np.int32).astype(np.int64)).max() <= 1
     assert np.array_equal(pairs.cpu().numpy()[same], ref["x"].astype(np.float32)[same])
+    _pairs_close_where_norm_is_one_ulp_off(pairs.cpu().numpy(), ref["x"], same)
 
 
 @pytest.mark.parametrize("kind", ["wide_range", "zeros_and_tiny"])
@@ -847,6 +954,8 @@ def test_row_normalisation_is_the_correctly_rounded_quotient(orc, kind):
     same = got_norms == ref_norms
     assert same.sum() >= 0.9 * d_out
     assert np.array_equal(pairs.cpu().numpy()[same], ref["x"].astype(np.float32)[same])
+    assert np.abs(got_norms.view(np.int32).astype(np.int64) - ref_norms.view(np.int32).astype(np.int64)).max() <= 1
+    _pairs_close_where_norm_is_one_ulp_off(pairs.cpu().numpy(), ref["x"], same)
 
 
 @pytest.mark.parametrize("K,iters", [(16, 1), (16, 4), (64, 12)])
