@@ -287,6 +287,16 @@ enum { QAMW_MAX_BATCH = 16 };
 int qamw_decode_batch(const qamw_decode_item *items, int n_items, const float *codebook, int bits,
                       int hadamard_block, void *stream);
 
+/* Measurement aid for the decoder of Sec. 3.2: the launch of qamw_decode_batch for these items with every load and
+ * store it issues (same addresses, widths, order and launch shape) and none of the arithmetic in between.  The time of
+ * this launch is what the memory system allows the decoder's access pattern, i.e. the ceiling its bandwidth figure is
+ * to be read against.  W_out of every item is OVERWRITTEN WITH MEANINGLESS VALUES.  Only for shapes the fast decoder
+ * takes (bits in {7, 8, 11}, hadamard_block >= 64, d_in a multiple of max(hadamard_block, 16), 16-byte aligned outputs
+ * and side vectors, 4-byte aligned packed rows); anything else -> QAMW_ERR_UNSUPPORTED, nothing launched.
+ * Errors otherwise as qamw_decode_batch. */
+int qamw_decode_traffic_probe(const qamw_decode_item *items, int n_items, const float *codebook, int bits,
+                              int hadamard_block, void *stream);
+
 /* Fused dequantise-and-multiply (the follow-up named in the paper's Limitations, "No fused
  * dequantization-matmul kernel"): Y = X W^T for m <= QAMW_MATMUL_MAX_ROWS activation rows, W = the matrix
  * that qamw_decode_f32 would produce from (packed, row_norms, ...), without materialising W.

@@ -288,8 +288,8 @@ int qamw_decode(const uint8_t *packed, const float *row_norms, int d_out, int d_
                       W_out, ldo, stream, true);
 }
 
-int qamw_decode_batch(const qamw_decode_item *items, int n_items, const float *codebook, int bits, int hadamard_block,
-                      void *stream) {
+static int decode_batch_impl(const qamw_decode_item *items, int n_items, const float *codebook, int bits, int hadamard_block,
+                             void *stream, bool traffic_only) {
     static_assert(QAMW_MAX_BATCH == qamw::QAMW_DECODE_MAX_BATCH, "batch limits differ");
     if (!items || !codebook || n_items < 1 || n_items > QAMW_MAX_BATCH) return QAMW_ERR_INVALID_ARG;
     qamw::DecodeItem its[QAMW_MAX_BATCH];
@@ -303,11 +303,12 @@ int qamw_decode_batch(const qamw_decode_item *items, int n_items, const float *c
     }
     qamw::Problem shared = make_problem(items[0].d_out, items[0].d_in, nullptr, nullptr, nullptr, codebook, bits,
                                         hadamard_block, stream);
-    if (g_kernel_path.load() != 1) {
-        hipError_t e = qamw::launch_decode_batch_fast(its, n_items, shared, true);
+    if (g_kernel_path.load() != 1 || traffic_only) {
+        hipError_t e = qamw::launch_decode_batch_fast(its, n_items, shared, true, traffic_only);
         if (e == hipSuccess) return QAMW_OK;
         if (e != hipErrorNotSupported) return QAMW_ERR_DEVICE;
     }
+    if (traffic_only) return QAMW_ERR_UNSUPPORTED;              // only the fast kernel has this mode
     for (int i = 0; i < n_items; ++i) {                         // nothing was launched: one general launch per item
         const qamw_decode_item &q = items[i];
         int rc = decode_any(q.packed, q.row_norms, q.d_out, q.d_in, q.chan_scale, q.signs, q.pair_sigma, codebook, bits,
@@ -315,6 +316,16 @@ int qamw_decode_batch(const qamw_decode_item *items, int n_items, const float *c
         if (rc != QAMW_OK) return rc;
     }
     return QAMW_OK;
+}
+
+int qamw_decode_batch(const qamw_decode_item *items, int n_items, const float *codebook, int bits, int hadamard_block,
+                      void *stream) {
+    return decode_batch_impl(items, n_items, codebook, bits, hadamard_block, stream, false);
+}
+
+int qamw_decode_traffic_probe(const qamw_decode_item *items, int n_items, const float *codebook, int bits,
+                              int hadamard_block, void *stream) {
+    return decode_batch_impl(items, n_items, codebook, bits, hadamard_block, stream, true);
 }
 
 int qamw_matmul_workspace_bytes(int d_in, int d_out, int m, size_t *bytes_out) {

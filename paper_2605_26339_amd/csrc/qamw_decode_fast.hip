@@ -23,6 +23,7 @@ constexpr int DF_THREADS = QAMW_DF_THREADS;
 constexpr int DF_WAVES = DF_THREADS / WAVE;
 constexpr int SLAB = 1024;
 constexpr int DF_MAX_BATCH = QAMW_DECODE_MAX_BATCH;
+constexpr int DF_MAX_K = 2048;
 // Rows of one unit of work: a wave requests the packed words of all of them at the start, in two halves, and
 // computes and stores one half while the other is still on its way.  Small units mean many waves per launch and a
 // short dependent chain per wave; measured best (7B and 13B shapes): 8 rows at 11 bits (704 packed bytes per row
@@ -33,11 +34,19 @@ typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float floatx2_t __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
-// Field i (i = 0..7) of a lane's 8*BITS-bit group, the group starting at bit 0 of w[0..2].
-template <int BITS> __device__ __forceinline__ uint32_t field(const uint32_t (&w)[4], int i) {
-    const int bit = i * BITS, word = bit >> 5, off = bit & 31;
-    uint32_t v = (off + BITS <= 32) ? (w[word] >> off) : __builtin_amdgcn_alignbit(w[word + 1], w[word], off);
-    return v & ((1u << BITS) - 1u);
+// Field i (i = 0..7) of a lane's 8*BITS-bit group (the group starts at bit 0 of w[0..2]) as a byte offset into the
+// codebook: index * 8 = (stream >> (bit - 3)) & mask8, one shift or funnel shift and one AND with the mask held in a
+// register (an AND of two registers issues at twice the rate of one with a literal operand).
+template <int BITS> __device__ __forceinline__ uint32_t field_x8(const uint32_t (&w)[4], int i, uint32_t mask8) {
+    const int bit = i * BITS, word = bit >> 5, off = bit & 31, s = off - 3;
+    uint32_t v;
+    if (s < 0)
+        v = w[word] << (-s);
+    else if (off + BITS <= 32)
+        v = w[word] >> s;
+    else
+        v = __builtin_amdgcn_alignbit(w[word + 1], w[word], s);
+    return v & mask8;
 }
 
 // Reciprocal with one Newton step: the correctly rounded quotient in all but a few rare cases
@@ -49,32 +58,33 @@ __device__ __forceinline__ float fast_recip(float s) {
 }
 
 // Per-lane column constants of 16 consecutive columns starting at c (a multiple of 16):
-// qs[e] = parity / s_j with the sign mask folded in, sig[k] = sigma of the lane's 8 pairs.
-// Vector loads: the host checks that the arrays are 16-byte aligned.
-__device__ __forceinline__ void load_column_constants(float (&qs)[16], float (&sig)[8], const Problem &p, int c,
-                                                      float parity) {
+// qs[e] = 1 / s_j carrying the sign mask in its sign bit, sig[k] = sigma of the lane's 8 pairs.
+// (The transform's lane sign is not folded in here: it rides on the row factor, one multiply per row instead of 16
+// per unit.)  Vector loads: the host checks that the arrays are 16-byte aligned.
+__device__ __forceinline__ void load_column_constants(float (&qs)[16], float (&sig)[8], const Problem &p, int c) {
     if (p.chan_scale) {
         const float4 *s4 = reinterpret_cast<const float4 *>(p.chan_scale + c);
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             float4 v = s4[t];
-            qs[4 * t] = fast_recip(v.x) * parity;
-            qs[4 * t + 1] = fast_recip(v.y) * parity;
-            qs[4 * t + 2] = fast_recip(v.z) * parity;
-            qs[4 * t + 3] = fast_recip(v.w) * parity;
+            qs[4 * t] = fast_recip(v.x);
+            qs[4 * t + 1] = fast_recip(v.y);
+            qs[4 * t + 2] = fast_recip(v.z);
+            qs[4 * t + 3] = fast_recip(v.w);
         }
     } else {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) qs[e] = parity;
+        for (int e = 0; e < 16; ++e) qs[e] = 1.0f;
     }
     if (p.signs) {
         const uint4 sg = *reinterpret_cast<const uint4 *>(p.signs + c);
         const uint32_t wds[4] = {sg.x, sg.y, sg.z, sg.w};
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            // int8 -1 = 0xFF: bit 7 of the byte is the sign; move it onto the float's sign bit
-            uint32_t neg = (wds[e >> 2] >> (8 * (e & 3) + 7)) & 1u;
-            qs[e] = __uint_as_float(__float_as_uint(qs[e]) ^ (neg << 31));
+            // int8 -1 = 0xFF: bit 7 of the byte is the sign.  A shift brings it to bit 31 and a bit-field insert
+            // replaces the sign bit of the (positive) reciprocal with it.  s_j > 0 is the contract.
+            const uint32_t at31 = wds[e >> 2] << (24 - 8 * (e & 3));
+            qs[e] = __uint_as_float((__float_as_uint(qs[e]) & 0x7FFFFFFFu) | (at31 & 0x80000000u));
         }
     }
     if (p.pair_sigma) {
@@ -120,10 +130,16 @@ struct DecodeBatch {
 // the unit are requested before anything is stored, so a wave never waits for its own stores to
 // drain before its loads are under way (loads and stores retire through one in-order counter on
 // this chip).
-template <int BITS, int B, bool OUT_BF16, int R>
-__global__ __launch_bounds__(DF_THREADS) void k_decode_fast(DecodeBatch bt, int n_waves) {
+// TRAFFIC_ONLY: the same loads and stores (addresses, widths, order, launch shape) with the arithmetic between them
+// left out -- what is stored is a meaningless mix of what was loaded.  It measures what the memory system gives this
+// access pattern, i.e. the ceiling of the decoder proper.
+// Register budget: the bf16 kernel with 8-row units fits 80 registers (6 waves per SIMD) without spilling; the
+// 16-row units, the fp32 output and blocks beyond 256 (their swap stages) need more and are left at 4.
+#define QAMW_DF_WAVES_PER_EU ((R > 4 || !OUT_BF16 || B > 256) ? 4 : 6)
+template <int BITS, int B, bool OUT_BF16, int R, bool TRAFFIC_ONLY = false>
+__global__ __launch_bounds__(DF_THREADS) __attribute__((amdgpu_waves_per_eu(QAMW_DF_WAVES_PER_EU))) void k_decode_fast(DecodeBatch bt, int n_waves) {
     constexpr int UNIT = 2 * R;                                 // rows of a unit: two halves of R rows
-    extern __shared__ float2 cb_lds[];                          // K codewords
+    __shared__ float2 cb_lds[DF_MAX_K];                         // K <= DF_MAX_K codewords; a static array: its address folds into the gathers' offset field
     typedef u32x4_t u32x4_a4_t __attribute__((aligned(4)));     // a 16-byte load that is only 4-byte aligned
     const int lane = threadIdx.x & (WAVE - 1);
     const int wid = threadIdx.x >> 6;
@@ -132,6 +148,7 @@ __global__ __launch_bounds__(DF_THREADS) void k_decode_fast(DecodeBatch bt, int 
     const int pos = slab_pos(lane);
     // after the half exchange: whose sub-block this lane stores in the first / second store instruction, and which half
     const int pos_a = slab_pos(lane & 31), pos_b = slab_pos((lane & 31) + 32), half = lane >> 5;
+    const uint32_t off_a = (uint32_t)(2 * pos_a + half) * 16u, off_b = (uint32_t)(2 * pos_b + half) * 16u;   // byte offsets inside the slab's 2 KB
 
     // n_waves = number of units.  A surplus wave of the last block goes through the motions on the last unit
     // (it has to reach the barrier below) and stores nothing.
@@ -150,7 +167,9 @@ __global__ __launch_bounds__(DF_THREADS) void k_decode_fast(DecodeBatch bt, int 
     const int d_in = M.d_in, last_row = M.d_out - 1;
     const int64_t row_bytes = M.row_bytes, ldo = M.ldo;
     const uint8_t *packed = M.packed;
-    const float *norms = M.norms;
+    // the row norms are the same for every lane: read through the scalar data path (constant address space)
+    typedef const float __attribute__((address_space(4))) *const_f32_ptr;
+    const_f32_ptr norms = (const_f32_ptr)(uintptr_t)M.norms;
     void *out = M.out;
 
     const int col0 = slab * SLAB + 16 * pos;
@@ -163,6 +182,9 @@ __global__ __launch_bounds__(DF_THREADS) void k_decode_fast(DecodeBatch bt, int 
     const int sh = (int)(lane_off & 3u) * 8;
     const unsigned row_dw = (unsigned)(row_bytes >> 2);
 
+    const float isb_parity = bt.inv_sqrt_block * ls.parity;     // exact: parity is +-1
+    uint32_t mask8;                                             // ((1 << BITS) - 1) * 8 in a register the optimiser cannot fold back into a literal
+    asm volatile("v_mov_b32 %0, %1" : "=v"(mask8) : "n"(((1 << BITS) - 1) * 8));
     float qs[16], sig[8];
     {
         Problem pc;
@@ -170,7 +192,7 @@ __global__ __launch_bounds__(DF_THREADS) void k_decode_fast(DecodeBatch bt, int 
         pc.signs = M.signs;
         pc.pair_sigma = M.pair_sigma;
         pc.sigma_default = M.sigma_default;
-        load_column_constants(qs, sig, pc, c, ls.parity);
+        load_column_constants(qs, sig, pc, c);
     }
 
     // FULL: every row of the unit exists and is not the matrix's last row, and the slab has all 1024
@@ -236,6 +258,16 @@ __global__ __launch_bounds__(DF_THREADS) void k_decode_fast(DecodeBatch bt, int 
 #pragma unroll
             for (int t = 0; t < R; ++t) {
                 const int row = row0 + sub + t;
+                if (TRAFFIC_ONLY) {
+                    const uint32_t mix = __float_as_uint(rn[t]) ^ __float_as_uint(qs[t]) ^ __float_as_uint(sig[t & 7]);
+                    const u32x4_t va = {d[t][0] ^ mix, d[t][1], d[t][2], d[t][3]}, vb = {d[t][3], d[t][2] ^ mix, d[t][1], d[t][0]};
+                    if (FULL || row <= last_row) {
+                        u32x4_t *dst = reinterpret_cast<u32x4_t *>(reinterpret_cast<uint16_t *>(out) + (int64_t)row * ldo + slab * SLAB);
+                        if (FULL || 16 * pos_a < slab_cols) __builtin_nontemporal_store(va, dst + 2 * pos_a + half);
+                        if (FULL || 16 * pos_b < slab_cols) __builtin_nontemporal_store(vb, dst + 2 * pos_b + half);
+                    }
+                    continue;
+                }
                 uint32_t w[4];
                 w[0] = __builtin_amdgcn_alignbit(d[t][1], d[t][0], sh);
                 w[1] = __builtin_amdgcn_alignbit(d[t][2], d[t][1], sh);
@@ -244,12 +276,12 @@ __global__ __launch_bounds__(DF_THREADS) void k_decode_fast(DecodeBatch bt, int 
                 float x[16];
 #pragma unroll
                 for (int k = 0; k < 8; ++k) {
-                    float2 cw = cb_lds[field<BITS>(w, k)];
+                    const float2 cw = *reinterpret_cast<const float2 *>(reinterpret_cast<const char *>(cb_lds) + field_x8<BITS>(w, k, mask8));
                     x[2 * k] = sig[k] * cw.x;
                     x[2 * k + 1] = sig[k] * cw.y;
                 }
                 fwht_wave<B>(x, ls);
-                const float a = rn[t] * bt.inv_sqrt_block;      // row factor r * block^-1/2
+                const float a = rn[t] * isb_parity;             // row factor r * block^-1/2, with the transform's lane sign
                 if (OUT_BF16) {
                     uint32_t o[8];
 #pragma unroll
@@ -269,12 +301,12 @@ __global__ __launch_bounds__(DF_THREADS) void k_decode_fast(DecodeBatch bt, int 
                         hi[q] = r[1];
                     }
                     if (FULL || row <= last_row) {
-                        u32x4_t *dst = reinterpret_cast<u32x4_t *>(reinterpret_cast<uint16_t *>(out) + (int64_t)row * ldo + slab * SLAB);
+                        char *dst = reinterpret_cast<char *>(reinterpret_cast<uint16_t *>(out) + (int64_t)row * ldo + slab * SLAB);
                         // instruction A: sub-blocks of lanes 0-31; instruction B: sub-blocks of lanes 32-63.
                         // The output is written once and not read again by this kernel: streaming stores.
                         const u32x4_t va = {lo[0], lo[1], lo[2], lo[3]}, vb = {hi[0], hi[1], hi[2], hi[3]};
-                        if (FULL || 16 * pos_a < slab_cols) __builtin_nontemporal_store(va, dst + 2 * pos_a + half);
-                        if (FULL || 16 * pos_b < slab_cols) __builtin_nontemporal_store(vb, dst + 2 * pos_b + half);
+                        if (FULL || 16 * pos_a < slab_cols) __builtin_nontemporal_store(va, reinterpret_cast<u32x4_t *>(dst + off_a));
+                        if (FULL || 16 * pos_b < slab_cols) __builtin_nontemporal_store(vb, reinterpret_cast<u32x4_t *>(dst + off_b));
                     }
                 } else if (FULL || (row <= last_row && 16 * pos < slab_cols)) {   // fp32 output (accuracy checks): plain per-lane stores
                     float4 *dst = reinterpret_cast<float4 *>(reinterpret_cast<float *>(out) + (int64_t)row * ldo + slab * SLAB + 16 * pos);
@@ -316,7 +348,7 @@ static bool decode_alignment_ok(const DecodeItem &it, bool out_bf16) {
 }
 
 template <int BITS, int B>
-static hipError_t launch_bb(const DecodeItem *items, int n, const Problem &p, bool out_bf16) {
+static hipError_t launch_bb(const DecodeItem *items, int n, const Problem &p, bool out_bf16, bool traffic_only) {
     constexpr int UNIT = df_unit_rows(BITS), R = UNIT / 2;
     DecodeBatch bt;
     int64_t units = 0;
@@ -348,8 +380,11 @@ static hipError_t launch_bb(const DecodeItem *items, int n, const Problem &p, bo
     // stride was measured slower on HBM-bound sizes: its waves move in lockstep through read and write phases.)
     const int64_t n_waves = units;
     const unsigned blocks = (unsigned)((n_waves + DF_WAVES - 1) / DF_WAVES);
-    const size_t lds = (size_t)p.K * sizeof(float2);
-    if (out_bf16)
+    if (p.K > DF_MAX_K) return hipErrorNotSupported;
+    const size_t lds = 0;
+    if (traffic_only)                                            // the access pattern does not depend on the block size
+        hipLaunchKernelGGL((k_decode_fast<BITS, 64, true, R, true>), dim3(blocks), dim3(DF_THREADS), lds, p.stream, bt, (int)n_waves);
+    else if (out_bf16)
         hipLaunchKernelGGL((k_decode_fast<BITS, B, true, R>), dim3(blocks), dim3(DF_THREADS), lds, p.stream, bt, (int)n_waves);
     else
         hipLaunchKernelGGL((k_decode_fast<BITS, B, false, R>), dim3(blocks), dim3(DF_THREADS), lds, p.stream, bt, (int)n_waves);
@@ -357,29 +392,30 @@ static hipError_t launch_bb(const DecodeItem *items, int n, const Problem &p, bo
 }
 
 template <int BITS>
-static hipError_t launch_b(const DecodeItem *items, int n, const Problem &p, bool out_bf16) {
+static hipError_t launch_b(const DecodeItem *items, int n, const Problem &p, bool out_bf16, bool traffic_only) {
+    if (traffic_only) return launch_bb<BITS, 64>(items, n, p, true, true);
     switch (p.block) {
-        case 64: return launch_bb<BITS, 64>(items, n, p, out_bf16);
-        case 128: return launch_bb<BITS, 128>(items, n, p, out_bf16);
-        case 256: return launch_bb<BITS, 256>(items, n, p, out_bf16);
-        case 512: return launch_bb<BITS, 512>(items, n, p, out_bf16);
-        case 1024: return launch_bb<BITS, 1024>(items, n, p, out_bf16);
+        case 64: return launch_bb<BITS, 64>(items, n, p, out_bf16, false);
+        case 128: return launch_bb<BITS, 128>(items, n, p, out_bf16, false);
+        case 256: return launch_bb<BITS, 256>(items, n, p, out_bf16, false);
+        case 512: return launch_bb<BITS, 512>(items, n, p, out_bf16, false);
+        case 1024: return launch_bb<BITS, 1024>(items, n, p, out_bf16, false);
         default: return hipErrorNotSupported;
     }
 }
 
 // Decode n <= DF_MAX_BATCH matrices that share codebook, bits and block in one launch.  p carries the shared
 // fields only.  Returns hipErrorNotSupported (nothing launched) when any item is outside the fast kernel's shapes.
-hipError_t launch_decode_batch_fast(const DecodeItem *items, int n, const Problem &p, bool out_bf16) {
+hipError_t launch_decode_batch_fast(const DecodeItem *items, int n, const Problem &p, bool out_bf16, bool traffic_only) {
     if (n < 1 || n > DF_MAX_BATCH) return hipErrorNotSupported;
     for (int i = 0; i < n; ++i) {
         Problem q = p;
         q.d_in = items[i].d_in;
         if (!fast_decode_supported(q) || !decode_alignment_ok(items[i], out_bf16)) return hipErrorNotSupported;
     }
-    if (p.bits == 11) return launch_b<11>(items, n, p, out_bf16);
-    if (p.bits == 8) return launch_b<8>(items, n, p, out_bf16);
-    if (p.bits == 7) return launch_b<7>(items, n, p, out_bf16);
+    if (p.bits == 11) return launch_b<11>(items, n, p, out_bf16, traffic_only);
+    if (p.bits == 8) return launch_b<8>(items, n, p, out_bf16, traffic_only);
+    if (p.bits == 7) return launch_b<7>(items, n, p, out_bf16, traffic_only);
     return hipErrorNotSupported;
 }
 

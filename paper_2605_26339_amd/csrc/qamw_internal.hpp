@@ -53,7 +53,8 @@ struct DecodeItem {
     int d_out, d_in;
 };
 // Several matrices sharing codebook, bits and block in ONE launch; hipErrorNotSupported = nothing launched.
-hipError_t launch_decode_batch_fast(const DecodeItem *items, int n, const Problem &p, bool out_bf16);
+// traffic_only: the loads and stores of the bf16 decoder without its arithmetic (a measurement of the memory system).
+hipError_t launch_decode_batch_fast(const DecodeItem *items, int n, const Problem &p, bool out_bf16, bool traffic_only = false);
 
 // Fast kernels: return hipErrorNotSupported when the shape is outside what they cover.
 bool fast_decode_supported(const Problem &p);

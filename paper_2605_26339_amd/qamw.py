@@ -22,7 +22,7 @@ EXPORTS = [
     "qamw_decode_f32", "qamw_decode_batch", "qamw_set_kernel_path", "qamw_polar_codebook", "qamw_encode_polar",
     "qamw_matmul_workspace_bytes", "qamw_matmul", "qamw_matmul_batch", "qamw_encode_stats",
     "qamw_normalised_pairs", "qamw_lloyd_workspace_bytes", "qamw_lloyd_device",
-    "qamw_search_grid_size", "qamw_search_grid_build", "qamw_encode_pruned", "qamw_calibrate_sigma_static",
+    "qamw_search_grid_size", "qamw_search_grid_build", "qamw_encode_pruned", "qamw_calibrate_sigma_static", "qamw_decode_traffic_probe",
 ]
 
 
@@ -80,6 +80,7 @@ def lib() -> C.CDLL:
         L.qamw_decode.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, i64, vp]
         L.qamw_decode_f32.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, i64, vp]
         L.qamw_decode_batch.argtypes = [C.POINTER(DecodeItem), i32, vp, i32, i32, vp]
+        L.qamw_decode_traffic_probe.argtypes = [C.POINTER(DecodeItem), i32, vp, i32, i32, vp]
         L.qamw_set_kernel_path.argtypes = [i32]
         L.qamw_matmul_workspace_bytes.argtypes = [i32, i32, i32, C.POINTER(C.c_size_t)]
         L.qamw_matmul.argtypes = [vp, i32, i32, i64, vp, vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, C.c_size_t, vp, i64, vp]
@@ -450,3 +451,11 @@ def decode_batch(items, codebook, bits: int, block: int, stream=None):
     """Decode up to MAX_BATCH matrices (a DecodeItem array from make_decode_items) in one launch."""
     arr = items[0] if isinstance(items, tuple) else items
     _check(lib().qamw_decode_batch(arr, len(arr), _ptr(codebook), bits, block, _stream(stream)), "qamw_decode_batch")
+
+
+def decode_traffic_probe(items, codebook, bits: int, block: int, stream=None):
+    """The loads and stores of decode_batch(items, ...) without the arithmetic: a measurement of the memory system.
+    Every item's output is overwritten with meaningless values."""
+    arr = items[0] if isinstance(items, tuple) else items
+    _check(lib().qamw_decode_traffic_probe(arr, len(arr), _ptr(codebook), bits, block, _stream(stream)),
+           "qamw_decode_traffic_probe")
