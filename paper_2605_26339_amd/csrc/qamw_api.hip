@@ -87,12 +87,13 @@ static int calibrate_impl(const void *W, int dtype, int d_out, int d_in, int64_t
     const int n = d_out < max_rows ? d_out : max_rows;
     float *row_norms = static_cast<float *>(workspace);
     double *partial = reinterpret_cast<double *>(static_cast<char *>(workspace) + align_up((size_t)n * sizeof(float), 256));
-    if (launch_norms(W, dtype, ldw, n, p, row_norms) != hipSuccess) return QAMW_ERR_DEVICE;
     hipError_t e;
-    if (g_kernel_path.load() != 1 && qamw::fast_calibrate_supported(W, dtype, ldw, p))
-        e = qamw::launch_calibrate_fast(W, dtype, ldw, n, p, row_norms, partial, sigma_out);
-    else
+    if (g_kernel_path.load() != 1 && qamw::fast_calibrate_supported(W, dtype, ldw, p)) {
+        e = qamw::launch_calibrate_fast(W, dtype, ldw, n, p, partial, sigma_out);      // computes the rows' norms itself
+    } else {
+        if (launch_norms(W, dtype, ldw, n, p, row_norms) != hipSuccess) return QAMW_ERR_DEVICE;
         e = qamw::launch_calibrate_general(W, dtype, ldw, n, p, row_norms, sigma_out);
+    }
     return e == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
 }
 
@@ -181,13 +182,18 @@ static int encode_impl(const void *W, int dtype, int d_out, int d_in, int64_t ld
     if (ldw < d_in) return QAMW_ERR_SHAPE;
     qamw::Problem p = make_problem(d_out, d_in, chan_scale, signs, pair_sigma, codebook, bits, hadamard_block, stream);
     p.full_scans = full_scans;
-    if (launch_norms(W, dtype, ldw, d_out, p, row_norms_out) != hipSuccess) return QAMW_ERR_DEVICE;
+    // The fast kernels compute the row norms themselves (W is fetched once); rows too long for that, and the general
+    // kernels, get them from a launch of their own first.
     const int path = g_kernel_path.load();
+    const bool fused = path != 1 && qamw::fused_norms_supported(p);
+    if (!fused && launch_norms(W, dtype, ldw, d_out, p, row_norms_out) != hipSuccess) return QAMW_ERR_DEVICE;
     hipError_t e = hipErrorNotSupported;                        // "not supported" = nothing launched yet
-    if (path == 0) e = qamw::launch_encode_mfma(W, dtype, ldw, p, row_norms_out, packed_out);
-    if (e == hipErrorNotSupported && path != 1 && qamw::fast_encode_supported(p))
-        e = qamw::launch_encode_fast(W, dtype, ldw, p, row_norms_out, packed_out);
-    if (e == hipErrorNotSupported) e = qamw::launch_encode_general(W, dtype, ldw, p, row_norms_out, packed_out);
+    if (path == 0) e = qamw::launch_encode_mfma(W, dtype, ldw, p, row_norms_out, !fused, packed_out);
+    if (e == hipErrorNotSupported && path != 1) e = qamw::launch_encode_fast(W, dtype, ldw, p, row_norms_out, !fused, packed_out);
+    if (e == hipErrorNotSupported) {
+        if (fused && launch_norms(W, dtype, ldw, d_out, p, row_norms_out) != hipSuccess) return QAMW_ERR_DEVICE;
+        e = qamw::launch_encode_general(W, dtype, ldw, p, row_norms_out, packed_out);
+    }
     return e == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
 }
 
@@ -216,8 +222,9 @@ int qamw_normalised_pairs(const void *W, int dtype, int d_out, int d_in, int64_t
     if (ldw < d_in) return QAMW_ERR_SHAPE;
     qamw::Problem p = make_problem(d_out, d_in, chan_scale, signs, pair_sigma, nullptr, 1, hadamard_block, stream);
     if (!qamw::pairs_launchable(W, dtype, ldw, p, pairs_out)) return QAMW_ERR_UNSUPPORTED;
-    if (launch_norms(W, dtype, ldw, d_out, p, row_norms_out) != hipSuccess) return QAMW_ERR_DEVICE;
-    return qamw::launch_pairs(W, dtype, ldw, p, row_norms_out, pairs_out) == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
+    const bool fused = qamw::fused_norms_supported(p);
+    if (!fused && launch_norms(W, dtype, ldw, d_out, p, row_norms_out) != hipSuccess) return QAMW_ERR_DEVICE;
+    return qamw::launch_pairs(W, dtype, ldw, p, row_norms_out, !fused, pairs_out) == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
 }
 
 int qamw_lloyd_workspace_bytes(int bits, size_t *bytes_out) {
@@ -253,8 +260,9 @@ int qamw_encode_polar(const void *W, int dtype, int d_out, int d_in, int64_t ldw
                                    stream);
     // nothing is launched for a shape outside the kernel's range
     if (!qamw::polar_encode_launchable(W, dtype, ldw, p, bits_a, bits_p)) return QAMW_ERR_UNSUPPORTED;
-    if (launch_norms(W, dtype, ldw, d_out, p, row_norms_out) != hipSuccess) return QAMW_ERR_DEVICE;
-    hipError_t e = qamw::launch_encode_polar(W, dtype, ldw, p, levels, bits_a, bits_p, row_norms_out, packed_out);
+    const bool fused = qamw::fused_norms_supported(p);
+    if (!fused && launch_norms(W, dtype, ldw, d_out, p, row_norms_out) != hipSuccess) return QAMW_ERR_DEVICE;
+    hipError_t e = qamw::launch_encode_polar(W, dtype, ldw, p, levels, bits_a, bits_p, row_norms_out, !fused, packed_out);
     return e == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
 }
 

@@ -63,34 +63,54 @@ bool launch_row_norms_fast(const void *W, int dtype, int64_t ldw, int n_rows, co
 }
 
 // ---------------------------------------------------------------------------------------------
-// Calibration, step 1: wave (slab, chunk) sums |z_k| over CAL_ROWS consecutive rows, row by row,
-// in fp64, and writes one partial sum per pair.
+// Calibration, step 1: one workgroup per chunk of CAL_ROWS consecutive rows.  It first computes the norms of its rows
+// (slab sums in LDS, as the encoders do: the head rows are fetched from memory once), then wave w takes the slabs
+// w, w + CF_WAVES, ... and sums |z_k| over the chunk's rows, row by row, in fp64, and writes one partial sum per pair.
 // ---------------------------------------------------------------------------------------------
 template <int DTYPE, int B>
 __global__ __launch_bounds__(CF_THREADS) void k_calibrate_partial(const void *__restrict__ W, int64_t ldw, int n_rows,
-                                                                  Problem p, const float *__restrict__ norms,
-                                                                  double *__restrict__ partial, int n_slabs, int n_chunks) {
+                                                                  Problem p, double *__restrict__ partial, int n_slabs) {
+    __shared__ double norm_part[CAL_ROWS * FUSED_NORM_MAX_SLABS];
     const int lane = threadIdx.x & (WAVE - 1);
-    const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * CF_WAVES + (threadIdx.x >> 6));
-    if (item >= n_slabs * n_chunks) return;
-    const int chunk = item / n_slabs, slab = item - chunk * n_slabs;
-    const LaneSigns<B> ls(lane);
-    const int col0 = slab * CSLAB + 16 * slab_pos(lane);
-    const bool active = col0 < p.d_in;
-    const int c = active ? col0 : 0;
-    double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    const int row1 = min(n_rows, (chunk + 1) * CAL_ROWS);
-    for (int row = chunk * CAL_ROWS; row < row1; ++row) {
-        float y[16];
-        rotated_unit_row<DTYPE, B>(y, W, (int64_t)row * ldw, c, norms[row], p, ls);
-#pragma unroll
-        for (int k = 0; k < 8; ++k)
-            acc[k] += sqrt((double)y[2 * k] * (double)y[2 * k] + (double)y[2 * k + 1] * (double)y[2 * k + 1]);
+    const int wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int chunk = blockIdx.x;
+    const int row0 = chunk * CAL_ROWS, row1 = min(n_rows, row0 + CAL_ROWS);
+    const int tasks = (row1 - row0) * n_slabs;
+    for (int t = wid; t < tasks; t += CF_WAVES) {
+        const int dr = t / n_slabs, slab = t - dr * n_slabs;
+        const double s2 = slab_sum_of_squares<DTYPE>(W, (int64_t)(row0 + dr) * ldw, slab, p, lane);
+        if (lane == 0) norm_part[t] = s2;
     }
-    if (active) {
-        double *dst = partial + (int64_t)chunk * (p.d_in >> 1) + (c >> 1);
+    __syncthreads();
+    float rn[CAL_ROWS];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) dst[k] = acc[k];
+    for (int dr = 0; dr < CAL_ROWS; ++dr) {
+        double s2 = 0.0;
+        if (row0 + dr < row1)
+            for (int s = 0; s < n_slabs; ++s) s2 += norm_part[dr * n_slabs + s];
+        rn[dr] = (float)sqrt(s2);
+    }
+    const LaneSigns<B> ls(lane);
+    for (int slab = wid; slab < n_slabs; slab += CF_WAVES) {
+        const int col0 = slab * CSLAB + 16 * slab_pos(lane);
+        const bool active = col0 < p.d_in;
+        const int c = active ? col0 : 0;
+        double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int dr = 0; dr < CAL_ROWS; ++dr) {
+            if (row0 + dr < row1) {
+                float y[16];
+                rotated_unit_row<DTYPE, B>(y, W, (int64_t)(row0 + dr) * ldw, c, rn[dr], p, ls);
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    acc[k] += sqrt((double)y[2 * k] * (double)y[2 * k] + (double)y[2 * k + 1] * (double)y[2 * k + 1]);
+            }
+        }
+        if (active) {
+            double *dst = partial + (int64_t)chunk * (p.d_in >> 1) + (c >> 1);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) dst[k] = acc[k];
+        }
     }
 }
 
@@ -115,19 +135,19 @@ __global__ __launch_bounds__(CF_THREADS) void k_calibrate_finish(const double *_
     sigma_out[k] = (s > 0.0f) ? s : sigma_default;
 }
 
+bool fused_norms_supported(const Problem &p) { return (p.d_in + 1023) / 1024 <= FUSED_NORM_MAX_SLABS; }
+
 size_t calibrate_partial_bytes(int d_in, int n_rows) {
     const size_t n_chunks = (size_t)(n_rows + CAL_ROWS - 1) / CAL_ROWS;
     return n_chunks * (size_t)(d_in / 2) * sizeof(double);
 }
 
 template <int DTYPE, int B>
-static hipError_t launch_cal(const void *W, int64_t ldw, int n_rows, const Problem &p, const float *norms, double *partial,
-                             float *sigma_out) {
+static hipError_t launch_cal(const void *W, int64_t ldw, int n_rows, const Problem &p, double *partial, float *sigma_out) {
     const int n_slabs = (p.d_in + CSLAB - 1) / CSLAB;
     const int n_chunks = (n_rows + CAL_ROWS - 1) / CAL_ROWS;
-    const int items = n_slabs * n_chunks;
-    hipLaunchKernelGGL((k_calibrate_partial<DTYPE, B>), dim3((items + CF_WAVES - 1) / CF_WAVES), dim3(CF_THREADS), 0, p.stream,
-                       W, ldw, n_rows, p, norms, partial, n_slabs, n_chunks);
+    hipLaunchKernelGGL((k_calibrate_partial<DTYPE, B>), dim3(n_chunks), dim3(CF_THREADS), 0, p.stream, W, ldw, n_rows, p,
+                       partial, n_slabs);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int n_pairs = p.d_in / 2;
@@ -137,27 +157,27 @@ static hipError_t launch_cal(const void *W, int64_t ldw, int n_rows, const Probl
 }
 
 template <int DTYPE>
-static hipError_t launch_cal_d(const void *W, int64_t ldw, int n_rows, const Problem &p, const float *norms, double *partial,
-                               float *sigma_out) {
+static hipError_t launch_cal_d(const void *W, int64_t ldw, int n_rows, const Problem &p, double *partial, float *sigma_out) {
     switch (p.block) {
-        case 64: return launch_cal<DTYPE, 64>(W, ldw, n_rows, p, norms, partial, sigma_out);
-        case 128: return launch_cal<DTYPE, 128>(W, ldw, n_rows, p, norms, partial, sigma_out);
-        case 256: return launch_cal<DTYPE, 256>(W, ldw, n_rows, p, norms, partial, sigma_out);
-        case 512: return launch_cal<DTYPE, 512>(W, ldw, n_rows, p, norms, partial, sigma_out);
-        case 1024: return launch_cal<DTYPE, 1024>(W, ldw, n_rows, p, norms, partial, sigma_out);
+        case 64: return launch_cal<DTYPE, 64>(W, ldw, n_rows, p, partial, sigma_out);
+        case 128: return launch_cal<DTYPE, 128>(W, ldw, n_rows, p, partial, sigma_out);
+        case 256: return launch_cal<DTYPE, 256>(W, ldw, n_rows, p, partial, sigma_out);
+        case 512: return launch_cal<DTYPE, 512>(W, ldw, n_rows, p, partial, sigma_out);
+        case 1024: return launch_cal<DTYPE, 1024>(W, ldw, n_rows, p, partial, sigma_out);
         default: return hipErrorNotSupported;
     }
 }
 
 bool fast_calibrate_supported(const void *W, int dtype, int64_t ldw, const Problem &p) {
     const int unit = p.block > 16 ? p.block : 16;
-    return p.d_in % unit == 0 && p.block >= 64 && front_alignment_ok(W, dtype, ldw, p);
+    return p.d_in % unit == 0 && p.block >= 64 && fused_norms_supported(p) && front_alignment_ok(W, dtype, ldw, p);
 }
 
-hipError_t launch_calibrate_fast(const void *W, int dtype, int64_t ldw, int n_rows, const Problem &p, const float *norms,
-                                 double *partial, float *sigma_out) {
-    return dtype == 0 ? launch_cal_d<0>(W, ldw, n_rows, p, norms, partial, sigma_out)
-                      : launch_cal_d<1>(W, ldw, n_rows, p, norms, partial, sigma_out);
+// Two launches; the kernels compute the head rows' norms themselves.
+hipError_t launch_calibrate_fast(const void *W, int dtype, int64_t ldw, int n_rows, const Problem &p, double *partial,
+                                 float *sigma_out) {
+    return dtype == 0 ? launch_cal_d<0>(W, ldw, n_rows, p, partial, sigma_out)
+                      : launch_cal_d<1>(W, ldw, n_rows, p, partial, sigma_out);
 }
 
 }  // namespace qamw

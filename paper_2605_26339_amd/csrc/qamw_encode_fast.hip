@@ -21,24 +21,25 @@ constexpr int CHUNK = 16;     // codewords per shortlist chunk: scored together,
 
 __device__ __forceinline__ float min3(float a, float b, float c) { return __builtin_fminf(__builtin_fminf(a, b), c); }
 
-// Exact fp32 squared distance, the quantity that decides the index.
-__device__ __forceinline__ float dist2(float x0, float x1, float2 c) {
-    float e0 = x0 - c.x, e1 = x1 - c.y;
-    return __builtin_fmaf(e1, e1, e0 * e0);
-}
-
 template <int DTYPE, int B>
 __global__ __launch_bounds__(EF_THREADS) void k_encode_fast(const void *__restrict__ W, int64_t ldw, Problem p,
-                                                            const float *__restrict__ norms,
-                                                            uint8_t *__restrict__ packed, int n_slabs, int n_items) {
+                                                            const float *__restrict__ norms_in, float *__restrict__ norms_out,
+                                                            uint8_t *__restrict__ packed, int n_slabs, int n_items,
+                                                            int n_blocks) {
     extern __shared__ float lds_raw[];
     float2 *c01 = reinterpret_cast<float2 *>(lds_raw);          // K x (c0, c1)
     float *cn = lds_raw + 2 * p.K;                              // K x ||c||^2
     __shared__ float red[EF_WAVES];
+    __shared__ double norm_part[2 * FUSED_NORM_MAX_SLABS];
 
     const int lane = threadIdx.x & (WAVE - 1);
     const int wid = threadIdx.x >> 6;
     const int K = p.K;
+    // norms_in == NULL: the workgroup computes the norms of the rows its items touch (and writes them out); the
+    // barrier after the codebook staging below also publishes the slab sums.
+    const bool fused = norms_in == nullptr;
+    const int item0 = (fused ? fused_norm_block(blockIdx.x, n_blocks) : (int)blockIdx.x) * EF_WAVES;
+    if (fused && item0 < n_items) block_slab_sums<DTYPE, EF_WAVES>(norm_part, W, ldw, p, item0, n_items, n_slabs, lane, wid);
 
     // stage the codebook; R^2 = max ||c||^2 enters the shortlist's error bound
     const float2 *cbk = reinterpret_cast<const float2 *>(p.codebook);
@@ -57,9 +58,16 @@ __global__ __launch_bounds__(EF_THREADS) void k_encode_fast(const void *__restri
     rmax2 = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
     const float R = sqrtf(rmax2) * 1.000001f;
 
-    const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * EF_WAVES + wid);
+    const int item = __builtin_amdgcn_readfirstlane(item0 + wid);
     if (item >= n_items) return;
     const int row = item / n_slabs, slab = item - row * n_slabs;
+    float rnorm;
+    if (fused) {
+        rnorm = row_norm_from_slab_sums(norm_part, row, item0, n_slabs);
+        if (slab == 0 && lane == 0) norms_out[row] = rnorm;
+    } else {
+        rnorm = norms_in[row];
+    }
     const LaneSigns<B> ls(lane);
     const int pos = slab_pos(lane);
     const int col0 = slab * ESLAB + 16 * pos;
@@ -68,19 +76,10 @@ __global__ __launch_bounds__(EF_THREADS) void k_encode_fast(const void *__restri
 
     // ---------------- front half: x_k = (F S (W D_s / r))_pair k / sigma_k, in registers
     float x[16];
-    rotated_unit_row<DTYPE, B>(x, W, (int64_t)row * ldw, c, norms[row], p, ls);
+    rotated_unit_row<DTYPE, B>(x, W, (int64_t)row * ldw, c, rnorm, p, ls);
     {
         float g[NPT];
-        if (p.pair_sigma) {
-            const float4 *g4 = reinterpret_cast<const float4 *>(p.pair_sigma + (c >> 1));
-            float4 a = g4[0], b = g4[1];
-            const float sg8[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-#pragma unroll
-            for (int k = 0; k < NPT; ++k) g[k] = 1.0f / sg8[k];                   // IEEE division
-        } else {
-#pragma unroll
-            for (int k = 0; k < NPT; ++k) g[k] = p.g_default;
-        }
+        load_pair_gains(g, p, c);
 #pragma unroll
         for (int e = 0; e < 16; ++e) x[e] = x[e] * g[e >> 1];
     }
@@ -151,7 +150,7 @@ __global__ __launch_bounds__(EF_THREADS) void k_encode_fast(const void *__restri
         int bi = best[j] * CHUNK;
 #pragma unroll
         for (int k = 0; k < CHUNK; ++k) {
-            float dd = dist2(x0, x1, c01[best[j] * CHUNK + k]);
+            float dd = exact_dist2(x0, x1, c01[best[j] * CHUNK + k]);
             if (dd < bd) {
                 bd = dd;
                 bi = best[j] * CHUNK + k;
@@ -161,10 +160,11 @@ __global__ __launch_bounds__(EF_THREADS) void k_encode_fast(const void *__restri
         if (!safe) flagged |= 1u << j;
         asm volatile("" ::: "memory");                          // keep one point's gathers in flight at a time (register budget)
     }
+    int n_scans = 0;                                            // uniform: pairs of this wave that took the whole-codebook scan
 #pragma unroll
     for (int j = 0; j < NPT; ++j) {
         unsigned long long mask = __ballot((flagged >> j) & 1u);
-        if (p.full_scans && mask && lane == 0) atomicAdd(p.full_scans, (unsigned long long)__popcll(mask));
+        n_scans += __popcll(mask);
         while (mask) {
             const int src = __ffsll((long long)mask) - 1;
             mask &= mask - 1;
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(EF_THREADS) void k_encode_fast(const void *__restri
             float bd = BIG;
             int bi = 0x7fffffff;
             for (int k = lane; k < K; k += WAVE) {
-                float dd = dist2(x0, x1, c01[k]);
+                float dd = exact_dist2(x0, x1, c01[k]);
                 if (dd < bd) {
                     bd = dd;
                     bi = k;
@@ -191,6 +191,10 @@ __global__ __launch_bounds__(EF_THREADS) void k_encode_fast(const void *__restri
             if (lane == src) idx[j] = bi;
         }
     }
+
+    // one update of the counter per wave, after the search (an atomic inside the loops above costs the whole kernel
+    // its register allocation)
+    if (p.full_scans && n_scans && lane == 0) atomicAdd(p.full_scans, (unsigned long long)n_scans);
 
     // ---------------- pack: the lane's 8 fields are exactly `bits` bytes, byte aligned in the row
     if (active) {
@@ -216,37 +220,40 @@ bool fast_encode_supported(const Problem &p) {
 }
 
 template <int DTYPE, int B>
-static hipError_t launch_db(const void *W, int64_t ldw, const Problem &p, const float *norms, uint8_t *packed) {
+static hipError_t launch_db(const void *W, int64_t ldw, const Problem &p, float *norms, bool norms_ready, uint8_t *packed) {
     const int n_slabs = (p.d_in + ESLAB - 1) / ESLAB;
     const int64_t n_items = (int64_t)p.d_out * n_slabs;
     if (n_items > 0x7fffffff) return hipErrorNotSupported;
-    const unsigned blocks = (unsigned)((n_items + EF_WAVES - 1) / EF_WAVES);
+    if (!norms_ready && n_slabs > FUSED_NORM_MAX_SLABS) return hipErrorNotSupported;
+    const int n_blocks = (int)((n_items + EF_WAVES - 1) / EF_WAVES);
+    const unsigned blocks = (unsigned)(norms_ready ? n_blocks : fused_norm_grid(n_blocks));
     const size_t lds = (size_t)p.K * 3 * sizeof(float);
-    hipLaunchKernelGGL((k_encode_fast<DTYPE, B>), dim3(blocks), dim3(EF_THREADS), lds, p.stream, W, ldw, p, norms, packed,
-                       n_slabs, (int)n_items);
+    hipLaunchKernelGGL((k_encode_fast<DTYPE, B>), dim3(blocks), dim3(EF_THREADS), lds, p.stream, W, ldw, p,
+                       norms_ready ? norms : nullptr, norms, packed, n_slabs, (int)n_items, n_blocks);
     return hipGetLastError();
 }
 
 template <int DTYPE>
-static hipError_t launch_d(const void *W, int64_t ldw, const Problem &p, const float *norms, uint8_t *packed) {
+static hipError_t launch_d(const void *W, int64_t ldw, const Problem &p, float *norms, bool norms_ready, uint8_t *packed) {
     switch (p.block) {
-        case 64: return launch_db<DTYPE, 64>(W, ldw, p, norms, packed);
-        case 128: return launch_db<DTYPE, 128>(W, ldw, p, norms, packed);
-        case 256: return launch_db<DTYPE, 256>(W, ldw, p, norms, packed);
-        case 512: return launch_db<DTYPE, 512>(W, ldw, p, norms, packed);
-        case 1024: return launch_db<DTYPE, 1024>(W, ldw, p, norms, packed);
+        case 64: return launch_db<DTYPE, 64>(W, ldw, p, norms, norms_ready, packed);
+        case 128: return launch_db<DTYPE, 128>(W, ldw, p, norms, norms_ready, packed);
+        case 256: return launch_db<DTYPE, 256>(W, ldw, p, norms, norms_ready, packed);
+        case 512: return launch_db<DTYPE, 512>(W, ldw, p, norms, norms_ready, packed);
+        case 1024: return launch_db<DTYPE, 1024>(W, ldw, p, norms, norms_ready, packed);
         default: return hipErrorNotSupported;
     }
 }
 
-hipError_t launch_encode_fast(const void *W, int dtype, int64_t ldw, const Problem &p, const float *norms,
+// norms_ready: the row norms are already in `norms`; otherwise the kernel computes them itself and writes them there.
+// Returns hipErrorNotSupported (nothing launched) when the shape or alignment is outside this kernel's range.
+hipError_t launch_encode_fast(const void *W, int dtype, int64_t ldw, const Problem &p, float *norms, bool norms_ready,
                               uint8_t *packed) {
     // vector loads: rows and side arrays must be 16-byte aligned
-    const bool ok = front_alignment_ok(W, dtype, ldw, p) && ((reinterpret_cast<uintptr_t>(p.codebook) & 15) == 0);
-    hipError_t e = hipErrorNotSupported;
-    if (ok) e = dtype == 0 ? launch_d<0>(W, ldw, p, norms, packed) : launch_d<1>(W, ldw, p, norms, packed);
-    if (e == hipErrorNotSupported) return launch_encode_general(W, dtype, ldw, p, norms, packed);
-    return e;
+    const bool ok = fast_encode_supported(p) && front_alignment_ok(W, dtype, ldw, p) &&
+                    ((reinterpret_cast<uintptr_t>(p.codebook) & 15) == 0);
+    if (!ok) return hipErrorNotSupported;
+    return dtype == 0 ? launch_d<0>(W, ldw, p, norms, norms_ready, packed) : launch_d<1>(W, ldw, p, norms, norms_ready, packed);
 }
 
 }  // namespace qamw

@@ -21,6 +21,8 @@
 // (lane = point of a 32-point block, lanes 0-31 / 32-63 = the two coordinates).  A chunk is the
 // lane's 16 accumulator rows {8q + 4h + t} of two consecutive 32-codeword blocks (of one block for
 // codebooks of up to 256 points).
+#include <atomic>
+
 #include "qamw_front.hpp"
 
 namespace qamw {
@@ -56,16 +58,23 @@ __device__ __forceinline__ uint32_t pack2(uint32_t even, uint32_t odd) { return 
 // of the decision stage (8 instead of 16 per lane and point), which is what matters for a small codebook.
 template <int DTYPE, int B, int CH>
 __global__ __launch_bounds__(MF_THREADS) void k_encode_mfma(const void *__restrict__ W, int64_t ldw, Problem p,
-                                                            const float *__restrict__ norms,
-                                                            uint8_t *__restrict__ packed, int n_slabs, int n_items) {
+                                                            const float *__restrict__ norms_in, float *__restrict__ norms_out,
+                                                            uint8_t *__restrict__ packed, int n_slabs, int n_items,
+                                                            int n_blocks) {
     extern __shared__ __align__(16) float lds_raw[];
     float2 *c01 = reinterpret_cast<float2 *>(lds_raw);          // K x (c0, c1)
     uint32_t *e67 = reinterpret_cast<uint32_t *>(lds_raw + 2 * p.K);   // K x 2: bf16 pieces of ||c||^2, (h, m) and (l, 0)
     __shared__ float red[MF_WAVES];
+    __shared__ double norm_part[2 * FUSED_NORM_MAX_SLABS];
 
     const int lane = threadIdx.x & (WAVE - 1);
     const int wid = threadIdx.x >> 6;
     const int K = p.K;
+    // norms_in == NULL: the workgroup computes the norms of the rows its items touch (and writes them out) before
+    // anything else; the barrier after the codebook staging below also publishes the slab sums.
+    const bool fused = norms_in == nullptr;
+    const int item0 = (fused ? fused_norm_block(blockIdx.x, n_blocks) : (int)blockIdx.x) * MF_WAVES;
+    if (fused && item0 < n_items) block_slab_sums<DTYPE, MF_WAVES>(norm_part, W, ldw, p, item0, n_items, n_slabs, lane, wid);
     float *wave_area = lds_raw + 4 * K + wid * MF_WAVE_LDS_FLOATS;
     float2 *pts = reinterpret_cast<float2 *>(wave_area);        // the wave's 512 points, pair order
     uint16_t *idxl = reinterpret_cast<uint16_t *>(wave_area + 1024);   // their indices
@@ -91,9 +100,16 @@ __global__ __launch_bounds__(MF_THREADS) void k_encode_mfma(const void *__restri
     for (int w = 0; w < MF_WAVES; ++w) rmax2 = fmaxf(rmax2, red[w]);
     const float R = sqrtf(rmax2) * 1.000001f;
 
-    const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * MF_WAVES + wid);
+    const int item = __builtin_amdgcn_readfirstlane(item0 + wid);
     if (item >= n_items) return;
     const int row = item / n_slabs, slab = item - row * n_slabs;
+    float rnorm;
+    if (fused) {
+        rnorm = row_norm_from_slab_sums(norm_part, row, item0, n_slabs);
+        if (slab == 0 && lane == 0) norms_out[row] = rnorm;
+    } else {
+        rnorm = norms_in[row];
+    }
     const LaneSigns<B> ls(lane);
     const int pos = slab_pos(lane);
     const int col0 = slab * MSLAB + 16 * pos;
@@ -103,7 +119,7 @@ __global__ __launch_bounds__(MF_THREADS) void k_encode_mfma(const void *__restri
     // ---------------- front half, then the pairs go to LDS in pair order
     {
         float x[16];
-        rotated_unit_row<DTYPE, B>(x, W, (int64_t)row * ldw, c, norms[row], p, ls);
+        rotated_unit_row<DTYPE, B>(x, W, (int64_t)row * ldw, c, rnorm, p, ls);
         float g[8];
         load_pair_gains(g, p, c);
         float4 *dst = reinterpret_cast<float4 *>(pts + 8 * pos);
@@ -250,53 +266,68 @@ bool mfma_encode_supported(const Problem &p) {
     return p.block >= 64;
 }
 
+// More than the default 64 KB of LDS per workgroup has to be asked for: a host-side setting per kernel and device, made
+// once per kernel instantiation and device (the devices' bits of `done`).
+template <int DTYPE, int B, int CH> static bool allow_large_lds() {
+    static std::atomic<uint64_t> done{0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        (void)hipGetLastError();
+        return false;
+    }
+    if (done.load(std::memory_order_acquire) & (1ull << dev)) return true;
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_mfma<DTYPE, B, CH>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, MF_MAX_LDS_BYTES);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    done.fetch_or(1ull << dev, std::memory_order_release);
+    return true;
+}
+
 template <int DTYPE, int B, int CH>
-static hipError_t launch_mdbc(const void *W, int64_t ldw, const Problem &p, const float *norms, uint8_t *packed) {
+static hipError_t launch_mdbc(const void *W, int64_t ldw, const Problem &p, float *norms, bool norms_ready, uint8_t *packed) {
     const int n_slabs = (p.d_in + MSLAB - 1) / MSLAB;
     const int64_t n_items = (int64_t)p.d_out * n_slabs;
     if (n_items > 0x7fffffff) return hipErrorNotSupported;
-    const unsigned blocks = (unsigned)((n_items + MF_WAVES - 1) / MF_WAVES);
+    if (!norms_ready && n_slabs > FUSED_NORM_MAX_SLABS) return hipErrorNotSupported;
+    const int n_blocks = (int)((n_items + MF_WAVES - 1) / MF_WAVES);
+    const unsigned blocks = (unsigned)(norms_ready ? n_blocks : fused_norm_grid(n_blocks));
     const size_t lds = ((size_t)p.K * 4 + (size_t)MF_WAVES * MF_WAVE_LDS_FLOATS) * sizeof(float);
-    if (lds > 64 * 1024) {
-        // More than the default 64 KB of LDS per workgroup has to be asked for (a host-side setting
-        // of the current device, cheap enough to repeat on every launch).
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_mfma<DTYPE, B, CH>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, MF_MAX_LDS_BYTES);
-        if (e != hipSuccess) {
-            (void)hipGetLastError();
-            return hipErrorNotSupported;
-        }
-    }
-    hipLaunchKernelGGL((k_encode_mfma<DTYPE, B, CH>), dim3(blocks), dim3(MF_THREADS), lds, p.stream, W, ldw, p, norms, packed,
-                       n_slabs, (int)n_items);
+    if (lds > 64 * 1024 && !allow_large_lds<DTYPE, B, CH>()) return hipErrorNotSupported;
+    hipLaunchKernelGGL((k_encode_mfma<DTYPE, B, CH>), dim3(blocks), dim3(MF_THREADS), lds, p.stream, W, ldw, p,
+                       norms_ready ? norms : nullptr, norms, packed, n_slabs, (int)n_items, n_blocks);
     return hipGetLastError();
 }
 
 // one-block chunks for codebooks of up to 256 points, where the decision stage outweighs the main loop
 template <int DTYPE, int B>
-static hipError_t launch_mdb(const void *W, int64_t ldw, const Problem &p, const float *norms, uint8_t *packed) {
-    return p.K <= 256 ? launch_mdbc<DTYPE, B, 1>(W, ldw, p, norms, packed) : launch_mdbc<DTYPE, B, 2>(W, ldw, p, norms, packed);
+static hipError_t launch_mdb(const void *W, int64_t ldw, const Problem &p, float *norms, bool norms_ready, uint8_t *packed) {
+    return p.K <= 256 ? launch_mdbc<DTYPE, B, 1>(W, ldw, p, norms, norms_ready, packed)
+                      : launch_mdbc<DTYPE, B, 2>(W, ldw, p, norms, norms_ready, packed);
 }
 
 template <int DTYPE>
-static hipError_t launch_md(const void *W, int64_t ldw, const Problem &p, const float *norms, uint8_t *packed) {
+static hipError_t launch_md(const void *W, int64_t ldw, const Problem &p, float *norms, bool norms_ready, uint8_t *packed) {
     switch (p.block) {
-        case 64: return launch_mdb<DTYPE, 64>(W, ldw, p, norms, packed);
-        case 128: return launch_mdb<DTYPE, 128>(W, ldw, p, norms, packed);
-        case 256: return launch_mdb<DTYPE, 256>(W, ldw, p, norms, packed);
-        case 512: return launch_mdb<DTYPE, 512>(W, ldw, p, norms, packed);
-        case 1024: return launch_mdb<DTYPE, 1024>(W, ldw, p, norms, packed);
+        case 64: return launch_mdb<DTYPE, 64>(W, ldw, p, norms, norms_ready, packed);
+        case 128: return launch_mdb<DTYPE, 128>(W, ldw, p, norms, norms_ready, packed);
+        case 256: return launch_mdb<DTYPE, 256>(W, ldw, p, norms, norms_ready, packed);
+        case 512: return launch_mdb<DTYPE, 512>(W, ldw, p, norms, norms_ready, packed);
+        case 1024: return launch_mdb<DTYPE, 1024>(W, ldw, p, norms, norms_ready, packed);
         default: return hipErrorNotSupported;
     }
 }
 
 // Returns hipErrorNotSupported (nothing launched) when the shape or alignment is outside this kernel's range.
-hipError_t launch_encode_mfma(const void *W, int dtype, int64_t ldw, const Problem &p, const float *norms,
+// norms_ready: the row norms are already in `norms`; otherwise the kernel computes them itself and writes them there.
+hipError_t launch_encode_mfma(const void *W, int dtype, int64_t ldw, const Problem &p, float *norms, bool norms_ready,
                               uint8_t *packed) {
     const bool ok = mfma_encode_supported(p) && front_alignment_ok(W, dtype, ldw, p) &&
                     ((reinterpret_cast<uintptr_t>(p.codebook) & 15) == 0);
     if (!ok) return hipErrorNotSupported;
-    return dtype == 0 ? launch_md<0>(W, ldw, p, norms, packed) : launch_md<1>(W, ldw, p, norms, packed);
+    return dtype == 0 ? launch_md<0>(W, ldw, p, norms, norms_ready, packed) : launch_md<1>(W, ldw, p, norms, norms_ready, packed);
 }
 
 }  // namespace qamw

@@ -25,12 +25,21 @@ constexpr int PF_MAX_BINS = 4096;      // phase bins
 template <int DTYPE, int B>
 __global__ __launch_bounds__(PF_THREADS) void k_encode_polar(const void *__restrict__ W, int64_t ldw, Problem p,
                                                              const float *__restrict__ levels, int bits_a, int bits_p,
-                                                             const float *__restrict__ norms,
-                                                             uint8_t *__restrict__ packed, int n_slabs, int n_items) {
+                                                             const float *__restrict__ norms_in, float *__restrict__ norms_out,
+                                                             uint8_t *__restrict__ packed, int n_slabs, int n_items,
+                                                             int n_blocks) {
     extern __shared__ __align__(16) float lds_raw[];
     const int Na = 1 << bits_a, Np = 1 << bits_p;
     float *thr2 = lds_raw;                                      // Na: thr2[i] = (midpoint of levels i-1, i)^2, i >= 1
     float2 *bdir = reinterpret_cast<float2 *>(lds_raw + (Na < 2 ? 2 : Na));   // Np boundary directions (cos, sin)(2 k h), 8-byte aligned
+    __shared__ double norm_part[2 * FUSED_NORM_MAX_SLABS];
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int wid = threadIdx.x >> 6;
+    // norms_in == NULL: the workgroup computes the norms of the rows its items touch (and writes them out); the
+    // barrier after the table set-up below also publishes the slab sums.
+    const bool fused = norms_in == nullptr;
+    const int item0 = (fused ? fused_norm_block(blockIdx.x, n_blocks) : (int)blockIdx.x) * PF_WAVES;
+    if (fused && item0 < n_items) block_slab_sums<DTYPE, PF_WAVES>(norm_part, W, ldw, p, item0, n_items, n_slabs, lane, wid);
 
     for (int i = threadIdx.x; i < Na; i += PF_THREADS) {
         const float t = (i > 0) ? 0.5f * (levels[i - 1] + levels[i]) : 0.0f;
@@ -43,11 +52,16 @@ __global__ __launch_bounds__(PF_THREADS) void k_encode_polar(const void *__restr
     }
     __syncthreads();
 
-    const int lane = threadIdx.x & (WAVE - 1);
-    const int wid = threadIdx.x >> 6;
-    const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * PF_WAVES + wid);
+    const int item = __builtin_amdgcn_readfirstlane(item0 + wid);
     if (item >= n_items) return;
     const int row = item / n_slabs, slab = item - row * n_slabs;
+    float rnorm;
+    if (fused) {
+        rnorm = row_norm_from_slab_sums(norm_part, row, item0, n_slabs);
+        if (slab == 0 && lane == 0) norms_out[row] = rnorm;
+    } else {
+        rnorm = norms_in[row];
+    }
     const LaneSigns<B> ls(lane);
     const int pos = slab_pos(lane);
     const int col0 = slab * PSLAB + 16 * pos;
@@ -56,7 +70,7 @@ __global__ __launch_bounds__(PF_THREADS) void k_encode_polar(const void *__restr
 
     // ---------------- front half: x_k = (F S (W D_s / r))_pair k / sigma_k, in registers
     float x[16];
-    rotated_unit_row<DTYPE, B>(x, W, (int64_t)row * ldw, c, norms[row], p, ls);
+    rotated_unit_row<DTYPE, B>(x, W, (int64_t)row * ldw, c, rnorm, p, ls);
     {
         float g[8];
         load_pair_gains(g, p, c);
@@ -102,26 +116,28 @@ static bool polar_encode_supported(const Problem &p, int bits_a, int bits_p) {
 
 template <int DTYPE, int B>
 static hipError_t launch_pdb(const void *W, int64_t ldw, const Problem &p, const float *levels, int bits_a, int bits_p,
-                             const float *norms, uint8_t *packed) {
+                             float *norms, bool norms_ready, uint8_t *packed) {
     const int n_slabs = (p.d_in + PSLAB - 1) / PSLAB;
     const int64_t n_items = (int64_t)p.d_out * n_slabs;
     if (n_items > 0x7fffffff) return hipErrorNotSupported;
-    const unsigned blocks = (unsigned)((n_items + PF_WAVES - 1) / PF_WAVES);
+    if (!norms_ready && n_slabs > FUSED_NORM_MAX_SLABS) return hipErrorNotSupported;
+    const int n_blocks = (int)((n_items + PF_WAVES - 1) / PF_WAVES);
+    const unsigned blocks = (unsigned)(norms_ready ? n_blocks : fused_norm_grid(n_blocks));
     const size_t lds = ((size_t)(bits_a ? (1 << bits_a) : 2) + 2 * (size_t)(1 << bits_p)) * sizeof(float);
     hipLaunchKernelGGL((k_encode_polar<DTYPE, B>), dim3(blocks), dim3(PF_THREADS), lds, p.stream, W, ldw, p, levels, bits_a,
-                       bits_p, norms, packed, n_slabs, (int)n_items);
+                       bits_p, norms_ready ? norms : nullptr, norms, packed, n_slabs, (int)n_items, n_blocks);
     return hipGetLastError();
 }
 
 template <int DTYPE>
 static hipError_t launch_pd(const void *W, int64_t ldw, const Problem &p, const float *levels, int bits_a, int bits_p,
-                            const float *norms, uint8_t *packed) {
+                            float *norms, bool norms_ready, uint8_t *packed) {
     switch (p.block) {
-        case 64: return launch_pdb<DTYPE, 64>(W, ldw, p, levels, bits_a, bits_p, norms, packed);
-        case 128: return launch_pdb<DTYPE, 128>(W, ldw, p, levels, bits_a, bits_p, norms, packed);
-        case 256: return launch_pdb<DTYPE, 256>(W, ldw, p, levels, bits_a, bits_p, norms, packed);
-        case 512: return launch_pdb<DTYPE, 512>(W, ldw, p, levels, bits_a, bits_p, norms, packed);
-        case 1024: return launch_pdb<DTYPE, 1024>(W, ldw, p, levels, bits_a, bits_p, norms, packed);
+        case 64: return launch_pdb<DTYPE, 64>(W, ldw, p, levels, bits_a, bits_p, norms, norms_ready, packed);
+        case 128: return launch_pdb<DTYPE, 128>(W, ldw, p, levels, bits_a, bits_p, norms, norms_ready, packed);
+        case 256: return launch_pdb<DTYPE, 256>(W, ldw, p, levels, bits_a, bits_p, norms, norms_ready, packed);
+        case 512: return launch_pdb<DTYPE, 512>(W, ldw, p, levels, bits_a, bits_p, norms, norms_ready, packed);
+        case 1024: return launch_pdb<DTYPE, 1024>(W, ldw, p, levels, bits_a, bits_p, norms, norms_ready, packed);
         default: return hipErrorNotSupported;
     }
 }
@@ -133,10 +149,10 @@ bool polar_encode_launchable(const void *W, int dtype, int64_t ldw, const Proble
 
 // Returns hipErrorNotSupported (nothing launched) when the shape or alignment is outside this kernel's range.
 hipError_t launch_encode_polar(const void *W, int dtype, int64_t ldw, const Problem &p, const float *levels, int bits_a,
-                               int bits_p, const float *norms, uint8_t *packed) {
+                               int bits_p, float *norms, bool norms_ready, uint8_t *packed) {
     if (!polar_encode_launchable(W, dtype, ldw, p, bits_a, bits_p)) return hipErrorNotSupported;
-    return dtype == 0 ? launch_pd<0>(W, ldw, p, levels, bits_a, bits_p, norms, packed)
-                      : launch_pd<1>(W, ldw, p, levels, bits_a, bits_p, norms, packed);
+    return dtype == 0 ? launch_pd<0>(W, ldw, p, levels, bits_a, bits_p, norms, norms_ready, packed)
+                      : launch_pd<1>(W, ldw, p, levels, bits_a, bits_p, norms, norms_ready, packed);
 }
 
 }  // namespace qamw

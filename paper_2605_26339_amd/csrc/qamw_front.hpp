@@ -104,6 +104,91 @@ __device__ __forceinline__ void rotated_unit_row(float (&y)[16], const void *__r
     rotated_unit_row_from<DTYPE, B>(y, raw, c, r, p, ls);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Row norms inside the kernels that need them (Sec. 3.1 step 1 on the channel-scaled row of Sec. B.2), so that the
+// matrix is fetched from memory once per entry point instead of once by a norm kernel and once more by the kernel
+// proper.
+//
+// A workgroup of NWAVES waves owns NWAVES consecutive (row, slab) items, which touch a few consecutive rows.  For every
+// slab of every such row one wave sums the squares of the slab's 1024 scaled weights in fp64 (products of fp32 are
+// exact in fp64; 16 per lane in column order, then the fixed butterfly of wave_sum) and leaves the sum in LDS; after
+// the workgroup's barrier every wave adds its row's slab sums in slab order and takes the square root.  The value of a
+// row's norm therefore does not depend on which workgroup computes it.  Rows shared by neighbouring workgroups are
+// summed by each of them; fused_norm_block() numbers the workgroups so that neighbours run on the same XCD and
+// find each other's rows in its L2.
+// ---------------------------------------------------------------------------------------------
+constexpr int FUSED_NORM_MAX_SLABS = 64;                       // rows of up to 65536 columns
+constexpr int FUSED_NORM_XCDS = 8;
+
+// Hardware workgroup b runs on XCD b mod 8.  Workgroup number used by the kernel: XCD x takes the x-th eighth of the
+// work, in order.  A value >= n_blocks means: nothing to do.
+__device__ __forceinline__ int fused_norm_block(int b, int n_blocks) {
+    const int per = (n_blocks + FUSED_NORM_XCDS - 1) / FUSED_NORM_XCDS;
+    return (b % FUSED_NORM_XCDS) * per + b / FUSED_NORM_XCDS;
+}
+inline int fused_norm_grid(int n_blocks) {                       // workgroups to launch for n_blocks of work
+    return (n_blocks + FUSED_NORM_XCDS - 1) / FUSED_NORM_XCDS * FUSED_NORM_XCDS;
+}
+
+// Sum of squares of the scaled weights of columns [1024 slab, 1024 slab + 1024) of one row, the same in every lane.
+template <int DTYPE>
+__device__ __forceinline__ double slab_sum_of_squares(const void *__restrict__ W, int64_t row_base, int slab, const Problem &p,
+                                                       int lane) {
+    const int c = slab * 1024 + 16 * lane;
+    double acc = 0.0;
+    if (c < p.d_in) {
+        RawRow<DTYPE> raw;
+        load_raw_row<DTYPE>(raw, W, row_base, c);
+        float w[16];
+        if (DTYPE == 0) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) w[e] = __uint_as_float(raw.w[e]);
+        } else {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                w[2 * q] = __uint_as_float(raw.w[q] << 16);
+                w[2 * q + 1] = __uint_as_float(raw.w[q] & 0xFFFF0000u);
+            }
+        }
+        if (p.chan_scale) {
+            const float4 *s4 = reinterpret_cast<const float4 *>(p.chan_scale + c);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float4 v = s4[t];
+                w[4 * t] *= v.x; w[4 * t + 1] *= v.y; w[4 * t + 2] *= v.z; w[4 * t + 3] *= v.w;
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc += (double)w[e] * (double)w[e];
+    }
+    return wave_sum(acc);
+}
+
+// Slab sums of every row touched by the items [item0, item0 + NWAVES) (clipped to n_items) into part[], dealt to
+// the workgroup's waves.  The caller's barrier follows; then row_norm_from_slab_sums().
+// part: LDS, 2 * max(n_slabs, NWAVES) doubles.  All waves of the workgroup call this.
+template <int DTYPE, int NWAVES>
+__device__ __forceinline__ void block_slab_sums(double *part, const void *__restrict__ W, int64_t ldw, const Problem &p, int item0,
+                                                int n_items, int n_slabs, int lane, int wid) {
+    const int last = min(item0 + NWAVES, n_items) - 1;
+    const int r0 = item0 / n_slabs, r1 = last / n_slabs;
+    const int tasks = (r1 - r0 + 1) * n_slabs;
+    for (int t = __builtin_amdgcn_readfirstlane(wid); t < tasks; t += NWAVES) {
+        const int dr = t / n_slabs, slab = t - dr * n_slabs;
+        const double s2 = slab_sum_of_squares<DTYPE>(W, (int64_t)(r0 + dr) * ldw, slab, p, lane);
+        if (lane == 0) part[t] = s2;
+    }
+}
+
+// The norm of `row` from the slab sums left by block_slab_sums() (after the barrier): slab order, fp64, one rounding
+// to fp32 after the square root.
+__device__ __forceinline__ float row_norm_from_slab_sums(const double *part, int row, int item0, int n_slabs) {
+    const double *src = part + (row - item0 / n_slabs) * n_slabs;
+    double s2 = 0.0;
+    for (int s = 0; s < n_slabs; ++s) s2 += src[s];
+    return (float)sqrt(s2);
+}
+
 // Exact squared distance as every encoder decides with it: fma(e1, e1, e0 * e0), e = x - c.
 __device__ __forceinline__ float exact_dist2(float x0, float x1, float2 c) {
     const float e0 = x0 - c.x, e1 = x1 - c.y;

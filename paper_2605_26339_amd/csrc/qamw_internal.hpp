@@ -37,8 +37,8 @@ bool launch_row_norms_fast(const void *W, int dtype, int64_t ldw, int n_rows, co
 // Two-step calibration through caller-provided partial sums (calibrate_partial_bytes() of them).
 size_t calibrate_partial_bytes(int d_in, int n_rows);
 bool fast_calibrate_supported(const void *W, int dtype, int64_t ldw, const Problem &p);
-hipError_t launch_calibrate_fast(const void *W, int dtype, int64_t ldw, int n_rows, const Problem &p, const float *norms,
-                                 double *partial, float *sigma_out);
+hipError_t launch_calibrate_fast(const void *W, int dtype, int64_t ldw, int n_rows, const Problem &p, double *partial,
+                                 float *sigma_out);
 
 // One matrix of a decode batch (host-side description).
 constexpr int QAMW_DECODE_MAX_BATCH = 16;
@@ -61,11 +61,13 @@ bool fast_decode_supported(const Problem &p);
 hipError_t launch_decode_fast(const uint8_t *packed, const float *norms, const Problem &p, void *out,
                               int64_t ldo, bool out_bf16);
 bool fast_encode_supported(const Problem &p);
-hipError_t launch_encode_fast(const void *W, int dtype, int64_t ldw, const Problem &p, const float *norms,
+// norms_ready = false: the kernel computes the row norms itself (one read of W) and writes them to `norms`.
+hipError_t launch_encode_fast(const void *W, int dtype, int64_t ldw, const Problem &p, float *norms, bool norms_ready,
                               uint8_t *packed);
+bool fused_norms_supported(const Problem &p);   // rows short enough for the kernels to compute their own norms
 bool polar_encode_launchable(const void *W, int dtype, int64_t ldw, const Problem &p, int bits_a, int bits_p);
 hipError_t launch_encode_polar(const void *W, int dtype, int64_t ldw, const Problem &p, const float *levels, int bits_a,
-                               int bits_p, const float *norms, uint8_t *packed);
+                               int bits_p, float *norms, bool norms_ready, uint8_t *packed);
 bool matmul_supported(const Problem &p, int m);
 size_t matmul_workspace_bytes(int d_in, int d_out, int m);
 constexpr int QAMW_MATMUL_MAX_BATCH = 16;
@@ -85,7 +87,7 @@ size_t lloyd_workspace_bytes(int K);
 hipError_t run_lloyd(const float *samples, long long n, int K, float *codebook, int max_iters, double tol, void *workspace,
                      double *mse_out, int *iters_out, hipStream_t stream);
 bool pairs_launchable(const void *W, int dtype, int64_t ldw, const Problem &p, const float *pairs);
-hipError_t launch_pairs(const void *W, int dtype, int64_t ldw, const Problem &p, const float *norms, float *pairs);
+hipError_t launch_pairs(const void *W, int dtype, int64_t ldw, const Problem &p, float *norms, bool norms_ready, float *pairs);
 // The pruned-search table in device memory (layout: qamw_search_grid_build) and its grid size, which follows from bits.
 struct SearchGridView {
     const void *table;
@@ -96,7 +98,7 @@ bool grid_encode_launchable(const void *W, int dtype, int64_t ldw, const Problem
 hipError_t launch_encode_grid(const void *W, int dtype, int64_t ldw, const Problem &p, const SearchGridView &g,
                               const float *norms, uint8_t *packed);
 bool mfma_encode_supported(const Problem &p);
-hipError_t launch_encode_mfma(const void *W, int dtype, int64_t ldw, const Problem &p, const float *norms,
+hipError_t launch_encode_mfma(const void *W, int dtype, int64_t ldw, const Problem &p, float *norms, bool norms_ready,
                               uint8_t *packed);
 
 }  // namespace qamw

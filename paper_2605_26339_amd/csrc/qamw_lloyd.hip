@@ -178,20 +178,36 @@ hipError_t run_lloyd(const float *samples, long long n, int K, float *codebook, 
 // ---------------------------------------------------------------------------------------------- pairs
 template <int DTYPE, int B>
 __global__ __launch_bounds__(LL_THREADS) void k_pairs(const void *__restrict__ W, int64_t ldw, Problem p,
-                                                      const float *__restrict__ norms, float *__restrict__ pairs,
-                                                      int n_slabs, int n_items) {
+                                                      const float *__restrict__ norms_in, float *__restrict__ norms_out,
+                                                      float *__restrict__ pairs, int n_slabs, int n_items, int n_blocks) {
+    constexpr int NW = LL_THREADS / WAVE;
+    __shared__ double norm_part[2 * FUSED_NORM_MAX_SLABS];
     const int lane = threadIdx.x & (WAVE - 1);
     const int wid = threadIdx.x >> 6;
-    const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * (LL_THREADS / WAVE) + wid);
+    // norms_in == NULL: the workgroup computes the norms of the rows its items touch (and writes them out)
+    const bool fused = norms_in == nullptr;
+    const int item0 = (fused ? fused_norm_block(blockIdx.x, n_blocks) : (int)blockIdx.x) * NW;
+    if (fused) {
+        if (item0 < n_items) block_slab_sums<DTYPE, NW>(norm_part, W, ldw, p, item0, n_items, n_slabs, lane, wid);
+        __syncthreads();
+    }
+    const int item = __builtin_amdgcn_readfirstlane(item0 + wid);
     if (item >= n_items) return;
     const int row = item / n_slabs, slab = item - row * n_slabs;
+    float rnorm;
+    if (fused) {
+        rnorm = row_norm_from_slab_sums(norm_part, row, item0, n_slabs);
+        if (slab == 0 && lane == 0) norms_out[row] = rnorm;
+    } else {
+        rnorm = norms_in[row];
+    }
     const LaneSigns<B> ls(lane);
     const int pos = slab_pos(lane);
     const int col0 = slab * 1024 + 16 * pos;
     const bool active = col0 < p.d_in;
     const int c = active ? col0 : 0;
     float x[16];
-    rotated_unit_row<DTYPE, B>(x, W, (int64_t)row * ldw, c, norms[row], p, ls);
+    rotated_unit_row<DTYPE, B>(x, W, (int64_t)row * ldw, c, rnorm, p, ls);
     float g[8];
     if (p.pair_sigma) {
         const float4 *g4 = reinterpret_cast<const float4 *>(p.pair_sigma + (c >> 1));
@@ -218,13 +234,17 @@ bool pairs_launchable(const void *W, int dtype, int64_t ldw, const Problem &p, c
 }
 
 template <int DTYPE>
-static hipError_t launch_pairs_d(const void *W, int64_t ldw, const Problem &p, const float *norms, float *pairs) {
+static hipError_t launch_pairs_d(const void *W, int64_t ldw, const Problem &p, float *norms, bool norms_ready, float *pairs) {
     const int n_slabs = (p.d_in + 1023) / 1024;
     const int64_t n_items = (int64_t)p.d_out * n_slabs;
     if (n_items > 0x7fffffff) return hipErrorNotSupported;
-    const unsigned blocks = (unsigned)((n_items + 3) / 4);
+    if (!norms_ready && n_slabs > FUSED_NORM_MAX_SLABS) return hipErrorNotSupported;
+    static_assert(LL_THREADS / WAVE == 4, "four items per workgroup");
+    const int n_blocks = (int)((n_items + 3) / 4);
+    const unsigned blocks = (unsigned)(norms_ready ? n_blocks : fused_norm_grid(n_blocks));
+    const float *norms_in = norms_ready ? norms : nullptr;
 #define QAMW_PAIRS(BB) \
-    case BB: hipLaunchKernelGGL((k_pairs<DTYPE, BB>), dim3(blocks), dim3(LL_THREADS), 0, p.stream, W, ldw, p, norms, pairs, n_slabs, (int)n_items); break;
+    case BB: hipLaunchKernelGGL((k_pairs<DTYPE, BB>), dim3(blocks), dim3(LL_THREADS), 0, p.stream, W, ldw, p, norms_in, norms, pairs, n_slabs, (int)n_items, n_blocks); break;
     switch (p.block) {
         QAMW_PAIRS(64) QAMW_PAIRS(128) QAMW_PAIRS(256) QAMW_PAIRS(512) QAMW_PAIRS(1024)
         default: return hipErrorNotSupported;
@@ -233,9 +253,9 @@ static hipError_t launch_pairs_d(const void *W, int64_t ldw, const Problem &p, c
     return hipGetLastError();
 }
 
-hipError_t launch_pairs(const void *W, int dtype, int64_t ldw, const Problem &p, const float *norms, float *pairs) {
+hipError_t launch_pairs(const void *W, int dtype, int64_t ldw, const Problem &p, float *norms, bool norms_ready, float *pairs) {
     if (!pairs_launchable(W, dtype, ldw, p, pairs)) return hipErrorNotSupported;
-    return dtype == 0 ? launch_pairs_d<0>(W, ldw, p, norms, pairs) : launch_pairs_d<1>(W, ldw, p, norms, pairs);
+    return dtype == 0 ? launch_pairs_d<0>(W, ldw, p, norms, norms_ready, pairs) : launch_pairs_d<1>(W, ldw, p, norms, norms_ready, pairs);
 }
 
 }  // namespace qamw
