@@ -20,6 +20,8 @@
  *     waiting.  A launch failure is reported as QAMW_ERR_DEVICE.  Outputs are unspecified after
  *     an error.  Behaviour on non-finite input values is unspecified.
  *   - Matrices are row-major with an explicit leading dimension in ELEMENTS.
+ *   - Packed buffers (packed, packed_out) are 4-byte aligned: the stream is read and written in 32-bit words;
+ *     a misaligned one is an INVALID_ARG.
  *   - P = d_in/2 pairs per row, K = 2^bits codewords.  Pair k of a row is columns (2k, 2k+1).
  *
  * Packed layout (the paper leaves it open; this is the library's definition): per row, pair k
@@ -58,6 +60,8 @@ enum {
 enum { QAMW_DTYPE_F32 = 0, QAMW_DTYPE_BF16 = 1 };
 
 enum { QAMW_MAX_BITS = 12, QAMW_MAX_BLOCK = 1024 };
+
+enum { QAMW_MAX_BATCH = 16 };   /* matrices per qamw_encode_batch / qamw_decode_batch call */
 
 /* Text for a status code (static storage, never NULL). */
 const char *qamw_status_string(int status);
@@ -164,6 +168,27 @@ int qamw_encode_stats(const void *W, int dtype, int d_out, int d_in, int64_t ldw
                       const int8_t *signs, const float *pair_sigma, const float *codebook, int bits,
                       int hadamard_block, uint8_t *packed_out, float *row_norms_out,
                       unsigned long long *full_scans, void *stream);
+
+/* Several matrices that share codebook, bits, hadamard_block and element type encoded in ONE launch (Sec. 3.1; a
+ * TinyLlama-sized projection is a fraction of a millisecond of work, so per-launch ramp-up and tail are a large part
+ * of qamw_encode for small matrices; a batch, e.g. a layer's seven projections, amortises them).
+ * items: HOST array of n_items descriptors (read during the call, not retained); every pointer inside is a device
+ * pointer with the meaning it has in qamw_encode.  1 <= n_items <= QAMW_MAX_BATCH.
+ * Results are identical, bit for bit, to n_items calls of qamw_encode.  Items the batched kernel cannot take
+ * (shape, alignment, codebooks of fewer than 64 or more than 2048 points) make the whole call fall back to one
+ * qamw_encode per item.  Errors: items NULL, n_items out of range, any item invalid as for qamw_encode. */
+typedef struct qamw_encode_item {
+    const void *W;               /* d_out rows of d_in elements of the batch's dtype, leading dimension ldw */
+    int64_t ldw;
+    const float *chan_scale;     /* d_in floats or NULL                                                   */
+    const int8_t *signs;         /* d_in int8 or NULL                                                     */
+    const float *pair_sigma;     /* d_in/2 floats or NULL                                                 */
+    uint8_t *packed_out;         /* d_out * qamw_packed_row_bytes(d_in, bits) bytes                       */
+    float *row_norms_out;        /* d_out floats                                                          */
+    int32_t d_out, d_in;
+} qamw_encode_item;
+int qamw_encode_batch(const qamw_encode_item *items, int n_items, int dtype, const float *codebook, int bits,
+                      int hadamard_block, void *stream);
 
 /* Codebook training on the device (Sec. 3.5; a codebook fitted to a checkpoint's own pairs is the follow-up
  * named in the paper's discussion).
@@ -283,7 +308,6 @@ typedef struct qamw_decode_item {
     int64_t ldo;
     int32_t d_out, d_in;
 } qamw_decode_item;
-enum { QAMW_MAX_BATCH = 16 };
 int qamw_decode_batch(const qamw_decode_item *items, int n_items, const float *codebook, int bits,
                       int hadamard_block, void *stream);
 
@@ -297,8 +321,8 @@ int qamw_decode_batch(const qamw_decode_item *items, int n_items, const float *c
 int qamw_decode_traffic_probe(const qamw_decode_item *items, int n_items, const float *codebook, int bits,
                               int hadamard_block, void *stream);
 
-/* Fused dequantise-and-multiply (the follow-up named in the paper's Limitations, "No fused
- * dequantization-matmul kernel"): Y = X W^T for m <= QAMW_MATMUL_MAX_ROWS activation rows, W = the matrix
+/* Fused dequantise-and-multiply (the follow-up the paper's Limitations paragraph on inference kernels names):
+ * Y = X W^T for m <= QAMW_MATMUL_MAX_ROWS activation rows, W = the matrix
  * that qamw_decode_f32 would produce from (packed, row_norms, ...), without materialising W.
  * By the linearity of the decoder (Sec. 3.2, Sec. B.2) and the symmetry of F (Lemma 1),
  *     <w_i, x> = r_i * sum_k < c[idx_ik], z_k >,   z = the pairs of sigma (.) F S (x / s):

@@ -43,14 +43,6 @@ def sources():
     return [os.path.join(CSRC, s) for s in SOURCES]
 
 
-def is_stale() -> bool:
-    if not os.path.exists(LIB):
-        return True
-    t = os.path.getmtime(LIB)
-    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(ROOT, "include", "qamw.h")]
-    return any(os.path.getmtime(d) > t for d in deps)
-
-
 def build(verbose: bool = True) -> str:
     """Compile every source and link the shared library.  Always recompiles."""
     objs = []

@@ -10,6 +10,9 @@ namespace {
 
 std::atomic<int> g_kernel_path{0};
 
+// The packed stream is read and written in 32-bit words (its rows are multiples of 4 bytes).
+bool misaligned4(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 3) != 0; }
+
 int check_common(int d_out, int d_in, int bits, int block) {
     if (d_out <= 0 || d_in <= 0 || bits < 1 || bits > QAMW_MAX_BITS) return QAMW_ERR_INVALID_ARG;
     if (d_in & 1) return QAMW_ERR_SHAPE;
@@ -48,7 +51,7 @@ hipError_t launch_norms(const void *W, int dtype, int64_t ldw, int n_rows, const
 int decode_any(const uint8_t *packed, const float *row_norms, int d_out, int d_in, const float *chan_scale,
                const int8_t *signs, const float *pair_sigma, const float *codebook, int bits, int block, void *out,
                int64_t ldo, void *stream, bool bf16) {
-    if (!packed || !row_norms || !codebook || !out) return QAMW_ERR_INVALID_ARG;
+    if (!packed || !row_norms || !codebook || !out || misaligned4(packed)) return QAMW_ERR_INVALID_ARG;
     int rc = check_common(d_out, d_in, bits, block);
     if (rc != QAMW_OK) return rc;
     if (ldo < d_in) return QAMW_ERR_SHAPE;
@@ -175,7 +178,7 @@ int qamw_calibrate_sigma_static(const void *W, int dtype, int d_out, int d_in, i
 static int encode_impl(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
                        const int8_t *signs, const float *pair_sigma, const float *codebook, int bits, int hadamard_block,
                        uint8_t *packed_out, float *row_norms_out, unsigned long long *full_scans, void *stream) {
-    if (!W || !codebook || !packed_out || !row_norms_out) return QAMW_ERR_INVALID_ARG;
+    if (!W || !codebook || !packed_out || !row_norms_out || misaligned4(packed_out)) return QAMW_ERR_INVALID_ARG;
     if (dtype != QAMW_DTYPE_F32 && dtype != QAMW_DTYPE_BF16) return QAMW_ERR_INVALID_ARG;
     int rc = check_common(d_out, d_in, bits, hadamard_block);
     if (rc != QAMW_OK) return rc;
@@ -210,6 +213,39 @@ int qamw_encode_stats(const void *W, int dtype, int d_out, int d_in, int64_t ldw
     if (!full_scans) return QAMW_ERR_INVALID_ARG;
     return encode_impl(W, dtype, d_out, d_in, ldw, chan_scale, signs, pair_sigma, codebook, bits, hadamard_block, packed_out,
                        row_norms_out, full_scans, stream);
+}
+
+int qamw_encode_batch(const qamw_encode_item *items, int n_items, int dtype, const float *codebook, int bits,
+                      int hadamard_block, void *stream) {
+    static_assert(QAMW_MAX_BATCH == qamw::QAMW_ENCODE_MAX_BATCH, "batch limits differ");
+    if (!items || !codebook || n_items < 1 || n_items > QAMW_MAX_BATCH) return QAMW_ERR_INVALID_ARG;
+    if (dtype != QAMW_DTYPE_F32 && dtype != QAMW_DTYPE_BF16) return QAMW_ERR_INVALID_ARG;
+    qamw::EncodeItem its[QAMW_MAX_BATCH];
+    bool fused = true;
+    for (int i = 0; i < n_items; ++i) {
+        const qamw_encode_item &q = items[i];
+        if (!q.W || !q.packed_out || !q.row_norms_out || misaligned4(q.packed_out)) return QAMW_ERR_INVALID_ARG;
+        int rc = check_common(q.d_out, q.d_in, bits, hadamard_block);
+        if (rc != QAMW_OK) return rc;
+        if (q.ldw < q.d_in) return QAMW_ERR_SHAPE;
+        its[i] = qamw::EncodeItem{q.W, q.ldw, q.chan_scale, q.signs, q.pair_sigma, q.row_norms_out, q.packed_out, q.d_out, q.d_in};
+        qamw::Problem pi = make_problem(q.d_out, q.d_in, nullptr, nullptr, nullptr, codebook, bits, hadamard_block, stream);
+        fused = fused && qamw::fused_norms_supported(pi);
+    }
+    if (g_kernel_path.load() == 0 && fused) {
+        qamw::Problem shared = make_problem(items[0].d_out, items[0].d_in, nullptr, nullptr, nullptr, codebook, bits,
+                                            hadamard_block, stream);
+        hipError_t e = qamw::launch_encode_batch_mfma(its, n_items, dtype, shared, false);
+        if (e == hipSuccess) return QAMW_OK;
+        if (e != hipErrorNotSupported) return QAMW_ERR_DEVICE;
+    }
+    for (int i = 0; i < n_items; ++i) {                         // nothing was launched: one call per item
+        const qamw_encode_item &q = items[i];
+        int rc = encode_impl(q.W, dtype, q.d_out, q.d_in, q.ldw, q.chan_scale, q.signs, q.pair_sigma, codebook, bits,
+                             hadamard_block, q.packed_out, q.row_norms_out, nullptr, stream);
+        if (rc != QAMW_OK) return rc;
+    }
+    return QAMW_OK;
 }
 
 int qamw_normalised_pairs(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
@@ -250,7 +286,7 @@ int qamw_lloyd_device(const float *samples, uint64_t n_samples, int bits, float 
 int qamw_encode_polar(const void *W, int dtype, int d_out, int d_in, int64_t ldw, const float *chan_scale,
                       const int8_t *signs, const float *pair_sigma, const float *levels, int bits_a, int bits_p,
                       int hadamard_block, uint8_t *packed_out, float *row_norms_out, void *stream) {
-    if (!W || !levels || !packed_out || !row_norms_out) return QAMW_ERR_INVALID_ARG;
+    if (!W || !levels || !packed_out || !row_norms_out || misaligned4(packed_out)) return QAMW_ERR_INVALID_ARG;
     if (dtype != QAMW_DTYPE_F32 && dtype != QAMW_DTYPE_BF16) return QAMW_ERR_INVALID_ARG;
     if (bits_a < 0 || bits_a > QAMW_MAX_POLAR_AMPLITUDE_BITS || bits_p < 0 || bits_p > 12) return QAMW_ERR_INVALID_ARG;
     int rc = check_common(d_out, d_in, bits_a + bits_p, hadamard_block);
@@ -270,7 +306,7 @@ int qamw_encode_pruned(const void *W, int dtype, int d_out, int d_in, int64_t ld
                        const int8_t *signs, const float *pair_sigma, const float *codebook, int bits, int hadamard_block,
                        const void *grid, uint8_t *packed_out, float *row_norms_out, unsigned long long *full_scans,
                        void *stream) {
-    if (!W || !codebook || !grid || !packed_out || !row_norms_out) return QAMW_ERR_INVALID_ARG;
+    if (!W || !codebook || !grid || !packed_out || !row_norms_out || misaligned4(packed_out)) return QAMW_ERR_INVALID_ARG;
     if (dtype != QAMW_DTYPE_F32 && dtype != QAMW_DTYPE_BF16) return QAMW_ERR_INVALID_ARG;
     int rc = check_common(d_out, d_in, bits, hadamard_block);
     if (rc != QAMW_OK) return rc;
@@ -303,7 +339,7 @@ static int decode_batch_impl(const qamw_decode_item *items, int n_items, const f
     qamw::DecodeItem its[QAMW_MAX_BATCH];
     for (int i = 0; i < n_items; ++i) {
         const qamw_decode_item &q = items[i];
-        if (!q.packed || !q.row_norms || !q.W_out) return QAMW_ERR_INVALID_ARG;
+        if (!q.packed || !q.row_norms || !q.W_out || misaligned4(q.packed)) return QAMW_ERR_INVALID_ARG;
         int rc = check_common(q.d_out, q.d_in, bits, hadamard_block);
         if (rc != QAMW_OK) return rc;
         if (q.ldo < q.d_in) return QAMW_ERR_SHAPE;

@@ -22,6 +22,7 @@
 // lane's 16 accumulator rows {8q + 4h + t} of two consecutive 32-codeword blocks (of one block for
 // codebooks of up to 256 points).
 #include <atomic>
+#include <cmath>
 
 #include "qamw_front.hpp"
 
@@ -56,24 +57,66 @@ __device__ __forceinline__ uint32_t pack2(uint32_t even, uint32_t odd) { return 
 
 // CH: 32-codeword blocks per chunk.  Two halve the tracking work of the main loop; one halves the exact distances
 // of the decision stage (8 instead of 16 per lane and point), which is what matters for a small codebook.
+// One matrix of an encode launch, as the kernel sees it, and the work list of the launch: workgroups are numbered
+// matrix-major; a workgroup's MF_WAVES items belong to one matrix.
+struct EncodeMat {
+    const void *W;
+    int64_t ldw;
+    const float *chan_scale;
+    const int8_t *signs;
+    const float *pair_sigma;
+    float *norms;
+    uint8_t *packed;
+    int64_t row_bytes;
+    int d_in, n_slabs, n_items;
+    float g_default;                      // sqrt(d_in): the pair gain when pair_sigma is NULL
+};
+struct EncodeBatch {
+    EncodeMat m[QAMW_ENCODE_MAX_BATCH];
+    int block_begin[QAMW_ENCODE_MAX_BATCH + 1];   // first workgroup of each matrix; block_begin[n] = total
+    int n;
+    int bits, K;
+    float inv_sqrt_block;
+    const float *codebook;
+    unsigned long long *full_scans;
+};
+
 template <int DTYPE, int B, int CH>
-__global__ __launch_bounds__(MF_THREADS) void k_encode_mfma(const void *__restrict__ W, int64_t ldw, Problem p,
-                                                            const float *__restrict__ norms_in, float *__restrict__ norms_out,
-                                                            uint8_t *__restrict__ packed, int n_slabs, int n_items,
-                                                            int n_blocks) {
+__global__ __launch_bounds__(MF_THREADS) void k_encode_mfma(EncodeBatch bt, int fused) {
     extern __shared__ __align__(16) float lds_raw[];
     float2 *c01 = reinterpret_cast<float2 *>(lds_raw);          // K x (c0, c1)
-    uint32_t *e67 = reinterpret_cast<uint32_t *>(lds_raw + 2 * p.K);   // K x 2: bf16 pieces of ||c||^2, (h, m) and (l, 0)
+    uint32_t *e67 = reinterpret_cast<uint32_t *>(lds_raw + 2 * bt.K);   // K x 2: bf16 pieces of ||c||^2, (h, m) and (l, 0)
     __shared__ float red[MF_WAVES];
     __shared__ double norm_part[2 * FUSED_NORM_MAX_SLABS];
 
     const int lane = threadIdx.x & (WAVE - 1);
     const int wid = threadIdx.x >> 6;
-    const int K = p.K;
-    // norms_in == NULL: the workgroup computes the norms of the rows its items touch (and writes them out) before
-    // anything else; the barrier after the codebook staging below also publishes the slab sums.
-    const bool fused = norms_in == nullptr;
-    const int item0 = (fused ? fused_norm_block(blockIdx.x, n_blocks) : (int)blockIdx.x) * MF_WAVES;
+    const int K = bt.K;
+    // fused: the workgroup computes the norms of the rows its items touch (and writes them out) before anything else;
+    // the barrier after the codebook staging below also publishes the slab sums.  Otherwise they are read.
+    const int n_blocks = bt.block_begin[bt.n];
+    const int blk = min(fused ? fused_norm_block(blockIdx.x, n_blocks) : (int)blockIdx.x, n_blocks);   // n_blocks: nothing to do
+    int mi = 0;
+    while (mi + 1 < bt.n && blk >= bt.block_begin[mi + 1]) ++mi;
+    const EncodeMat &M = bt.m[mi];
+    Problem p;
+    p.d_in = M.d_in;
+    p.bits = bt.bits;
+    p.K = K;
+    p.chan_scale = M.chan_scale;
+    p.signs = M.signs;
+    p.pair_sigma = M.pair_sigma;
+    p.codebook = bt.codebook;
+    p.inv_sqrt_block = bt.inv_sqrt_block;
+    p.g_default = M.g_default;
+    p.row_bytes = M.row_bytes;
+    p.full_scans = bt.full_scans;
+    const void *__restrict__ W = M.W;
+    const int64_t ldw = M.ldw;
+    const int n_slabs = M.n_slabs, n_items = M.n_items;
+    float *__restrict__ norms = M.norms;
+    uint8_t *__restrict__ packed = M.packed;
+    const int item0 = blk < n_blocks ? (blk - bt.block_begin[mi]) * MF_WAVES : n_items;
     if (fused && item0 < n_items) block_slab_sums<DTYPE, MF_WAVES>(norm_part, W, ldw, p, item0, n_items, n_slabs, lane, wid);
     float *wave_area = lds_raw + 4 * K + wid * MF_WAVE_LDS_FLOATS;
     float2 *pts = reinterpret_cast<float2 *>(wave_area);        // the wave's 512 points, pair order
@@ -106,9 +149,9 @@ __global__ __launch_bounds__(MF_THREADS) void k_encode_mfma(const void *__restri
     float rnorm;
     if (fused) {
         rnorm = row_norm_from_slab_sums(norm_part, row, item0, n_slabs);
-        if (slab == 0 && lane == 0) norms_out[row] = rnorm;
+        if (slab == 0 && lane == 0) norms[row] = rnorm;
     } else {
-        rnorm = norms_in[row];
+        rnorm = norms[row];
     }
     const LaneSigns<B> ls(lane);
     const int pos = slab_pos(lane);
@@ -287,47 +330,85 @@ template <int DTYPE, int B, int CH> static bool allow_large_lds() {
 }
 
 template <int DTYPE, int B, int CH>
-static hipError_t launch_mdbc(const void *W, int64_t ldw, const Problem &p, float *norms, bool norms_ready, uint8_t *packed) {
-    const int n_slabs = (p.d_in + MSLAB - 1) / MSLAB;
-    const int64_t n_items = (int64_t)p.d_out * n_slabs;
-    if (n_items > 0x7fffffff) return hipErrorNotSupported;
-    if (!norms_ready && n_slabs > FUSED_NORM_MAX_SLABS) return hipErrorNotSupported;
-    const int n_blocks = (int)((n_items + MF_WAVES - 1) / MF_WAVES);
-    const unsigned blocks = (unsigned)(norms_ready ? n_blocks : fused_norm_grid(n_blocks));
+static hipError_t launch_mdbc(const EncodeItem *items, int n, const Problem &p, bool norms_ready) {
+    EncodeBatch bt;
+    int64_t blocks_total = 0;
+    for (int i = 0; i < n; ++i) {
+        EncodeMat &M = bt.m[i];
+        const int n_slabs = (items[i].d_in + MSLAB - 1) / MSLAB;
+        const int64_t n_items = (int64_t)items[i].d_out * n_slabs;
+        if (n_items > 0x3fffffff) return hipErrorNotSupported;
+        if (!norms_ready && n_slabs > FUSED_NORM_MAX_SLABS) return hipErrorNotSupported;
+        M.W = items[i].W;
+        M.ldw = items[i].ldw;
+        M.chan_scale = items[i].chan_scale;
+        M.signs = items[i].signs;
+        M.pair_sigma = items[i].pair_sigma;
+        M.norms = items[i].norms;
+        M.packed = items[i].packed;
+        M.row_bytes = (((int64_t)(items[i].d_in / 2) * p.bits + 31) / 32) * 4;
+        M.d_in = items[i].d_in;
+        M.n_slabs = n_slabs;
+        M.n_items = (int)n_items;
+        M.g_default = (float)std::sqrt((double)items[i].d_in);
+        bt.block_begin[i] = (int)blocks_total;
+        blocks_total += (n_items + MF_WAVES - 1) / MF_WAVES;
+        if (blocks_total > 0x3fffffff) return hipErrorNotSupported;
+    }
+    for (int i = n; i <= QAMW_ENCODE_MAX_BATCH; ++i) bt.block_begin[i] = (int)blocks_total;
+    for (int i = n; i < QAMW_ENCODE_MAX_BATCH; ++i) bt.m[i] = bt.m[0];
+    bt.n = n;
+    bt.bits = p.bits;
+    bt.K = p.K;
+    bt.inv_sqrt_block = p.inv_sqrt_block;
+    bt.codebook = p.codebook;
+    bt.full_scans = p.full_scans;
+    const unsigned blocks = (unsigned)(norms_ready ? blocks_total : fused_norm_grid((int)blocks_total));
     const size_t lds = ((size_t)p.K * 4 + (size_t)MF_WAVES * MF_WAVE_LDS_FLOATS) * sizeof(float);
     if (lds > 64 * 1024 && !allow_large_lds<DTYPE, B, CH>()) return hipErrorNotSupported;
-    hipLaunchKernelGGL((k_encode_mfma<DTYPE, B, CH>), dim3(blocks), dim3(MF_THREADS), lds, p.stream, W, ldw, p,
-                       norms_ready ? norms : nullptr, norms, packed, n_slabs, (int)n_items, n_blocks);
+    hipLaunchKernelGGL((k_encode_mfma<DTYPE, B, CH>), dim3(blocks), dim3(MF_THREADS), lds, p.stream, bt, norms_ready ? 0 : 1);
     return hipGetLastError();
 }
 
 // one-block chunks for codebooks of up to 256 points, where the decision stage outweighs the main loop
 template <int DTYPE, int B>
-static hipError_t launch_mdb(const void *W, int64_t ldw, const Problem &p, float *norms, bool norms_ready, uint8_t *packed) {
-    return p.K <= 256 ? launch_mdbc<DTYPE, B, 1>(W, ldw, p, norms, norms_ready, packed)
-                      : launch_mdbc<DTYPE, B, 2>(W, ldw, p, norms, norms_ready, packed);
+static hipError_t launch_mdb(const EncodeItem *items, int n, const Problem &p, bool norms_ready) {
+    return p.K <= 256 ? launch_mdbc<DTYPE, B, 1>(items, n, p, norms_ready) : launch_mdbc<DTYPE, B, 2>(items, n, p, norms_ready);
 }
 
 template <int DTYPE>
-static hipError_t launch_md(const void *W, int64_t ldw, const Problem &p, float *norms, bool norms_ready, uint8_t *packed) {
+static hipError_t launch_md(const EncodeItem *items, int n, const Problem &p, bool norms_ready) {
     switch (p.block) {
-        case 64: return launch_mdb<DTYPE, 64>(W, ldw, p, norms, norms_ready, packed);
-        case 128: return launch_mdb<DTYPE, 128>(W, ldw, p, norms, norms_ready, packed);
-        case 256: return launch_mdb<DTYPE, 256>(W, ldw, p, norms, norms_ready, packed);
-        case 512: return launch_mdb<DTYPE, 512>(W, ldw, p, norms, norms_ready, packed);
-        case 1024: return launch_mdb<DTYPE, 1024>(W, ldw, p, norms, norms_ready, packed);
+        case 64: return launch_mdb<DTYPE, 64>(items, n, p, norms_ready);
+        case 128: return launch_mdb<DTYPE, 128>(items, n, p, norms_ready);
+        case 256: return launch_mdb<DTYPE, 256>(items, n, p, norms_ready);
+        case 512: return launch_mdb<DTYPE, 512>(items, n, p, norms_ready);
+        case 1024: return launch_mdb<DTYPE, 1024>(items, n, p, norms_ready);
         default: return hipErrorNotSupported;
     }
 }
 
-// Returns hipErrorNotSupported (nothing launched) when the shape or alignment is outside this kernel's range.
-// norms_ready: the row norms are already in `norms`; otherwise the kernel computes them itself and writes them there.
+// n <= QAMW_ENCODE_MAX_BATCH matrices that share codebook, bits, block and element type in ONE launch; p carries the
+// shared fields.  Returns hipErrorNotSupported (nothing launched) when any item's shape or alignment is outside this
+// kernel's range.  norms_ready: the row norms are already in every item's `norms`; otherwise the kernel computes them
+// itself and writes them there.
+hipError_t launch_encode_batch_mfma(const EncodeItem *items, int n, int dtype, const Problem &p, bool norms_ready) {
+    if (n < 1 || n > QAMW_ENCODE_MAX_BATCH || (reinterpret_cast<uintptr_t>(p.codebook) & 15)) return hipErrorNotSupported;
+    for (int i = 0; i < n; ++i) {
+        Problem q = p;
+        q.d_in = items[i].d_in;
+        q.chan_scale = items[i].chan_scale;
+        q.signs = items[i].signs;
+        q.pair_sigma = items[i].pair_sigma;
+        if (!mfma_encode_supported(q) || !front_alignment_ok(items[i].W, dtype, items[i].ldw, q)) return hipErrorNotSupported;
+    }
+    return dtype == 0 ? launch_md<0>(items, n, p, norms_ready) : launch_md<1>(items, n, p, norms_ready);
+}
+
 hipError_t launch_encode_mfma(const void *W, int dtype, int64_t ldw, const Problem &p, float *norms, bool norms_ready,
                               uint8_t *packed) {
-    const bool ok = mfma_encode_supported(p) && front_alignment_ok(W, dtype, ldw, p) &&
-                    ((reinterpret_cast<uintptr_t>(p.codebook) & 15) == 0);
-    if (!ok) return hipErrorNotSupported;
-    return dtype == 0 ? launch_md<0>(W, ldw, p, norms, norms_ready, packed) : launch_md<1>(W, ldw, p, norms, norms_ready, packed);
+    const EncodeItem it{W, ldw, p.chan_scale, p.signs, p.pair_sigma, norms, packed, p.d_out, p.d_in};
+    return launch_encode_batch_mfma(&it, 1, dtype, p, norms_ready);
 }
 
 }  // namespace qamw

@@ -100,5 +100,18 @@ hipError_t launch_encode_grid(const void *W, int dtype, int64_t ldw, const Probl
 bool mfma_encode_supported(const Problem &p);
 hipError_t launch_encode_mfma(const void *W, int dtype, int64_t ldw, const Problem &p, float *norms, bool norms_ready,
                               uint8_t *packed);
+// One matrix of an encode batch (host-side description) and the batch launch of the matrix-core encoder.
+constexpr int QAMW_ENCODE_MAX_BATCH = 16;
+struct EncodeItem {
+    const void *W;
+    int64_t ldw;
+    const float *chan_scale;
+    const int8_t *signs;
+    const float *pair_sigma;
+    float *norms;
+    uint8_t *packed;
+    int d_out, d_in;
+};
+hipError_t launch_encode_batch_mfma(const EncodeItem *items, int n, int dtype, const Problem &p, bool norms_ready);
 
 }  // namespace qamw

@@ -367,10 +367,11 @@ __global__ __launch_bounds__(GV_THREADS) void k_qgemv(GemvBatch bt) {
                     acc[t][r] = __builtin_fmaf(cw.y, z[t][2 * k + 1], __builtin_fmaf(cw.x, z[t][2 * k], acc[t][r]));
             }
         }
-        // totals over the lanes: every lane ends with one of the group's 8 rows (8 lanes hold each); one of them adds it in
+        // totals over the lanes: every lane ends with one of the group's RG rows (64 / RG lanes hold each, the ones that
+        // share the lane number's upper bits); the first of them adds it in
 #pragma unroll
         for (int t = 0; t < MT; ++t) gv_reduce_rows<RG>(acc[t], lane);
-        if ((lane & 7) == 0) {
+        if ((lane & (WAVE / RG - 1)) == 0) {
 #pragma unroll
             for (int t = 0; t < MT; ++t) red[(wid * UR + g * RG + my_row) * MT + t] += acc[t][0];
         }

@@ -680,6 +680,31 @@ def test_decode_batch_equals_single_calls(orc, codebooks, kernel_path, sigma):
         check_decode(orc, cs, ref["idx"], ref["norms"].astype(np.float32), got_bf16=got)
 
 
+@pytest.mark.parametrize("bits,block,dtype", [(11, 128, "bf16"), (7, 256, "f32"), (5, 64, "f32")])
+def test_encode_batch_equals_single_calls(orc, codebooks, kernel_path, bits, block, dtype):
+    """One launch for several matrices of different shapes (ragged slabs, odd row counts, rows that straddle
+    workgroups) gives exactly the bytes and norms the per-matrix entry point gives, and both match the oracle.
+    (5 bits: a codebook the batched kernel does not take -- the call falls back to single launches.)"""
+    say(f"[encode batch] B={bits} b={block} {dtype} path={kernel_path}")
+    shapes = [(171, 33, 4096), (172, 18, 11008), (173, 7, 1280), (174, 41, 5632), (175, 1, 256), (176, 9, 13824), (177, 5, 2048)]
+    cases = [Case(orc, sd, do, di, bits, block, dtype=dtype, codebook=codebooks[bits]) for sd, do, di in shapes]
+    entries, singles = [], []
+    for cs in cases:
+        rb = qamw.packed_row_bytes(cs.d_in, bits)
+        packed = torch.full((cs.d_out, rb), 0xAB, dtype=torch.uint8, device="cuda")
+        norms = torch.full((cs.d_out,), -1.0, dtype=torch.float32, device="cuda")
+        entries.append((cs.W_dev, cs.s_dev, cs.sg_dev, cs.sigma_dev, packed, norms))
+        singles.append(qamw.encode(cs.W_dev, cs.cb_dev, bits, block, chan_scale=cs.s_dev, signs=cs.sg_dev, pair_sigma=cs.sigma_dev))
+    items = qamw.make_encode_items(entries)
+    qamw.encode_batch(items, cases[0].cb_dev, bits, block)
+    torch.cuda.synchronize()
+    for cs, e, single in zip(cases, entries, singles):
+        assert torch.equal(e[4], single[0]) and torch.equal(e[5], single[1])
+        rep = {}
+        check_encode(orc, cs, e[4].cpu().numpy(), e[5].cpu().numpy(), cs.oracle_encode(orc), report=rep)
+        say("   ", rep)
+
+
 def test_calibrate_sigma_matches_oracle(orc, kernel_path):
     for seed, d_out, d_in, block, dtype in [(61, 1500, 512, 128, "f32"), (62, 300, 2048, 1024, "bf16"),
                                             (63, 64, 1280, 256, "f32"), (64, 10, 96, 2, "f32"), (65, 33, 5632, 512, "f32"),

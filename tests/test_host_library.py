@@ -100,6 +100,9 @@ def test_device_entry_points_reject_bad_arguments_before_any_launch():
         assert f(d_in=384, ldw=384, block=256) == qamw.ERR_SHAPE   # does not divide d_in
         assert f(ldw=255) == qamw.ERR_SHAPE                    # leading dimension too small
     assert enc(dtype=7) == qamw.ERR_INVALID_ARG
+    # the packed stream is handled in 32-bit words: a buffer that is not 4-byte aligned is rejected
+    assert enc(packed=C.c_void_p(0x1002)) == qamw.ERR_INVALID_ARG
+    assert dec(packed=C.c_void_p(0x1001)) == qamw.ERR_INVALID_ARG
     a = good
     assert L.qamw_encode_stats(a["W"], 0, 8, 256, 256, None, None, None, a["cb"], 11, 128, a["packed"], a["norms"], None,
                                None) == qamw.ERR_INVALID_ARG          # the counter is required
@@ -145,6 +148,29 @@ def test_device_entry_points_reject_bad_arguments_before_any_launch():
     assert cal_static(dtype=2) == qamw.ERR_INVALID_ARG
     assert qamw.calibrate_workspace_bytes(16384, 4096, 1024) <= qamw.STATIC_SCRATCH_BYTES
     assert cal_static(d_out=2048, d_in=16512, ldw=16512) == qamw.ERR_UNSUPPORTED   # beyond the static scratch
+
+
+def test_encode_batch_rejects_bad_arguments():
+    L = qamw.lib()
+    p = C.c_void_p(0x1000)
+    arr = (qamw.EncodeItem * 2)()
+    for i in range(2):
+        arr[i] = qamw.EncodeItem(0x1000, 256, None, None, None, 0x2000, 0x3000, 8, 256)
+    assert L.qamw_encode_batch(None, 2, 0, p, 11, 128, None) == qamw.ERR_INVALID_ARG
+    assert L.qamw_encode_batch(arr, 0, 0, p, 11, 128, None) == qamw.ERR_INVALID_ARG
+    assert L.qamw_encode_batch(arr, 17, 0, p, 11, 128, None) == qamw.ERR_INVALID_ARG
+    assert L.qamw_encode_batch(arr, 2, 0, None, 11, 128, None) == qamw.ERR_INVALID_ARG
+    assert L.qamw_encode_batch(arr, 2, 5, p, 11, 128, None) == qamw.ERR_INVALID_ARG          # element type
+    assert L.qamw_encode_batch(arr, 2, 0, p, 13, 128, None) == qamw.ERR_INVALID_ARG
+    assert L.qamw_encode_batch(arr, 2, 0, p, 11, 96, None) == qamw.ERR_SHAPE
+    arr[1].ldw = 100
+    assert L.qamw_encode_batch(arr, 2, 0, p, 11, 128, None) == qamw.ERR_SHAPE                # leading dimension too small
+    arr[1].ldw = 256
+    arr[1].packed_out = None
+    assert L.qamw_encode_batch(arr, 2, 0, p, 11, 128, None) == qamw.ERR_INVALID_ARG
+    arr[1].packed_out = 0x2000
+    arr[0].d_in = 255
+    assert L.qamw_encode_batch(arr, 2, 0, p, 11, 128, None) == qamw.ERR_SHAPE
 
 
 def test_decode_batch_rejects_bad_arguments():
