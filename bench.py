@@ -3,7 +3,8 @@
 
 A step is one pass of the whole hot path over one model-shaped synthetic weight set that is
 already resident in HBM: for every matrix, pair-scale calibration (Eq. 1) and encode (row norms,
-rotation, nearest codeword, bit-pack), then decode of every layer to bf16 (one launch per layer).
+rotation, nearest codeword, bit-pack), then decode of every layer to bf16; a layer's matrices go
+through each entry point together (qamw_calibrate_sigma_batch, qamw_encode_batch, qamw_decode_batch).
 Rank 0 prints one JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--layers L]
@@ -72,32 +73,32 @@ def build_workload(wl, layers, device):
     return mats
 
 
-def run_step(mats, batches, wl, cb, ws, timed):
-    """One pass: calibrate + encode every matrix, then decode every layer (one qamw_decode_batch launch per
-    layer).  Returns the event triples (before calibration, between, after encode) per matrix and the event pairs of
-    each decode launch."""
+def run_step(layers, wl, cb, ws, timed):
+    """One pass: for every layer, pair-scale calibration of its matrices (qamw_calibrate_sigma_batch), their encode
+    (qamw_encode_batch), and after all layers the decode of every layer (qamw_decode_batch): three entry points per
+    layer, one launch (calibration: two) each.  Returns the event triples (before calibration, between, after encode)
+    per layer and the event pairs of each decode launch."""
     import torch
 
     from paper_2605_26339_amd import qamw
 
     ev_enc, ev_dec = [], []
-    for m in mats:
+    for cal_items, enc_items, _ in layers:
         e = [torch.cuda.Event(enable_timing=True) for _ in range(3)] if timed else None
         if timed:
             e[0].record()
-        qamw.calibrate_sigma(m["W"], wl.block, chan_scale=m["s"], signs=m["sg"], workspace=ws, out=m["sigma"])
+        qamw.calibrate_sigma_batch(cal_items, wl.block, ws)
         if timed:
             e[1].record()
-        qamw.encode(m["W"], cb, wl.bits, wl.block, chan_scale=m["s"], signs=m["sg"], pair_sigma=m["sigma"],
-                    out=(m["packed"], m["norms"]))
+        qamw.encode_batch(enc_items, cb, wl.bits, wl.block)
         if timed:
             e[2].record()
             ev_enc.append(e)
-    for items in batches:
+    for _, _, dec_items in layers:
         e = [torch.cuda.Event(enable_timing=True) for _ in range(2)] if timed else None
         if timed:
             e[0].record()
-        qamw.decode_batch(items, cb, wl.bits, wl.block)
+        qamw.decode_batch(dec_items, cb, wl.bits, wl.block)
         if timed:
             e[1].record()
             ev_dec.append(e)
@@ -142,20 +143,24 @@ def measure_workload(wl, layers, steps, warmup, decode_passes, dev, cb, valu_pat
     from paper_2605_26339_amd import qamw
 
     mats = build_workload(wl, layers, dev)
-    ws = torch.empty(max(qamw.calibrate_workspace_bytes(m["d_in"], m["d_out"]) for m in mats), dtype=torch.uint8, device=dev)
     per_layer = len(wl.matrices)
-    batches = [qamw.make_decode_items([(m["packed"], m["norms"], m["d_in"], m["s"], m["sg"], m["sigma"], m["out"])
-                                       for m in mats[i:i + per_layer]]) for i in range(0, len(mats), per_layer)]
+    by_layer = [mats[i:i + per_layer] for i in range(0, len(mats), per_layer)]
+    batches = [qamw.make_decode_items([(m["packed"], m["norms"], m["d_in"], m["s"], m["sg"], m["sigma"], m["out"]) for m in lm])
+               for lm in by_layer]
+    layer_items = [(qamw.make_calibrate_items([(m["W"], m["s"], m["sg"], m["sigma"]) for m in lm]),
+                    qamw.make_encode_items([(m["W"], m["s"], m["sg"], m["sigma"], m["packed"], m["norms"]) for m in lm]), dec)
+                   for lm, dec in zip(by_layer, batches)]
+    ws = torch.empty(max(li[0][3] for li in layer_items), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
     for _ in range(warmup):
-        run_step(mats, batches, wl, cb, ws, timed=False)
+        run_step(layer_items, wl, cb, ws, timed=False)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     start.record()
     all_enc, all_dec = [], []
     for _ in range(steps):
-        ev_enc, ev_dec = run_step(mats, batches, wl, cb, ws, timed=True)
+        ev_enc, ev_dec = run_step(layer_items, wl, cb, ws, timed=True)
         all_enc.extend(ev_enc)
         all_dec.extend(ev_dec)
     stop.record()
@@ -236,12 +241,12 @@ def measure_workload(wl, layers, steps, warmup, decode_passes, dev, cb, valu_pat
                    "pass_gb_per_s_median": pass_ms and dec_bytes_step / (median(pass_ms) * 1e-3) / 1e9,
                    "pass_gb_per_s_best": pass_ms and dec_bytes_step / (min(pass_ms) * 1e-3) / 1e9,
                    "pass_frac_of_peak_median": pass_ms and dec_bytes_step / (median(pass_ms) * 1e-3) / 1e9 / PEAK_HBM_GBS},
-        "roofline": {"kernel": "qamw_encode (row norm + nearest-codeword search)", "bound": "alu",
+        "roofline": {"kernel": "qamw_encode_batch (one launch per layer, %d matrices: row norms + nearest-codeword search)" % per_layer, "bound": "alu",
                      "unit_doing_the_work": SHORTLIST_UNIT,
                      "achieved": enc_tflops, "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s",
                      "frac": enc_tflops / PEAK_FP32_TFLOPS,
                      "strict_roofline_gpairs_per_s": PEAK_FP32_TFLOPS * 1e3 / FLOPS_PER_EVAL / wl.K,
-                     "traffic": traffic and traffic["encode"], "traffic_source": traffic_source,
+                     "traffic": traffic and traffic["encode"] * per_layer, "traffic_source": traffic_source,
                      "avg_launch_ms": enc_ms / n_launch,
                      "algorithmic_flops_per_launch": evals * FLOPS_PER_EVAL / n_launch,
                      # what the shortlist spends on the matrix cores to get there: one 32x32x16 bf16 tile

@@ -135,6 +135,25 @@ int qamw_calibrate_sigma(const void *W, int dtype, int d_out, int d_in, int64_t 
                          int max_rows, void *workspace, size_t workspace_bytes, float *sigma_out,
                          void *stream);
 
+/* qamw_calibrate_sigma for several matrices that share the element type and hadamard_block, in one pair of launches
+ * (the calibration of one matrix is tens of microseconds of work on a fraction of the chip).  items: HOST array, read
+ * during the call only; every pointer in it is a device pointer with the meaning it has in qamw_calibrate_sigma.
+ * workspace: at least the sum over the items of qamw_calibrate_workspace_bytes() each rounded up to a multiple of 256,
+ * 16-byte aligned.  Results are identical, bit for bit, to n_items calls of qamw_calibrate_sigma.  Items the fast
+ * kernels cannot take make the whole call fall back to one call per item.
+ * Errors: items NULL, n_items outside [1, QAMW_MAX_BATCH], workspace NULL / misaligned / too small, any item invalid
+ * as for qamw_calibrate_sigma. */
+typedef struct qamw_calibrate_item {
+    const void *W;               /* d_out rows of d_in elements of the batch's dtype, leading dimension ldw */
+    int64_t ldw;
+    const float *chan_scale;     /* d_in floats or NULL                                                   */
+    const int8_t *signs;         /* d_in int8 or NULL                                                     */
+    float *sigma_out;            /* d_in/2 floats                                                         */
+    int32_t d_out, d_in;
+} qamw_calibrate_item;
+int qamw_calibrate_sigma_batch(const qamw_calibrate_item *items, int n_items, int dtype, int hadamard_block,
+                               int max_rows, void *workspace, size_t workspace_bytes, void *stream);
+
 /* qamw_calibrate_sigma for callers that cannot allocate device memory or pass a workspace: code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the workspace,
  * same kernels, same result bit for bit; the scratch is a static device array of QAMW_STATIC_SCRATCH_BYTES

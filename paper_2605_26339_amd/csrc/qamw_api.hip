@@ -121,6 +121,48 @@ int qamw_calibrate_sigma(const void *W, int dtype, int d_out, int d_in, int64_t 
     return calibrate_impl(W, dtype, d_out, d_in, ldw, chan_scale, signs, hadamard_block, max_rows, workspace, sigma_out, stream);
 }
 
+int qamw_calibrate_sigma_batch(const qamw_calibrate_item *items, int n_items, int dtype, int hadamard_block, int max_rows,
+                               void *workspace, size_t workspace_bytes, void *stream) {
+    static_assert(QAMW_MAX_BATCH == qamw::CAL_MAX_BATCH, "batch limits differ");
+    if (!items || !workspace || n_items < 1 || n_items > QAMW_MAX_BATCH) return QAMW_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(workspace) & 15) return QAMW_ERR_INVALID_ARG;
+    qamw::CalItem its[QAMW_MAX_BATCH];
+    char *ws = static_cast<char *>(workspace);
+    size_t used = 0;
+    bool fast = g_kernel_path.load() != 1;
+    for (int i = 0; i < n_items; ++i) {
+        const qamw_calibrate_item &q = items[i];
+        int rc = calibrate_check(q.W, dtype, q.d_out, q.d_in, q.ldw, hadamard_block, max_rows, q.sigma_out);
+        if (rc != QAMW_OK) return rc;
+        size_t need = 0;
+        qamw_calibrate_workspace_bytes(q.d_in, q.d_out, max_rows, &need);
+        need = align_up(need, 256);
+        if (used + need > workspace_bytes) return QAMW_ERR_INVALID_ARG;
+        const int n = q.d_out < max_rows ? q.d_out : max_rows;
+        double *partial = reinterpret_cast<double *>(ws + used + align_up((size_t)n * sizeof(float), 256));
+        its[i] = qamw::CalItem{q.W, q.ldw, q.chan_scale, q.signs, partial, q.sigma_out, n, q.d_in};
+        qamw::Problem pi = make_problem(q.d_out, q.d_in, q.chan_scale, q.signs, nullptr, nullptr, 1, hadamard_block, stream);
+        fast = fast && qamw::fast_calibrate_supported(q.W, dtype, q.ldw, pi);
+        used += need;
+    }
+    if (fast) {
+        hipError_t e = qamw::launch_calibrate_batch_fast(its, n_items, dtype, hadamard_block, (hipStream_t)stream);
+        if (e == hipSuccess) return QAMW_OK;
+        if (e != hipErrorNotSupported) return QAMW_ERR_DEVICE;
+    }
+    used = 0;
+    for (int i = 0; i < n_items; ++i) {                         // nothing was launched: one call per item, each in its own piece
+        const qamw_calibrate_item &q = items[i];
+        size_t need = 0;
+        qamw_calibrate_workspace_bytes(q.d_in, q.d_out, max_rows, &need);
+        int rc = calibrate_impl(q.W, dtype, q.d_out, q.d_in, q.ldw, q.chan_scale, q.signs, hadamard_block, max_rows, ws + used,
+                                q.sigma_out, stream);
+        if (rc != QAMW_OK) return rc;
+        used += align_up(need, 256);
+    }
+    return QAMW_OK;
+}
+
 // ---------------------------------------------------------------------------------------------
 // The calibration for callers that cannot allocate: its scratch is this file-scope device array.
 // Every device the library runs on holds its own copy at its own address; the name below is only

@@ -1,4 +1,6 @@
 // Vectorised row norms and the shape-specialised pair-scale calibration (Eq. 1).
+#include <cmath>
+
 #include "qamw_front.hpp"
 
 namespace qamw {
@@ -63,17 +65,48 @@ bool launch_row_norms_fast(const void *W, int dtype, int64_t ldw, int n_rows, co
 }
 
 // ---------------------------------------------------------------------------------------------
-// Calibration, step 1: one workgroup per chunk of CAL_ROWS consecutive rows.  It first computes the norms of its rows
-// (slab sums in LDS, as the encoders do: the head rows are fetched from memory once), then wave w takes the slabs
+// Calibration of up to CAL_MAX_BATCH matrices in one pair of launches.
+// Step 1: one workgroup per chunk of CAL_ROWS consecutive rows of one matrix.  It first computes the norms of its
+// rows (slab sums in LDS, as the encoders do: the head rows are fetched from memory once), then wave w takes the slabs
 // w, w + CF_WAVES, ... and sums |z_k| over the chunk's rows, row by row, in fp64, and writes one partial sum per pair.
+// Step 2: per pair, the partial sums added in chunk order, then Eq. 1.
 // ---------------------------------------------------------------------------------------------
+struct CalMat {
+    const void *W;
+    int64_t ldw;
+    const float *chan_scale;
+    const int8_t *signs;
+    double *partial;                      // n_chunks x (d_in / 2) partial sums
+    float *sigma_out;
+    int n_rows, d_in, n_slabs, n_chunks;
+    float sigma_default;
+};
+struct CalBatch {
+    CalMat m[CAL_MAX_BATCH];
+    int chunk_begin[CAL_MAX_BATCH + 1];   // first step-1 workgroup of each matrix
+    int fin_begin[CAL_MAX_BATCH + 1];     // first step-2 workgroup of each matrix
+    int n;
+    float inv_sqrt_block;
+};
+
 template <int DTYPE, int B>
-__global__ __launch_bounds__(CF_THREADS) void k_calibrate_partial(const void *__restrict__ W, int64_t ldw, int n_rows,
-                                                                  Problem p, double *__restrict__ partial, int n_slabs) {
+__global__ __launch_bounds__(CF_THREADS) void k_calibrate_partial(CalBatch bt) {
     __shared__ double norm_part[CAL_ROWS * FUSED_NORM_MAX_SLABS];
     const int lane = threadIdx.x & (WAVE - 1);
     const int wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int chunk = blockIdx.x;
+    int mi = 0;
+    while (mi + 1 < bt.n && (int)blockIdx.x >= bt.chunk_begin[mi + 1]) ++mi;
+    const CalMat &M = bt.m[mi];
+    Problem p;
+    p.d_in = M.d_in;
+    p.chan_scale = M.chan_scale;
+    p.signs = M.signs;
+    p.inv_sqrt_block = bt.inv_sqrt_block;
+    const void *__restrict__ W = M.W;
+    const int64_t ldw = M.ldw;
+    const int n_rows = M.n_rows, n_slabs = M.n_slabs;
+    double *__restrict__ partial = M.partial;
+    const int chunk = (int)blockIdx.x - bt.chunk_begin[mi];
     const int row0 = chunk * CAL_ROWS, row1 = min(n_rows, row0 + CAL_ROWS);
     const int tasks = (row1 - row0) * n_slabs;
     for (int t = wid; t < tasks; t += CF_WAVES) {
@@ -114,11 +147,13 @@ __global__ __launch_bounds__(CF_THREADS) void k_calibrate_partial(const void *__
     }
 }
 
-// Step 2: per pair, add the partial sums in chunk order and apply Eq. 1.
-__global__ __launch_bounds__(CF_THREADS) void k_calibrate_finish(const double *__restrict__ partial, int n_chunks, int n_rows,
-                                                                 int n_pairs, float sigma_default,
-                                                                 float *__restrict__ sigma_out) {
-    const int k = blockIdx.x * CF_THREADS + threadIdx.x;
+__global__ __launch_bounds__(CF_THREADS) void k_calibrate_finish(CalBatch bt) {
+    int mi = 0;
+    while (mi + 1 < bt.n && (int)blockIdx.x >= bt.fin_begin[mi + 1]) ++mi;
+    const CalMat &M = bt.m[mi];
+    const int n_pairs = M.d_in >> 1, n_chunks = M.n_chunks;
+    const double *__restrict__ partial = M.partial;
+    const int k = ((int)blockIdx.x - bt.fin_begin[mi]) * CF_THREADS + threadIdx.x;
     if (k >= n_pairs) return;
     double acc = 0.0;
     int q = 0;
@@ -131,8 +166,8 @@ __global__ __launch_bounds__(CF_THREADS) void k_calibrate_finish(const double *_
     }
     for (; q < n_chunks; ++q) acc += partial[(int64_t)q * n_pairs + k];
     const double sqrt_half_pi = 1.2533141373155002512078826424055;
-    const float s = (float)((acc / (double)n_rows) / sqrt_half_pi);
-    sigma_out[k] = (s > 0.0f) ? s : sigma_default;
+    const float s = (float)((acc / (double)M.n_rows) / sqrt_half_pi);
+    M.sigma_out[k] = (s > 0.0f) ? s : M.sigma_default;
 }
 
 bool fused_norms_supported(const Problem &p) { return (p.d_in + 1023) / 1024 <= FUSED_NORM_MAX_SLABS; }
@@ -142,28 +177,21 @@ size_t calibrate_partial_bytes(int d_in, int n_rows) {
     return n_chunks * (size_t)(d_in / 2) * sizeof(double);
 }
 
-template <int DTYPE, int B>
-static hipError_t launch_cal(const void *W, int64_t ldw, int n_rows, const Problem &p, double *partial, float *sigma_out) {
-    const int n_slabs = (p.d_in + CSLAB - 1) / CSLAB;
-    const int n_chunks = (n_rows + CAL_ROWS - 1) / CAL_ROWS;
-    hipLaunchKernelGGL((k_calibrate_partial<DTYPE, B>), dim3(n_chunks), dim3(CF_THREADS), 0, p.stream, W, ldw, n_rows, p,
-                       partial, n_slabs);
+template <int DTYPE, int B> static hipError_t launch_cal(const CalBatch &bt, hipStream_t stream) {
+    hipLaunchKernelGGL((k_calibrate_partial<DTYPE, B>), dim3(bt.chunk_begin[bt.n]), dim3(CF_THREADS), 0, stream, bt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int n_pairs = p.d_in / 2;
-    hipLaunchKernelGGL(k_calibrate_finish, dim3((n_pairs + CF_THREADS - 1) / CF_THREADS), dim3(CF_THREADS), 0, p.stream,
-                       partial, n_chunks, n_rows, n_pairs, p.sigma_default, sigma_out);
+    hipLaunchKernelGGL(k_calibrate_finish, dim3(bt.fin_begin[bt.n]), dim3(CF_THREADS), 0, stream, bt);
     return hipGetLastError();
 }
 
-template <int DTYPE>
-static hipError_t launch_cal_d(const void *W, int64_t ldw, int n_rows, const Problem &p, double *partial, float *sigma_out) {
-    switch (p.block) {
-        case 64: return launch_cal<DTYPE, 64>(W, ldw, n_rows, p, partial, sigma_out);
-        case 128: return launch_cal<DTYPE, 128>(W, ldw, n_rows, p, partial, sigma_out);
-        case 256: return launch_cal<DTYPE, 256>(W, ldw, n_rows, p, partial, sigma_out);
-        case 512: return launch_cal<DTYPE, 512>(W, ldw, n_rows, p, partial, sigma_out);
-        case 1024: return launch_cal<DTYPE, 1024>(W, ldw, n_rows, p, partial, sigma_out);
+template <int DTYPE> static hipError_t launch_cal_d(const CalBatch &bt, int block, hipStream_t stream) {
+    switch (block) {
+        case 64: return launch_cal<DTYPE, 64>(bt, stream);
+        case 128: return launch_cal<DTYPE, 128>(bt, stream);
+        case 256: return launch_cal<DTYPE, 256>(bt, stream);
+        case 512: return launch_cal<DTYPE, 512>(bt, stream);
+        case 1024: return launch_cal<DTYPE, 1024>(bt, stream);
         default: return hipErrorNotSupported;
     }
 }
@@ -173,11 +201,45 @@ bool fast_calibrate_supported(const void *W, int dtype, int64_t ldw, const Probl
     return p.d_in % unit == 0 && p.block >= 64 && fused_norms_supported(p) && front_alignment_ok(W, dtype, ldw, p);
 }
 
-// Two launches; the kernels compute the head rows' norms themselves.
+// n <= CAL_MAX_BATCH matrices, two launches in all; the kernels compute the head rows' norms themselves.  The caller
+// has checked every item with fast_calibrate_supported().
+hipError_t launch_calibrate_batch_fast(const CalItem *items, int n, int dtype, int block, hipStream_t stream) {
+    if (n < 1 || n > CAL_MAX_BATCH) return hipErrorNotSupported;
+    CalBatch bt;
+    int64_t chunks = 0, fin = 0;
+    for (int i = 0; i < n; ++i) {
+        CalMat &M = bt.m[i];
+        M.W = items[i].W;
+        M.ldw = items[i].ldw;
+        M.chan_scale = items[i].chan_scale;
+        M.signs = items[i].signs;
+        M.partial = items[i].partial;
+        M.sigma_out = items[i].sigma_out;
+        M.n_rows = items[i].n_rows;
+        M.d_in = items[i].d_in;
+        M.n_slabs = (items[i].d_in + CSLAB - 1) / CSLAB;
+        M.n_chunks = (items[i].n_rows + CAL_ROWS - 1) / CAL_ROWS;
+        M.sigma_default = (float)(1.0 / std::sqrt((double)items[i].d_in));
+        bt.chunk_begin[i] = (int)chunks;
+        bt.fin_begin[i] = (int)fin;
+        chunks += M.n_chunks;
+        fin += (items[i].d_in / 2 + CF_THREADS - 1) / CF_THREADS;
+        if (chunks > 0x3fffffff || fin > 0x3fffffff) return hipErrorNotSupported;
+    }
+    for (int i = n; i <= CAL_MAX_BATCH; ++i) {
+        bt.chunk_begin[i] = (int)chunks;
+        bt.fin_begin[i] = (int)fin;
+    }
+    for (int i = n; i < CAL_MAX_BATCH; ++i) bt.m[i] = bt.m[0];
+    bt.n = n;
+    bt.inv_sqrt_block = (float)(1.0 / std::sqrt((double)block));
+    return dtype == 0 ? launch_cal_d<0>(bt, block, stream) : launch_cal_d<1>(bt, block, stream);
+}
+
 hipError_t launch_calibrate_fast(const void *W, int dtype, int64_t ldw, int n_rows, const Problem &p, double *partial,
                                  float *sigma_out) {
-    return dtype == 0 ? launch_cal_d<0>(W, ldw, n_rows, p, partial, sigma_out)
-                      : launch_cal_d<1>(W, ldw, n_rows, p, partial, sigma_out);
+    const CalItem it{W, ldw, p.chan_scale, p.signs, partial, sigma_out, n_rows, p.d_in};
+    return launch_calibrate_batch_fast(&it, 1, dtype, p.block, p.stream);
 }
 
 }  // namespace qamw

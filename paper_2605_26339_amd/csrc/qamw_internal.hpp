@@ -39,6 +39,18 @@ size_t calibrate_partial_bytes(int d_in, int n_rows);
 bool fast_calibrate_supported(const void *W, int dtype, int64_t ldw, const Problem &p);
 hipError_t launch_calibrate_fast(const void *W, int dtype, int64_t ldw, int n_rows, const Problem &p, double *partial,
                                  float *sigma_out);
+// Several matrices in one pair of launches (every item checked with fast_calibrate_supported() by the caller).
+constexpr int CAL_MAX_BATCH = 16;
+struct CalItem {
+    const void *W;
+    int64_t ldw;
+    const float *chan_scale;
+    const int8_t *signs;
+    double *partial;                      // calibrate_partial_bytes(d_in, n_rows) bytes
+    float *sigma_out;
+    int n_rows, d_in;                     // n_rows: the head rows used
+};
+hipError_t launch_calibrate_batch_fast(const CalItem *items, int n, int dtype, int block, hipStream_t stream);
 
 // One matrix of a decode batch (host-side description).
 constexpr int QAMW_DECODE_MAX_BATCH = 16;

@@ -22,7 +22,7 @@ EXPORTS = [
     "qamw_decode_f32", "qamw_decode_batch", "qamw_set_kernel_path", "qamw_polar_codebook", "qamw_encode_polar",
     "qamw_matmul_workspace_bytes", "qamw_matmul", "qamw_matmul_batch", "qamw_encode_stats",
     "qamw_normalised_pairs", "qamw_lloyd_workspace_bytes", "qamw_lloyd_device",
-    "qamw_search_grid_size", "qamw_search_grid_build", "qamw_encode_pruned", "qamw_calibrate_sigma_static", "qamw_decode_traffic_probe", "qamw_encode_batch",
+    "qamw_search_grid_size", "qamw_search_grid_build", "qamw_encode_pruned", "qamw_calibrate_sigma_static", "qamw_decode_traffic_probe", "qamw_encode_batch", "qamw_calibrate_sigma_batch",
 ]
 
 
@@ -34,6 +34,12 @@ class MatmulItem(C.Structure):
     _fields_ = [("X", C.c_void_p), ("ldx", C.c_int64), ("packed", C.c_void_p), ("row_norms", C.c_void_p),
                 ("chan_scale", C.c_void_p), ("signs", C.c_void_p), ("pair_sigma", C.c_void_p), ("Y", C.c_void_p),
                 ("ldy", C.c_int64), ("d_out", C.c_int32), ("d_in", C.c_int32)]
+
+
+class CalibrateItem(C.Structure):
+    """qamw_calibrate_item of include/qamw.h."""
+    _fields_ = [("W", C.c_void_p), ("ldw", C.c_int64), ("chan_scale", C.c_void_p), ("signs", C.c_void_p),
+                ("sigma_out", C.c_void_p), ("d_out", C.c_int32), ("d_in", C.c_int32)]
 
 
 class EncodeItem(C.Structure):
@@ -89,6 +95,7 @@ def lib() -> C.CDLL:
         L.qamw_decode_batch.argtypes = [C.POINTER(DecodeItem), i32, vp, i32, i32, vp]
         L.qamw_decode_traffic_probe.argtypes = [C.POINTER(DecodeItem), i32, vp, i32, i32, vp]
         L.qamw_encode_batch.argtypes = [C.POINTER(EncodeItem), i32, i32, vp, i32, i32, vp]
+        L.qamw_calibrate_sigma_batch.argtypes = [C.POINTER(CalibrateItem), i32, i32, i32, i32, vp, C.c_size_t, vp]
         L.qamw_set_kernel_path.argtypes = [i32]
         L.qamw_matmul_workspace_bytes.argtypes = [i32, i32, i32, C.POINTER(C.c_size_t)]
         L.qamw_matmul.argtypes = [vp, i32, i32, i64, vp, vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, C.c_size_t, vp, i64, vp]
@@ -491,3 +498,30 @@ def encode_batch(items, codebook, bits: int, block: int, stream=None):
     """Encode up to MAX_BATCH matrices (an EncodeItem array from make_encode_items) in one launch."""
     arr, _keep, code = items
     _check(lib().qamw_encode_batch(arr, len(arr), code, _ptr(codebook), bits, block, _stream(stream)), "qamw_encode_batch")
+
+
+def make_calibrate_items(entries, max_rows: int = 1024):
+    """Host descriptor array for calibrate_sigma_batch: each entry = (W, chan_scale, signs, sigma_out).
+    Returns (array, keepalive, dtype code, workspace bytes, max_rows)."""
+    arr = (CalibrateItem * len(entries))()
+    code, need = None, 0
+    for i, (W, s, sg, sigma) in enumerate(entries):
+        _require_cuda(W, s, sg, sigma)
+        if W.dim() != 2 or W.stride(1) != 1:
+            raise ValueError("W must be 2-D with unit column stride")
+        if code is None:
+            code = _dtype_code(W)
+        if _dtype_code(W) != code:
+            raise ValueError("all matrices of a batch share the element type")
+        arr[i] = CalibrateItem(W.data_ptr(), W.stride(0), None if s is None else s.data_ptr(), None if sg is None else sg.data_ptr(),
+                               sigma.data_ptr(), W.shape[0], W.shape[1])
+        need += (calibrate_workspace_bytes(W.shape[1], W.shape[0], max_rows) + 255) // 256 * 256
+    return arr, list(entries), code, need, max_rows
+
+
+def calibrate_sigma_batch(items, block: int, workspace, stream=None):
+    """Pair scales of up to MAX_BATCH matrices (a CalibrateItem array from make_calibrate_items) in two launches."""
+    arr, _keep, code, need, max_rows = items
+    _check(lib().qamw_calibrate_sigma_batch(arr, len(arr), code, block, max_rows, _ptr(workspace),
+                                            workspace.numel() * workspace.element_size(), _stream(stream)),
+           "qamw_calibrate_sigma_batch")

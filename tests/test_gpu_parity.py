@@ -705,6 +705,32 @@ def test_encode_batch_equals_single_calls(orc, codebooks, kernel_path, bits, blo
         say("   ", rep)
 
 
+@pytest.mark.parametrize("block,dtype,max_rows", [(128, "bf16", 1024), (256, "f32", 100), (32, "f32", 1024)])
+def test_calibrate_batch_equals_single_calls(orc, kernel_path, block, dtype, max_rows):
+    """Pair scales of several matrices from one pair of launches: bit for bit what the per-matrix entry point gives,
+    and the oracle's to 1e-6.  (block 32: a shape the fast kernels do not take -- the call falls back to single calls.)"""
+    say(f"[calibrate batch] b={block} {dtype} max_rows={max_rows} path={kernel_path}")
+    shapes = [(271, 1500, 4096), (272, 300, 11008), (273, 7, 1280), (274, 1027, 5632), (275, 1, 256), (276, 64, 13824)]
+    dummy = np.zeros((2, 2), np.float32)
+    cases = [Case(orc, sd, do, di, 1, block, dtype=dtype, sigma=None, codebook=dummy) for sd, do, di in shapes]
+    entries = [(cs.W_dev, cs.s_dev, cs.sg_dev, torch.full((cs.d_in // 2,), -1.0, device="cuda")) for cs in cases]
+    items = qamw.make_calibrate_items(entries, max_rows=max_rows)
+    ws = torch.empty(items[3], dtype=torch.uint8, device="cuda")
+    for again in range(2):                                     # the second call finds the first one's workspace contents
+        for e in entries:
+            e[3].fill_(-1.0)
+        qamw.calibrate_sigma_batch(items, block, ws)
+        torch.cuda.synchronize()
+        for cs, e in zip(cases, entries):
+            single = qamw.calibrate_sigma(cs.W_dev, block, chan_scale=cs.s_dev, signs=cs.sg_dev, max_rows=max_rows)
+            assert torch.equal(e[3], single)
+            want = orc.calibrate_sigma(cs.W, block, chan_scale=cs.s, signs=cs.sg, max_rows=max_rows)
+            assert np.allclose(e[3].cpu().numpy(), want, rtol=1e-6, atol=0)
+    with pytest.raises(qamw.QamwError) as ei:                  # a workspace one byte short of the sum
+        qamw.calibrate_sigma_batch(items, block, ws[:items[3] - 1])
+    assert ei.value.status == qamw.ERR_INVALID_ARG
+
+
 def test_calibrate_sigma_matches_oracle(orc, kernel_path):
     for seed, d_out, d_in, block, dtype in [(61, 1500, 512, 128, "f32"), (62, 300, 2048, 1024, "bf16"),
                                             (63, 64, 1280, 256, "f32"), (64, 10, 96, 2, "f32"), (65, 33, 5632, 512, "f32"),

@@ -173,6 +173,30 @@ def test_encode_batch_rejects_bad_arguments():
     assert L.qamw_encode_batch(arr, 2, 0, p, 11, 128, None) == qamw.ERR_SHAPE
 
 
+def test_calibrate_batch_rejects_bad_arguments():
+    L = qamw.lib()
+    p = C.c_void_p(0x1000)
+    arr = (qamw.CalibrateItem * 2)()
+    for i in range(2):
+        arr[i] = qamw.CalibrateItem(0x1000, 256, None, None, 0x2000, 8, 256)
+    big = 1 << 30
+    assert L.qamw_calibrate_sigma_batch(None, 2, 0, 128, 1024, p, big, None) == qamw.ERR_INVALID_ARG
+    assert L.qamw_calibrate_sigma_batch(arr, 0, 0, 128, 1024, p, big, None) == qamw.ERR_INVALID_ARG
+    assert L.qamw_calibrate_sigma_batch(arr, 17, 0, 128, 1024, p, big, None) == qamw.ERR_INVALID_ARG
+    assert L.qamw_calibrate_sigma_batch(arr, 2, 0, 128, 1024, None, big, None) == qamw.ERR_INVALID_ARG
+    assert L.qamw_calibrate_sigma_batch(arr, 2, 0, 128, 1024, C.c_void_p(0x1004), big, None) == qamw.ERR_INVALID_ARG
+    assert L.qamw_calibrate_sigma_batch(arr, 2, 3, 128, 1024, p, big, None) == qamw.ERR_INVALID_ARG      # element type
+    assert L.qamw_calibrate_sigma_batch(arr, 2, 0, 128, 0, p, big, None) == qamw.ERR_INVALID_ARG         # max_rows
+    assert L.qamw_calibrate_sigma_batch(arr, 2, 0, 96, 1024, p, big, None) == qamw.ERR_SHAPE
+    need = 2 * ((qamw.calibrate_workspace_bytes(256, 8, 1024) + 255) // 256 * 256)
+    assert L.qamw_calibrate_sigma_batch(arr, 2, 0, 128, 1024, p, need - 1, None) == qamw.ERR_INVALID_ARG   # workspace too small
+    arr[1].sigma_out = None
+    assert L.qamw_calibrate_sigma_batch(arr, 2, 0, 128, 1024, p, big, None) == qamw.ERR_INVALID_ARG
+    arr[1].sigma_out = 0x2000
+    arr[1].ldw = 10
+    assert L.qamw_calibrate_sigma_batch(arr, 2, 0, 128, 1024, p, big, None) == qamw.ERR_SHAPE
+
+
 def test_decode_batch_rejects_bad_arguments():
     L = qamw.lib()
     p = 0x1000
