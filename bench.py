@@ -73,17 +73,17 @@ def build_workload(wl, layers, device):
     return mats
 
 
-def run_step(layers, wl, cb, ws, timed):
+def run_step(layers, batches, wl, cb, ws, timed):
     """One pass: for every layer, pair-scale calibration of its matrices (qamw_calibrate_sigma_batch), their encode
-    (qamw_encode_batch), and after all layers the decode of every layer (qamw_decode_batch): three entry points per
-    layer, one launch (calibration: two) each.  Returns the event triples (before calibration, between, after encode)
+    (qamw_encode_batch), and after all layers the decode of the set (qamw_decode_batch, several layers per call): one
+    launch per call (calibration: two).  Returns the event triples (before calibration, between, after encode)
     per layer and the event pairs of each decode launch."""
     import torch
 
     from paper_2605_26339_amd import qamw
 
     ev_enc, ev_dec = [], []
-    for cal_items, enc_items, _ in layers:
+    for cal_items, enc_items in layers:
         e = [torch.cuda.Event(enable_timing=True) for _ in range(3)] if timed else None
         if timed:
             e[0].record()
@@ -94,7 +94,7 @@ def run_step(layers, wl, cb, ws, timed):
         if timed:
             e[2].record()
             ev_enc.append(e)
-    for _, _, dec_items in layers:
+    for dec_items in batches:
         e = [torch.cuda.Event(enable_timing=True) for _ in range(2)] if timed else None
         if timed:
             e[0].record()
@@ -145,22 +145,25 @@ def measure_workload(wl, layers, steps, warmup, decode_passes, dev, cb, valu_pat
     mats = build_workload(wl, layers, dev)
     per_layer = len(wl.matrices)
     by_layer = [mats[i:i + per_layer] for i in range(0, len(mats), per_layer)]
-    batches = [qamw.make_decode_items([(m["packed"], m["norms"], m["d_in"], m["s"], m["sg"], m["sigma"], m["out"]) for m in lm])
-               for lm in by_layer]
+    # decode: as many whole layers per qamw_decode_batch call as its item limit takes (4 layers of 7 matrices): a launch
+    # of one layer is ~100 us of HBM time, of which the ramp-up and the tail of the launch are a tenth
+    lpd = max(1, qamw.MAX_BATCH // per_layer)
+    batches = [qamw.make_decode_items([(m["packed"], m["norms"], m["d_in"], m["s"], m["sg"], m["sigma"], m["out"])
+                                       for lm in by_layer[i:i + lpd] for m in lm]) for i in range(0, len(by_layer), lpd)]
     layer_items = [(qamw.make_calibrate_items([(m["W"], m["s"], m["sg"], m["sigma"]) for m in lm]),
-                    qamw.make_encode_items([(m["W"], m["s"], m["sg"], m["sigma"], m["packed"], m["norms"]) for m in lm]), dec)
-                   for lm, dec in zip(by_layer, batches)]
+                    qamw.make_encode_items([(m["W"], m["s"], m["sg"], m["sigma"], m["packed"], m["norms"]) for m in lm]))
+                   for lm in by_layer]
     ws = torch.empty(max(li[0][3] for li in layer_items), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
     for _ in range(warmup):
-        run_step(layer_items, wl, cb, ws, timed=False)
+        run_step(layer_items, batches, wl, cb, ws, timed=False)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     start.record()
     all_enc, all_dec = [], []
     for _ in range(steps):
-        ev_enc, ev_dec = run_step(layer_items, wl, cb, ws, timed=True)
+        ev_enc, ev_dec = run_step(layer_items, batches, wl, cb, ws, timed=True)
         all_enc.extend(ev_enc)
         all_dec.extend(ev_dec)
     stop.record()
@@ -254,13 +257,13 @@ def measure_workload(wl, layers, steps, warmup, decode_passes, dev, cb, valu_pat
                      "matrix_core": {"instruction": "v_mfma_f32_32x32x16_bf16", "tflops": mfma_tf,
                                      "peak": PEAK_BF16_TFLOPS, "frac": mfma_tf / PEAK_BF16_TFLOPS},
                      "valu_only": valu},
-        "roofline_decode": {"kernel": "qamw_decode_batch (one launch per layer, %d matrices)" % per_layer, "bound": "hbm",
+        "roofline_decode": {"kernel": "qamw_decode_batch (one launch per %d layers, %d matrices)" % (lpd, lpd * per_layer), "bound": "hbm",
                             "achieved": dec_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS,
                             "ceiling_gb_per_s": ceiling_gbs, "ceiling_frac_of_peak": ceiling_gbs / PEAK_HBM_GBS,
                             "frac_of_ceiling": dec_gbs / ceiling_gbs,
                             "ceiling_source": "qamw_decode_traffic_probe in this run: the same launches with every load and "
                                               "store of the decoder and none of its arithmetic, median of 5 whole-set passes",
-                            "traffic": traffic and traffic["decode"] * per_layer,
+                            "traffic": traffic and traffic["decode"] * (len(mats) / len(batches)),
                             "traffic_source": traffic_source,
                             "avg_launch_ms": dec_ms / n_dec_launch,
                             "algorithmic_bytes_per_launch": dec_bytes / n_dec_launch},

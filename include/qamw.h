@@ -61,7 +61,7 @@ enum { QAMW_DTYPE_F32 = 0, QAMW_DTYPE_BF16 = 1 };
 
 enum { QAMW_MAX_BITS = 12, QAMW_MAX_BLOCK = 1024 };
 
-enum { QAMW_MAX_BATCH = 16 };   /* matrices per qamw_encode_batch / qamw_decode_batch call */
+enum { QAMW_MAX_BATCH = 32 };   /* matrices per qamw_calibrate_sigma_batch / qamw_encode_batch / qamw_decode_batch call */
 
 /* Text for a status code (static storage, never NULL). */
 const char *qamw_status_string(int status);

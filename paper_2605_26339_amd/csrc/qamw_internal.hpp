@@ -40,7 +40,7 @@ bool fast_calibrate_supported(const void *W, int dtype, int64_t ldw, const Probl
 hipError_t launch_calibrate_fast(const void *W, int dtype, int64_t ldw, int n_rows, const Problem &p, double *partial,
                                  float *sigma_out);
 // Several matrices in one pair of launches (every item checked with fast_calibrate_supported() by the caller).
-constexpr int CAL_MAX_BATCH = 16;
+constexpr int CAL_MAX_BATCH = 32;
 struct CalItem {
     const void *W;
     int64_t ldw;
@@ -53,7 +53,7 @@ struct CalItem {
 hipError_t launch_calibrate_batch_fast(const CalItem *items, int n, int dtype, int block, hipStream_t stream);
 
 // One matrix of a decode batch (host-side description).
-constexpr int QAMW_DECODE_MAX_BATCH = 16;
+constexpr int QAMW_DECODE_MAX_BATCH = 32;
 struct DecodeItem {
     const uint8_t *packed;
     const float *norms;
@@ -113,7 +113,7 @@ bool mfma_encode_supported(const Problem &p);
 hipError_t launch_encode_mfma(const void *W, int dtype, int64_t ldw, const Problem &p, float *norms, bool norms_ready,
                               uint8_t *packed);
 // One matrix of an encode batch (host-side description) and the batch launch of the matrix-core encoder.
-constexpr int QAMW_ENCODE_MAX_BATCH = 16;
+constexpr int QAMW_ENCODE_MAX_BATCH = 32;
 struct EncodeItem {
     const void *W;
     int64_t ldw;

@@ -26,7 +26,7 @@ EXPORTS = [
 ]
 
 
-MAX_BATCH = 16
+MAX_BATCH = 32
 
 
 class MatmulItem(C.Structure):

@@ -680,6 +680,40 @@ def test_decode_batch_equals_single_calls(orc, codebooks, kernel_path, sigma):
         check_decode(orc, cs, ref["idx"], ref["norms"].astype(np.float32), got_bf16=got)
 
 
+def test_batches_of_the_largest_size(orc, codebooks):
+    """MAX_BATCH matrices (small ones, mixed shapes) through calibrate / encode / decode batches: identical to single
+    calls, and the first and last matrices checked against the oracle."""
+    bits, block, n = 7, 128, qamw.MAX_BATCH
+    say(f"[largest batch] {n} matrices")
+    shapes = [(300 + i, 3 + (5 * i) % 23, [256, 1280, 2048, 1152][i % 4]) for i in range(n)]
+    cases = [Case(orc, sd, do, di, bits, block, dtype="bf16", sigma=None, codebook=codebooks[bits]) for sd, do, di in shapes]
+    cb_d = cases[0].cb_dev
+    sig = [torch.empty(cs.d_in // 2, device="cuda") for cs in cases]
+    cal = qamw.make_calibrate_items([(cs.W_dev, cs.s_dev, cs.sg_dev, sg) for cs, sg in zip(cases, sig)])
+    qamw.calibrate_sigma_batch(cal, block, torch.empty(cal[3], dtype=torch.uint8, device="cuda"))
+    pk = [torch.empty((cs.d_out, qamw.packed_row_bytes(cs.d_in, bits)), dtype=torch.uint8, device="cuda") for cs in cases]
+    nr = [torch.empty(cs.d_out, device="cuda") for cs in cases]
+    qamw.encode_batch(qamw.make_encode_items([(cs.W_dev, cs.s_dev, cs.sg_dev, sg, p_, n_) for cs, sg, p_, n_ in zip(cases, sig, pk, nr)]),
+                      cb_d, bits, block)
+    outs = [torch.empty((cs.d_out, cs.d_in), dtype=torch.bfloat16, device="cuda") for cs in cases]
+    qamw.decode_batch(qamw.make_decode_items([(p_, n_, cs.d_in, cs.s_dev, cs.sg_dev, sg, o) for cs, sg, p_, n_, o in zip(cases, sig, pk, nr, outs)]),
+                      cb_d, bits, block)
+    torch.cuda.synchronize()
+    for i, cs in enumerate(cases):
+        s1 = qamw.calibrate_sigma(cs.W_dev, block, chan_scale=cs.s_dev, signs=cs.sg_dev)
+        assert torch.equal(s1, sig[i])
+        p1, n1 = qamw.encode(cs.W_dev, cb_d, bits, block, chan_scale=cs.s_dev, signs=cs.sg_dev, pair_sigma=s1)
+        assert torch.equal(p1, pk[i]) and torch.equal(n1, nr[i])
+        o1 = qamw.decode(p1, n1, cs.d_in, cb_d, bits, block, chan_scale=cs.s_dev, signs=cs.sg_dev, pair_sigma=s1)
+        assert torch.equal(o1.view(torch.int16), outs[i].view(torch.int16))
+    for i in (0, n - 1):
+        cs = cases[i]
+        cs.sigma = sig[i].cpu().numpy()
+        check_encode(orc, cs, pk[i].cpu().numpy(), nr[i].cpu().numpy(), cs.oracle_encode(orc))
+        check_decode(orc, cs, orc.unpack(pk[i].cpu().numpy(), cs.d_in, bits), nr[i].cpu().numpy(),
+                     got_bf16=outs[i].cpu().view(torch.int16).numpy().view(np.uint16))
+
+
 @pytest.mark.parametrize("bits,block,dtype", [(11, 128, "bf16"), (7, 256, "f32"), (5, 64, "f32")])
 def test_encode_batch_equals_single_calls(orc, codebooks, kernel_path, bits, block, dtype):
     """One launch for several matrices of different shapes (ragged slabs, odd row counts, rows that straddle

@@ -158,7 +158,7 @@ def test_encode_batch_rejects_bad_arguments():
         arr[i] = qamw.EncodeItem(0x1000, 256, None, None, None, 0x2000, 0x3000, 8, 256)
     assert L.qamw_encode_batch(None, 2, 0, p, 11, 128, None) == qamw.ERR_INVALID_ARG
     assert L.qamw_encode_batch(arr, 0, 0, p, 11, 128, None) == qamw.ERR_INVALID_ARG
-    assert L.qamw_encode_batch(arr, 17, 0, p, 11, 128, None) == qamw.ERR_INVALID_ARG
+    assert L.qamw_encode_batch(arr, qamw.MAX_BATCH + 1, 0, p, 11, 128, None) == qamw.ERR_INVALID_ARG
     assert L.qamw_encode_batch(arr, 2, 0, None, 11, 128, None) == qamw.ERR_INVALID_ARG
     assert L.qamw_encode_batch(arr, 2, 5, p, 11, 128, None) == qamw.ERR_INVALID_ARG          # element type
     assert L.qamw_encode_batch(arr, 2, 0, p, 13, 128, None) == qamw.ERR_INVALID_ARG
@@ -182,7 +182,7 @@ def test_calibrate_batch_rejects_bad_arguments():
     big = 1 << 30
     assert L.qamw_calibrate_sigma_batch(None, 2, 0, 128, 1024, p, big, None) == qamw.ERR_INVALID_ARG
     assert L.qamw_calibrate_sigma_batch(arr, 0, 0, 128, 1024, p, big, None) == qamw.ERR_INVALID_ARG
-    assert L.qamw_calibrate_sigma_batch(arr, 17, 0, 128, 1024, p, big, None) == qamw.ERR_INVALID_ARG
+    assert L.qamw_calibrate_sigma_batch(arr, qamw.MAX_BATCH + 1, 0, 128, 1024, p, big, None) == qamw.ERR_INVALID_ARG
     assert L.qamw_calibrate_sigma_batch(arr, 2, 0, 128, 1024, None, big, None) == qamw.ERR_INVALID_ARG
     assert L.qamw_calibrate_sigma_batch(arr, 2, 0, 128, 1024, C.c_void_p(0x1004), big, None) == qamw.ERR_INVALID_ARG
     assert L.qamw_calibrate_sigma_batch(arr, 2, 3, 128, 1024, p, big, None) == qamw.ERR_INVALID_ARG      # element type
