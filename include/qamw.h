@@ -357,10 +357,13 @@ int qamw_decode_traffic_probe(const qamw_decode_item *items, int n_items, const 
  * bf16 (round to nearest even), products are exact, accumulation is fp32: what the paper's pipeline
  * (dequantise to bf16, then a bf16 matmul) does to its operands, in the rotated domain; the error is about
  * 2^-9 per operand.  This path also needs d_in a multiple of 256 and 8-byte aligned packed rows.
+ * m > QAMW_MATMUL_TILE_ROWS: the activation rows are processed in ceil(m / QAMW_MATMUL_TILE_ROWS) tiles of equal size
+ * (at most QAMW_MATMUL_TILE_ROWS rows), one rotation + product launch per tile on the stream, the packed matrix read
+ * once per tile; the workspace is that of one tile.  Row t of Y is the same whatever m is above the vector range.
  * Errors: m outside [1, QAMW_MATMUL_MAX_ROWS], NULL pointers, workspace too small or misaligned ->
  * INVALID_ARG; ldx < d_in, ldy < d_out -> SHAPE.  Shapes: bits in {7, 8, 11}, hadamard_block >= 64, d_in a
  * multiple of max(hadamard_block, 16), packed 4-byte aligned; anything else -> QAMW_ERR_UNSUPPORTED. */
-enum { QAMW_MATMUL_MAX_ROWS = 64, QAMW_MATMUL_VECTOR_ROWS = 8, QAMW_MATMUL_MAX_BATCH = 16 };
+enum { QAMW_MATMUL_MAX_ROWS = 4096, QAMW_MATMUL_TILE_ROWS = 64, QAMW_MATMUL_VECTOR_ROWS = 8, QAMW_MATMUL_MAX_BATCH = 16 };
 int qamw_matmul_workspace_bytes(int d_in, int d_out, int m, size_t *bytes_out);
 int qamw_matmul(const void *X, int x_dtype, int m, int64_t ldx, const uint8_t *packed, const float *row_norms,
                 int d_out, int d_in, const float *chan_scale, const int8_t *signs, const float *pair_sigma,

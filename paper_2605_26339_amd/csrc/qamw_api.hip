@@ -414,10 +414,18 @@ int qamw_decode_traffic_probe(const qamw_decode_item *items, int n_items, const 
     return decode_batch_impl(items, n_items, codebook, bits, hadamard_block, stream, true);
 }
 
+// More than QAMW_MATMUL_TILE_ROWS activation rows are processed in tiles of equal size (all above the vector kernel's
+// range, so every row of a product is computed by the same kernel): rows per tile.
+static int matmul_tile_rows(int m) {
+    if (m <= QAMW_MATMUL_TILE_ROWS) return m;
+    const int tiles = (m + QAMW_MATMUL_TILE_ROWS - 1) / QAMW_MATMUL_TILE_ROWS;
+    return (m + tiles - 1) / tiles;
+}
+
 int qamw_matmul_workspace_bytes(int d_in, int d_out, int m, size_t *bytes_out) {
     if (!bytes_out || d_out <= 0 || m < 1 || m > QAMW_MATMUL_MAX_ROWS) return QAMW_ERR_INVALID_ARG;
     if (d_in <= 0 || (d_in & 1)) return QAMW_ERR_SHAPE;
-    *bytes_out = qamw::matmul_workspace_bytes(d_in, d_out, m);
+    *bytes_out = qamw::matmul_workspace_bytes(d_in, d_out, matmul_tile_rows(m));
     return QAMW_OK;
 }
 
@@ -427,6 +435,7 @@ static int matmul_batch_impl(const qamw_matmul_item *items, int n_items, int x_d
     if (!items || !codebook || !workspace || n_items < 1 || n_items > QAMW_MATMUL_MAX_BATCH) return QAMW_ERR_INVALID_ARG;
     if (x_dtype != QAMW_DTYPE_F32 && x_dtype != QAMW_DTYPE_BF16) return QAMW_ERR_INVALID_ARG;
     if (m < 1 || m > QAMW_MATMUL_MAX_ROWS) return QAMW_ERR_INVALID_ARG;
+    const int tile = matmul_tile_rows(m);
     qamw::MatmulItem its[QAMW_MATMUL_MAX_BATCH];
     size_t need = 0;
     bool supported = true;
@@ -437,16 +446,28 @@ static int matmul_batch_impl(const qamw_matmul_item *items, int n_items, int x_d
         if (rc != QAMW_OK) return rc;
         if (q.ldx < q.d_in || q.ldy < q.d_out) return QAMW_ERR_SHAPE;
         qamw::Problem pi = make_problem(q.d_out, q.d_in, nullptr, nullptr, nullptr, codebook, bits, hadamard_block, stream);
-        if (!qamw::matmul_supported(pi, m) || (reinterpret_cast<uintptr_t>(q.packed) & 3)) supported = false;
-        need += qamw::matmul_workspace_bytes(q.d_in, q.d_out, m);
+        if (!qamw::matmul_supported(pi, tile) || (reinterpret_cast<uintptr_t>(q.packed) & 3)) supported = false;
+        need += qamw::matmul_workspace_bytes(q.d_in, q.d_out, tile);
         its[i] = qamw::MatmulItem{q.X, q.ldx, q.packed, q.row_norms, q.chan_scale, q.signs, q.pair_sigma, q.Y, q.ldy, q.d_out, q.d_in};
     }
     if (workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15)) return QAMW_ERR_INVALID_ARG;
     if (!supported) return QAMW_ERR_UNSUPPORTED;
     qamw::Problem p = make_problem(items[0].d_out, items[0].d_in, nullptr, nullptr, nullptr, codebook, bits, hadamard_block, stream);
-    hipError_t e = qamw::launch_matmul_batch(its, n_items, x_dtype, m, p, workspace, g_kernel_path.load());
-    if (e == hipErrorNotSupported) return QAMW_ERR_UNSUPPORTED;
-    return e == hipSuccess ? QAMW_OK : QAMW_ERR_DEVICE;
+    const size_t x_elem = x_dtype == QAMW_DTYPE_F32 ? sizeof(float) : sizeof(uint16_t);
+    // one launch pair per tile of activation rows; the tiles follow one another on the stream and share the workspace
+    for (int t0 = 0; t0 < m; t0 += tile) {
+        const int rows = m - t0 < tile ? m - t0 : tile;
+        if (t0 > 0) {
+            for (int i = 0; i < n_items; ++i) {
+                its[i].X = static_cast<const char *>(items[i].X) + (size_t)t0 * (size_t)items[i].ldx * x_elem;
+                its[i].Y = items[i].Y + (size_t)t0 * (size_t)items[i].ldy;
+            }
+        }
+        hipError_t e = qamw::launch_matmul_batch(its, n_items, x_dtype, rows, p, workspace, g_kernel_path.load());
+        if (e == hipErrorNotSupported) return QAMW_ERR_UNSUPPORTED;
+        if (e != hipSuccess) return QAMW_ERR_DEVICE;
+    }
+    return QAMW_OK;
 }
 
 int qamw_matmul_batch(const qamw_matmul_item *items, int n_items, int x_dtype, int m, const float *codebook, int bits,

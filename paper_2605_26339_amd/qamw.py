@@ -391,7 +391,8 @@ def decode(packed, row_norms, d_in: int, codebook, bits: int, block: int, chan_s
     return out
 
 
-MATMUL_MAX_ROWS = 64
+MATMUL_MAX_ROWS = 4096
+MATMUL_TILE_ROWS = 64
 MATMUL_VECTOR_ROWS = 8
 
 
@@ -403,8 +404,9 @@ def matmul_workspace_bytes(d_in: int, d_out: int, m: int) -> int:
 
 def matmul(X, packed, row_norms, codebook, bits: int, block: int, chan_scale=None, signs=None, pair_sigma=None,
            workspace=None, out=None, stream=None):
-    """Y = X W^T (fp32 [m][d_out]) for m <= 64 rows of X (fp32 or bf16 [m][d_in]) against the packed matrix.
-    Up to 8 rows: fp32 arithmetic throughout; more: bf16 operands on the matrix cores, fp32 accumulation."""
+    """Y = X W^T (fp32 [m][d_out]) for m <= 4096 rows of X (fp32 or bf16 [m][d_in]) against the packed matrix.
+    Up to 8 rows: fp32 arithmetic throughout; more: bf16 operands on the matrix cores, fp32 accumulation, in tiles of at
+    most 64 activation rows."""
     import torch
 
     _require_cuda(X, packed, row_norms, codebook, chan_scale, signs, pair_sigma)

@@ -469,6 +469,9 @@ GEMM_CASES = [
     (54, 130, 768, 8, 256, 64, "bf16"),       # 3 chunks
     (55, 96, 11008, 11, 128, 17, "plain"),    # no scales, signs or sigma; 43 chunks
     (56, 200, 8192, 7, 128, 50, "bf16"),      # 32 chunks, four row groups (the last of 8 rows), two token tiles
+    (57, 70, 2048, 11, 128, 128, "bf16"),     # more than 64 activation rows: two tiles of 64, one launch pair each
+    (58, 33, 1024, 7, 256, 65, "f32"),        # 65 rows: tiles of 33 and 32
+    (59, 40, 2304, 8, 256, 200, "bf16"),      # four tiles of 50
 ]
 
 

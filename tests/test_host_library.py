@@ -276,7 +276,7 @@ def test_matmul_rejects_bad_arguments():
     for k in ("X", "packed", "norms", "cb", "ws", "Y"):
         assert mm(**{k: None}) == qamw.ERR_INVALID_ARG
     assert mm(m=0) == qamw.ERR_INVALID_ARG
-    assert mm(m=65) == qamw.ERR_INVALID_ARG
+    assert mm(m=qamw.MATMUL_MAX_ROWS + 1) == qamw.ERR_INVALID_ARG
     assert mm(xd=5) == qamw.ERR_INVALID_ARG
     assert mm(bits=0) == qamw.ERR_INVALID_ARG
     assert mm(ws_bytes=need - 1) == qamw.ERR_INVALID_ARG
@@ -288,7 +288,11 @@ def test_matmul_rejects_bad_arguments():
     assert mm(d_in=64, ldx=64, block=32) == qamw.ERR_UNSUPPORTED
     assert mm(packed=C.c_void_p(0x1002)) == qamw.ERR_UNSUPPORTED
     out = C.c_size_t()
-    assert L.qamw_matmul_workspace_bytes(256, 8, 65, C.byref(out)) == qamw.ERR_INVALID_ARG
+    assert L.qamw_matmul_workspace_bytes(256, 8, qamw.MATMUL_MAX_ROWS + 1, C.byref(out)) == qamw.ERR_INVALID_ARG
+    # beyond 64 rows: the workspace of one tile (65 rows = tiles of 33 and 32; 200 rows = four tiles of 50), padded to 32
+    assert L.qamw_matmul_workspace_bytes(256, 8, 65, C.byref(out)) == qamw.OK and out.value == 64 * 256 * 2
+    assert L.qamw_matmul_workspace_bytes(256, 8, 200, C.byref(out)) == qamw.OK and out.value == 64 * 256 * 2
+    assert L.qamw_matmul_workspace_bytes(256, 8, 4096, C.byref(out)) == qamw.OK and out.value == 64 * 256 * 2
     assert L.qamw_matmul_workspace_bytes(256, 8, 9, C.byref(out)) == qamw.OK and out.value == 32 * 256 * 2   # bf16 rows, padded to 32
     assert L.qamw_matmul_workspace_bytes(256, 8, 33, C.byref(out)) == qamw.OK and out.value == 64 * 256 * 2
     assert L.qamw_matmul_workspace_bytes(255, 8, 1, C.byref(out)) == qamw.ERR_SHAPE
