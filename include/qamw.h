@@ -397,8 +397,10 @@ int qamw_matmul_batch(const qamw_matmul_item *items, int n_items, int x_dtype, i
  * 2 = the central cells in LDS whatever the size.  qamw_matmul / qamw_matmul_batch with one or two
  * activation rows: 0 = chosen by the size of the launch, 1 = activations rotated by a launch of their
  * own, 2 = rotated inside the product kernel; the results are the same, bit for bit.
- * Process-wide, for tests and measurements; returns the previous value (also for a value out of
- * range, which changes nothing). */
+ * This is the library's ONE piece of process-wide state: an atomic integer, safe to set from any thread, but it
+ * affects every call of every thread made afterwards -- a switch for tests and measurements, not for production code
+ * (all settings give the same results).  Returns the previous value (also for a value out of range, which changes
+ * nothing). */
 int qamw_set_kernel_path(int path);
 
 #ifdef __cplusplus
