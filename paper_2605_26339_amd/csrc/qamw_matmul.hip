@@ -39,6 +39,7 @@ constexpr int GV_RG = 8;                // rows per group: requested together, a
 constexpr int GV_STEPS_PER_WG = 16;     // target number of (slab, 8-row group) steps per workgroup: 4 per wave
 constexpr int GV_MIN_WGS = 256;         // a matrix is cut into at least this many workgroups when it has the rows
 constexpr int GV_MAX_ROWS_PER_WG = 64;
+constexpr int GV_AHEAD_MAX_WGS_2 = 512;        // two activation rows: launches of at most this many workgroups keep two steps' packed words in registers
 constexpr int GV_SELF_ROTATE_MAX_WGS = 1024;   // launches of at most this many workgroups (and one or two activation rows) skip k_rotate_x
 constexpr int GV_MAX_M = 8;                // activation rows of the vector-ALU kernel
 constexpr int GM_MAX_M = 64;               // ... of the matrix-core kernel (QAMW_MATMUL_MAX_ROWS of the public header)
@@ -95,31 +96,60 @@ __device__ __forceinline__ int64_t gm_z_offset(int tok, int col, int d_in) {
 // z = sigma (.) F S (x / s) of activation row tok for one 1024-column slab: lane l returns the 16 columns of sub-block
 // slab_pos(l) (the order of the register transform); all 64 lanes of the wave call it together.  Lanes past the end of
 // the row work on columns 0..15 (their blocks hold no lane that counts) and return values nobody uses.
-template <int XDTYPE, int B>
-__device__ __forceinline__ void gv_rotate_slab(float (&y)[16], const GemvBatch &bt, const GemvMat &M, int tok, int slab, int lane) {
-    const float *chan_scale = M.chan_scale, *pair_sigma = M.pair_sigma;
-    const int8_t *signs = M.signs;
-    const LaneSigns<B> ls(lane);
-    const int pos = slab_pos(lane);
-    const int col0 = slab * GV_SLAB + 16 * pos;
+// In two halves, so that a caller can have other memory requests on their way between the loads and the arithmetic.
+template <int MT> struct GvRotIn {          // what one lane loads: 16 values of each of MT activation rows and their columns' constants
+    float x[MT][16], scale[16], sigma[8];
+    int8_t sign[16];
+};
+// tok[t]: the activation row that goes into x[t]
+template <int XDTYPE, int MT>
+__device__ __forceinline__ void gv_rotate_load(GvRotIn<MT> &in, const GemvMat &M, const int (&tok)[MT], int slab, int lane) {
+    const int col0 = slab * GV_SLAB + 16 * slab_pos(lane);
     const int c = col0 < M.d_in ? col0 : 0;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) y[e] = Elem<XDTYPE>::load(M.X, (int64_t)tok * M.ldx + c + e);
-    if (chan_scale) {
+    for (int t = 0; t < MT; ++t)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) y[e] = y[e] * (1.0f / chan_scale[c + e]);    // times fl32(1/s_j), as the decoder does
+        for (int e = 0; e < 16; ++e) in.x[t][e] = Elem<XDTYPE>::load(M.X, (int64_t)tok[t] * M.ldx + c + e);
+    if (M.chan_scale) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) in.scale[e] = M.chan_scale[c + e];
     }
-    if (signs) {
+    if (M.signs) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) y[e] = (signs[c + e] < 0) ? -y[e] : y[e];
+        for (int e = 0; e < 16; ++e) in.sign[e] = M.signs[c + e];
+    }
+    if (M.pair_sigma) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) in.sigma[e] = M.pair_sigma[(c >> 1) + e];
+    }
+}
+template <int B, int MT>
+__device__ __forceinline__ void gv_rotate_compute(float (&y)[16], const GvRotIn<MT> &in, int t, const GemvBatch &bt, const GemvMat &M, int lane) {
+    const LaneSigns<B> ls(lane);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = in.x[t][e];
+    if (M.chan_scale) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) y[e] = y[e] * (1.0f / in.scale[e]);         // times fl32(1/s_j), as the decoder does
+    }
+    if (M.signs) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) y[e] = (in.sign[e] < 0) ? -y[e] : y[e];
     }
     fwht_wave<B>(y, ls);
     const float sigma_default = M.sigma_default;
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-        const float sg = pair_sigma ? pair_sigma[(c + e) >> 1] : sigma_default;
+        const float sg = M.pair_sigma ? in.sigma[e >> 1] : sigma_default;
         y[e] = ((y[e] * ls.parity) * bt.inv_sqrt_block) * sg;
     }
+}
+template <int XDTYPE, int B>
+__device__ __forceinline__ void gv_rotate_slab(float (&y)[16], const GemvBatch &bt, const GemvMat &M, int tok, int slab, int lane) {
+    GvRotIn<1> in;
+    const int toks[1] = {tok};
+    gv_rotate_load<XDTYPE, 1>(in, M, toks, slab, lane);
+    gv_rotate_compute<B, 1>(y, in, 0, bt, M, lane);
 }
 
 // z = sigma (.) F S (x / s) for every activation row: fp32, row-major [m][d_in], or bf16 in the order above.
@@ -221,13 +251,18 @@ template <int N> __device__ __forceinline__ void gv_reduce_rows(float (&a)[N], i
 // before).  RB > 0 (the block size): every wave rotates the slabs it needs itself, with the same arithmetic, and moves
 // the result from the transform's lane order to the natural one -- the same z in the same lanes, so the same Y, bit for
 // bit, without the first launch; for launches so small that a second launch costs more than the repeated rotations.
-template <int BITS, int MT, int RB>
-__global__ __launch_bounds__(GV_THREADS) void k_qgemv(GemvBatch bt) {
+// AHEAD (self-rotating kernels only): the wave keeps two steps' packed words in registers; one activation row fits
+// three waves per SIMD (768 resident workgroups, which covers the launches that rotate for themselves), two rows fit
+// two (512 workgroups: the host picks the plain form for larger two-row launches).
+#define QAMW_GV_WAVES_PER_EU (AHEAD ? (MT == 1 ? 3 : 2) : 1)
+template <int BITS, int MT, int RB, int AHEAD>
+__global__ __launch_bounds__(GV_THREADS) __attribute__((amdgpu_waves_per_eu(QAMW_GV_WAVES_PER_EU)))
+void k_qgemv(GemvBatch bt) {
     constexpr int RG = MT == 8 ? 4 : GV_RG, UR = GV_MAX_ROWS_PER_WG;
-    extern __shared__ __align__(16) float gv_lds[];
+    // statically sized, so that a codeword's address is its index times 8 with nothing to add (bt.K == 2^BITS)
+    __shared__ float2 cb_lds[1 << BITS];                        // the codewords
+    __shared__ float red[GV_WAVES * UR * MT];                   // [waves][UR rows][MT]
     typedef gv_u32x4_t u32x4_a4_t __attribute__((aligned(4)));
-    float2 *cb_lds = reinterpret_cast<float2 *>(gv_lds);        // K codewords
-    float *red = gv_lds + 2 * bt.K;                             // [waves][UR rows][MT]
     const int lane = threadIdx.x & (WAVE - 1);
     const int wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform over the wave: keeps the step bookkeeping scalar
 
@@ -277,32 +312,50 @@ __global__ __launch_bounds__(GV_THREADS) void k_qgemv(GemvBatch bt) {
         for (int l = 0; l < 16; ++l) z_from = (slab_pos(l) == (lane & 15)) ? l : z_from;
         z_from = ((lane & ~15) | z_from) << 2;
     }
-    auto load_z = [&](int slab, float (&z)[MT][16]) {           // the slab's rotated activations, zero for missing rows of X and idle lanes
+    // The slab's rotated activations, zero for missing rows of X and idle lanes: the self-rotating kernels load the
+    // inputs (rot_load) and rotate (rot_finish) in two steps, the others read the rotation kernel's output.
+    auto rot_load = [&](int slab, GvRotIn<MT> &in) {
+        int toks[MT];
+#pragma unroll
+        for (int t = 0; t < MT; ++t) toks[t] = t < m ? t : 0;
+        if (bt.xdtype == 0) gv_rotate_load<0, MT>(in, M, toks, slab, lane);
+        else gv_rotate_load<1, MT>(in, M, toks, slab, lane);
+    };
+    auto rot_finish = [&](int slab, const GvRotIn<MT> &in, float (&z)[MT][16]) {
         const bool active = slab * GV_SLAB + 16 * lane < d_in;
-        const int c = lane_col(slab);
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
             const bool have = active && t < m;
-            if (RB > 0) {
-                float y[16];
-                constexpr int B = RB > 0 ? RB : 64;
-                if (bt.xdtype == 0) gv_rotate_slab<0, B>(y, bt, M, t < m ? t : 0, slab, lane);
-                else gv_rotate_slab<1, B>(y, bt, M, t < m ? t : 0, slab, lane);
+            float y[16];
+            constexpr int B = RB > 0 ? RB : 64;
+            gv_rotate_compute<B, MT>(y, in, t, bt, M, lane);
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const float v = __int_as_float(__builtin_amdgcn_ds_bpermute(z_from, __float_as_int(y[e])));
-                    z[t][e] = have ? v : 0.0f;
-                }
-                continue;
+            for (int e = 0; e < 16; ++e) {
+                const float v = __int_as_float(__builtin_amdgcn_ds_bpermute(z_from, __float_as_int(y[e])));
+                z[t][e] = have ? v : 0.0f;
             }
-            const float4 *src = reinterpret_cast<const float4 *>(Z + (int64_t)(t < m ? t : 0) * d_in + c);
+        }
+    };
+    auto load_z = [&](int slab, float (&z)[MT][16]) {
+        if constexpr (RB > 0) {
+            GvRotIn<MT> in;
+            rot_load(slab, in);
+            rot_finish(slab, in, z);
+        } else {
+            const bool active = slab * GV_SLAB + 16 * lane < d_in;
+            const int c = lane_col(slab);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 v = src[q];
-                z[t][4 * q] = have ? v.x : 0.0f;
-                z[t][4 * q + 1] = have ? v.y : 0.0f;
-                z[t][4 * q + 2] = have ? v.z : 0.0f;
-                z[t][4 * q + 3] = have ? v.w : 0.0f;
+            for (int t = 0; t < MT; ++t) {
+                const bool have = active && t < m;
+                const float4 *src = reinterpret_cast<const float4 *>(Z + (int64_t)(t < m ? t : 0) * d_in + c);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 v = src[q];
+                    z[t][4 * q] = have ? v.x : 0.0f;
+                    z[t][4 * q + 1] = have ? v.y : 0.0f;
+                    z[t][4 * q + 2] = have ? v.z : 0.0f;
+                    z[t][4 * q + 3] = have ? v.w : 0.0f;
+                }
             }
         }
     };
@@ -314,39 +367,13 @@ __global__ __launch_bounds__(GV_THREADS) void k_qgemv(GemvBatch bt) {
     const int step0 = wid * per_wave, step1 = min(n_steps, step0 + per_wave);
     float z[MT][16];
     int cur_slab = step0 < step1 ? step0 / n_g : -1;
-    if (cur_slab >= 0) load_z(cur_slab, z);                     // on its way while the codebook is staged
-    // For more than one activation row the codebook goes from memory straight into LDS: wave w copies the 1 KB
-    // pieces w, w + 4, ..., lane l the 16 bytes l of a piece (the instruction places lane l's bytes at base + 16 l);
-    // measured 6 % faster at m = 4, 1-3 % slower at m = 1, where it goes through registers.
-    if (MT > 1) {
-        const char *src = reinterpret_cast<const char *>(bt.codebook);
-        const int bytes = bt.K * (int)sizeof(float2);
-        for (int off = wid * 1024; off < bytes; off += GV_WAVES * 1024) {
-            if (off + 16 * lane < bytes)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + off + 16 * lane),
-                                                 (__attribute__((address_space(3))) void *)(reinterpret_cast<char *>(cb_lds) + off),
-                                                 16, 0, 0);
-        }
-        __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0): this wave's pieces have landed before the barrier
-    } else {
-        const float2 *cbk = reinterpret_cast<const float2 *>(bt.codebook);
-        for (int i = threadIdx.x; i < bt.K; i += GV_THREADS) cb_lds[i] = cbk[i];
-    }
-    __syncthreads();
-
-    // this wave's running row totals live in its own part of LDS (only this wave touches it until the barrier)
-    for (int i = lane; i < UR * MT; i += WAVE) red[wid * UR * MT + i] = 0.0f;
     const int my_row = gv_lane_row<RG>(lane);                   // after the reduction: which of the group's rows this lane holds
-#pragma unroll 1
-    for (int step = step0; step < step1; ++step) {
+    float *my_red = red + wid * UR * MT;                        // this wave's running row totals (only this wave touches them until the last barrier)
+
+    // one step: the group's 8 x 64 x 8 codeword gathers and multiply-adds, the totals over the lanes, into my_red
+    auto work = [&](int step, const uint32_t (&d)[RG][4]) {
         const int slab = step / n_g, g = step - slab * n_g;
-        if (slab != cur_slab) {
-            load_z(slab, z);
-            cur_slab = slab;
-        }
         const int sh = (int)(((unsigned)(lane_col(slab) >> 4) * BITS) & 3u) * 8;
-        uint32_t d[RG][4];
-        fetch(slab, g, d);
         float acc[MT][RG];
 #pragma unroll
         for (int t = 0; t < MT; ++t)
@@ -373,7 +400,87 @@ __global__ __launch_bounds__(GV_THREADS) void k_qgemv(GemvBatch bt) {
         for (int t = 0; t < MT; ++t) gv_reduce_rows<RG>(acc[t], lane);
         if ((lane & (WAVE / RG - 1)) == 0) {
 #pragma unroll
-            for (int t = 0; t < MT; ++t) red[(wid * UR + g * RG + my_row) * MT + t] += acc[t][0];
+            for (int t = 0; t < MT; ++t) my_red[(g * RG + my_row) * MT + t] += acc[t][0];
+        }
+    };
+    auto fetch_step = [&](int step, uint32_t (&d)[RG][4]) {
+        const int slab = step / n_g;
+        fetch(slab, step - slab * n_g, d);
+    };
+
+    static_assert(!AHEAD || RB > 0, "only the self-rotating kernels run ahead");
+    if constexpr (!AHEAD) {
+        if (cur_slab >= 0) load_z(cur_slab, z);                 // on its way while the codebook is staged
+        // For more than one activation row the codebook goes from memory straight into LDS: wave w copies the 1 KB
+        // pieces w, w + 4, ..., lane l the 16 bytes l of a piece (the instruction places lane l's bytes at base + 16 l);
+        // measured 6 % faster at m = 4, 1-3 % slower at m = 1, where it goes through registers.
+        if (MT > 1) {
+            const char *src = reinterpret_cast<const char *>(bt.codebook);
+            const int bytes = bt.K * (int)sizeof(float2);
+            for (int off = wid * 1024; off < bytes; off += GV_WAVES * 1024) {
+                if (off + 16 * lane < bytes)
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + off + 16 * lane),
+                                                     (__attribute__((address_space(3))) void *)(reinterpret_cast<char *>(cb_lds) + off),
+                                                     16, 0, 0);
+            }
+            __builtin_amdgcn_s_waitcnt(0x0F70);                // vmcnt(0): this wave's pieces have landed before the barrier
+        } else {
+            const float2 *cbk = reinterpret_cast<const float2 *>(bt.codebook);
+            for (int i = threadIdx.x; i < bt.K; i += GV_THREADS) cb_lds[i] = cbk[i];
+        }
+        for (int i = lane; i < UR * MT; i += WAVE) my_red[i] = 0.0f;
+        __syncthreads();
+#pragma unroll 1
+        for (int step = step0; step < step1; ++step) {
+            const int slab = step / n_g;
+            if (slab != cur_slab) {
+                load_z(slab, z);
+                cur_slab = slab;
+            }
+            uint32_t d[RG][4];
+            fetch_step(step, d);
+            work(step, d);
+        }
+    } else {
+        // A launch that rotates the activations itself is a small one -- one to three waves per SIMD, two to four steps
+        // per wave -- and lasts as long as one wave's chain of memory round trips.  So the chain is kept short: the
+        // rotation's inputs, the workgroup's share of the codebook and the packed words of the wave's first two steps
+        // are requested before anything is waited for (the rotation's first: it has arithmetic to do while the rest
+        // arrives), and from then on the next step's packed words are on their way while a step is worked on.
+        // bt.K == 2^BITS here.
+        constexpr int KC = 1 << BITS, CB_PER_THREAD = (KC + GV_THREADS - 1) / GV_THREADS;
+        GvRotIn<MT> rin;
+        rot_load(cur_slab >= 0 ? cur_slab : 0, rin);
+        float2 cbv[CB_PER_THREAD];
+        const float2 *cbk = reinterpret_cast<const float2 *>(bt.codebook);
+#pragma unroll
+        for (int j = 0; j < CB_PER_THREAD; ++j) cbv[j] = cbk[min((int)threadIdx.x + j * GV_THREADS, KC - 1)];
+        uint32_t da[RG][4], db[RG][4];
+        if (step0 < step1) fetch_step(step0, da);
+        if (step0 + 1 < step1) fetch_step(step0 + 1, db);
+        if (cur_slab >= 0) rot_finish(cur_slab, rin, z);
+#pragma unroll
+        for (int j = 0; j < CB_PER_THREAD; ++j)
+            if ((int)threadIdx.x + j * GV_THREADS < KC) cb_lds[threadIdx.x + j * GV_THREADS] = cbv[j];
+        for (int i = lane; i < UR * MT; i += WAVE) my_red[i] = 0.0f;
+        __syncthreads();
+        auto keep_z = [&](int step) {
+            const int slab = step / n_g;
+            if (slab != cur_slab) {
+                load_z(slab, z);
+                cur_slab = slab;
+            }
+        };
+#pragma unroll 1
+        for (int step = step0; step < step1; step += 2) {
+            keep_z(step);
+            work(step, da);
+            if (step + 2 < step1) fetch_step(step + 2, da);
+            if (step + 1 < step1) {
+                keep_z(step + 1);
+                work(step + 1, db);
+                if (step + 3 < step1) fetch_step(step + 3, db);
+            }
         }
     }
     __syncthreads();
@@ -587,14 +694,18 @@ static hipError_t launch_rotate(const GemvBatch &bt, int block, hipStream_t stre
 template <int BITS, int RB>
 static hipError_t launch_qgemv_rb(const GemvBatch &bt, hipStream_t stream) {
     const unsigned blocks = (unsigned)bt.grp_begin[bt.n];
-#define QAMW_GV(MM)                                                                                                  \
-    hipLaunchKernelGGL((k_qgemv<BITS, MM, RB>), dim3(blocks), dim3(GV_THREADS),                                        \
-                       ((size_t)bt.K * 2 + (size_t)GV_WAVES * GV_MAX_ROWS_PER_WG * MM) * sizeof(float), stream, bt)
-    if (bt.m == 1) QAMW_GV(1);
-    else if (bt.m == 2) QAMW_GV(2);
-    else if constexpr (RB > 0) return hipErrorNotSupported;     // the self-rotating kernels exist for one and two rows
-    else if (bt.m <= 4) QAMW_GV(4);
-    else QAMW_GV(8);
+#define QAMW_GV(MM, AH) hipLaunchKernelGGL((k_qgemv<BITS, MM, RB, AH>), dim3(blocks), dim3(GV_THREADS), 0, stream, bt)
+    if constexpr (RB > 0) {                                     // the self-rotating kernels exist for one and two rows
+        if (bt.m == 1) QAMW_GV(1, 1);
+        else if (bt.m == 2 && blocks <= GV_AHEAD_MAX_WGS_2) QAMW_GV(2, 1);
+        else if (bt.m == 2) QAMW_GV(2, 0);
+        else return hipErrorNotSupported;
+    } else {
+        if (bt.m == 1) QAMW_GV(1, 0);
+        else if (bt.m == 2) QAMW_GV(2, 0);
+        else if (bt.m <= 4) QAMW_GV(4, 0);
+        else QAMW_GV(8, 0);
+    }
 #undef QAMW_GV
     return hipGetLastError();
 }
@@ -629,7 +740,7 @@ static hipError_t launch_qgemm(const GemvBatch &bt, hipStream_t stream) {
 // Returns hipErrorNotSupported (nothing launched) outside the supported shapes.  variant: 0, or 1 / 2 to force the
 // two-launch / the self-rotating form of the vector kernel.
 hipError_t launch_matmul_batch(const MatmulItem *items, int n, int xdtype, int m, const Problem &p, void *workspace, int variant) {
-    if (n < 1 || n > QAMW_MATMUL_MAX_BATCH) return hipErrorNotSupported;
+    if (n < 1 || n > QAMW_MATMUL_MAX_BATCH || p.K != (1 << p.bits)) return hipErrorNotSupported;   // the kernels size the codebook from the bit width
     GemvBatch bt;
     int64_t rot = 0, groups = 0;
     char *ws = static_cast<char *>(workspace);

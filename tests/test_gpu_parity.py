@@ -582,6 +582,40 @@ def test_fused_matmul_random_shapes(codebooks):
                 assert torch.equal(Yp, Y), f"kernel path {path}"
 
 
+@pytest.mark.parametrize("m,d_out", [(1, 40), (2, 40), (1, 4200), (2, 4200)])
+def test_fused_matmul_self_rotating_forms(codebooks, m, d_out):
+    """One and two activation rows against an 11-slab matrix (every wave of a workgroup walks two or three slabs), as a
+    small launch (the product kernel rotates the activations itself and keeps two steps' packed words in flight) and as one
+    of 525 workgroups (with two rows: the self-rotating kernel without the second buffer).  The product against X times
+    the decoder's fp32 output in fp64, and bit-identical whichever way the activations were rotated."""
+    say(f"[matmul self-rotating] m={m} d_out={d_out}")
+    bits, block, d_in = 11, 128, 11008
+    g = torch.Generator("cuda").manual_seed(7000 + m + d_out)
+    cb = torch.from_numpy(np.asarray(codebooks[bits], dtype=np.float32)).cuda()
+    pk = torch.randint(0, 256, (d_out, qamw.packed_row_bytes(d_in, bits)), dtype=torch.uint8, device="cuda", generator=g)
+    nr = torch.rand(d_out, device="cuda", generator=g) + 0.5
+    s = torch.exp(0.5 * torch.randn(d_in, device="cuda", generator=g))
+    sg = (torch.randint(0, 2, (d_in,), device="cuda", generator=g) * 2 - 1).to(torch.int8)
+    sigma = (torch.rand(d_in // 2, device="cuda", generator=g) + 0.5) / np.sqrt(d_in)
+    X = torch.randn((m, d_in), device="cuda", generator=g).to(torch.bfloat16)
+    W = qamw.decode(pk, nr, d_in, cb, bits, block, chan_scale=s, signs=sg, pair_sigma=sigma, f32=True).double()
+    Yref = X.double() @ W.t()
+    Y = qamw.matmul(X, pk, nr, cb, bits, block, chan_scale=s, signs=sg, pair_sigma=sigma)
+    torch.cuda.synchronize()
+    bar = 1e-5 * X.double().norm(dim=1)[:, None] * W.norm(dim=1)[None, :] + 1e-30
+    worst = float(((Y.double() - Yref).abs() / bar).max())
+    say(f"    worst error / bar = {worst:.3f}")
+    assert worst <= 1.0
+    for path in (1, 2):
+        prev = qamw.set_kernel_path(path)
+        try:
+            Yp = qamw.matmul(X, pk, nr, cb, bits, block, chan_scale=s, signs=sg, pair_sigma=sigma)
+            torch.cuda.synchronize()
+        finally:
+            qamw.set_kernel_path(prev)
+        assert torch.equal(Yp, Y), f"kernel path {path}"
+
+
 @pytest.mark.parametrize("m", [1, 3, 20])
 def test_fused_matmul_batch_equals_single_calls(orc, codebooks, m):
     """Several independent products in one call give, bit for bit, what one call per matrix gives (vector kernel
