@@ -44,6 +44,7 @@ constexpr int GV_SELF_ROTATE_MAX_WGS = 1024;   // launches of at most this many 
 constexpr int GV_MAX_M = 8;                // activation rows of the vector-ALU kernel
 constexpr int GM_MAX_M = 64;               // ... of the matrix-core kernel (QAMW_MATMUL_MAX_ROWS of the public header)
 constexpr int GM_ROWS = 32;                // weight rows of a workgroup: one tile of the matrix instruction
+constexpr int GM_HALF_TILE_MAX_WGS = 256;  // launches that would make at most this many 32-row workgroups use 16-row ones
 constexpr int GM_WAVES = 8;                // waves of a workgroup: each takes every eighth chunk of the rows
 constexpr int GM_THREADS = GM_WAVES * WAVE;
 constexpr int GM_CHUNK = 256;              // columns of one step of a wave: 2 halves x 16 instructions x 8 columns
@@ -76,6 +77,7 @@ struct GemvBatch {
     int n, m, K;
     int xdtype;                            // element type of X: 0 fp32, 1 bf16
     int z_bf16;                            // 1: k_rotate_x writes bf16 rows, padded with zero rows to a multiple of 32 (matrix-core kernel)
+    int gm_rows;                           // matrix-core kernel: weight rows per workgroup, 32 (a whole tile) or 16 (its upper half unused)
     float inv_sqrt_block;
     const float *codebook;
 };
@@ -536,7 +538,11 @@ void k_qgemm(GemvBatch bt) {
     const int grp = blockIdx.x;
     const int mi = gv_find(bt.grp_begin, bt.n, grp);
     const GemvMat &M = bt.mat[mi];
-    const int row0 = (grp - bt.grp_begin[mi]) * GM_ROWS;
+    // rows of the tile this workgroup fills: all 32, or the first 16 (a launch of few workgroups is cut finer so that it
+    // covers the chip; a row's sum is the same chunks in the same waves in the same order either way, bit for bit)
+    const int rows = bt.gm_rows;
+    const bool row_used = r < rows;
+    const int row0 = (grp - bt.grp_begin[mi]) * rows;
     const int d_in = M.d_in, last_row = M.d_out - 1, m = bt.m;
     const int64_t row_bytes = M.row_bytes;
     const uint16_t *Zb = reinterpret_cast<const uint16_t *>(M.Z);
@@ -555,9 +561,10 @@ void k_qgemm(GemvBatch bt) {
     // The chunk's packed bytes of the workgroup's 32 rows -- BITS 16-byte pieces per row -- are loaded with consecutive
     // lanes on consecutive pieces (piece 64 i + lane of the row-major 32 x BITS array) and laid down in LDS row by row.
     // Rows past the end of the matrix re-read the last row (their results are not stored); the pieces past the tile's
-    // last row (32 BITS is not always a multiple of 64) are loaded from valid addresses and not written to LDS.
+    // last row (rows x BITS is not always a multiple of 64) are neither loaded nor written to LDS.
     // (the offsets are recomputed where they are used: the vector ALU is idle here and the registers are not)
-    constexpr int TILE_PIECES = GM_ROWS * BITS, PIECES = (TILE_PIECES + 63) / 64;
+    constexpr int PIECES = (GM_ROWS * BITS + 63) / 64;
+    const int tile_pieces = rows * BITS;
     auto src_off = [&](int i) {
         const int piece = 64 * i + lane, row = piece / BITS, c16 = piece - row * BITS;
         return min(row0 + row, last_row) * (int)row_bytes + 16 * c16;
@@ -580,23 +587,26 @@ void k_qgemm(GemvBatch bt) {
     // The packed bytes of the wave's next chunk are requested before the current chunk's matrix instructions start.
     typedef gv_u32x4_t u32x4_a4_t __attribute__((aligned(4)));
     gv_u32x4_t v[PIECES];
+#pragma unroll
+    for (int i = 0; i < PIECES; ++i) v[i] = gv_u32x4_t{0u, 0u, 0u, 0u};
     if (wid < n_chunks) {
         const uint8_t *src = M.packed + (int64_t)wid * (16 * BITS);
 #pragma unroll
-        for (int i = 0; i < PIECES; ++i) v[i] = *reinterpret_cast<const u32x4_a4_t *>(src + src_off(i));
+        for (int i = 0; i < PIECES; ++i)
+            if (64 * i + lane < tile_pieces) v[i] = *reinterpret_cast<const u32x4_a4_t *>(src + src_off(i));
     }
 #pragma unroll 1
     for (int ch = wid; ch < n_chunks; ch += GM_WAVES) {
         // the chunk's packed bytes go through LDS: written piece by piece, read back as the lane's stream of 64 pairs
 #pragma unroll
         for (int i = 0; i < PIECES; ++i) {
-            if (TILE_PIECES % 64 != 0 && 64 * i + lane >= TILE_PIECES) continue;
+            if (64 * i + lane >= tile_pieces) continue;
             gv_u32x2_t *dst = reinterpret_cast<gv_u32x2_t *>(tile + dst_off(i));
             dst[0] = gv_u32x2_t{v[i][0], v[i][1]};
             dst[1] = gv_u32x2_t{v[i][2], v[i][3]};
         }
         uint32_t w[2 * BITS];
-        {
+        if (row_used) {
             const gv_u32x2_t *src = reinterpret_cast<const gv_u32x2_t *>(tile + r * PITCH + 8 * BITS * h);
 #pragma unroll
             for (int q = 0; q < BITS; ++q) {
@@ -621,15 +631,18 @@ void k_qgemm(GemvBatch bt) {
         if (ch + GM_WAVES < n_chunks) {                         // the next chunk's packed bytes
             const uint8_t *src = M.packed + (int64_t)(ch + GM_WAVES) * (16 * BITS);
 #pragma unroll
-            for (int i = 0; i < PIECES; ++i) v[i] = *reinterpret_cast<const u32x4_a4_t *>(src + src_off(i));
+            for (int i = 0; i < PIECES; ++i)
+                if (64 * i + lane < tile_pieces) v[i] = *reinterpret_cast<const u32x4_a4_t *>(src + src_off(i));
         }
 #pragma unroll
         for (int step = 0; step < 16; ++step) {                 // instruction of the chunk: pairs 4 step .. 4 step + 3 of the lane's 64
             if (step > 0 && step % ZB == 0) load_zb(step);
-            gv_u32x4_t a;
+            gv_u32x4_t a = {0u, 0u, 0u, 0u};                    // the unused half of a 16-row workgroup's tile: zeros, no gathers
+            if (row_used) {
 #pragma unroll
-            for (int f = 0; f < 4; ++f)
-                a[f] = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(cbh) + gm_field_x4<BITS>(w, 4 * step + f));
+                for (int f = 0; f < 4; ++f)
+                    a[f] = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(cbh) + gm_field_x4<BITS>(w, 4 * step + f));
+            }
             const gv_bf16x8_t av = __builtin_bit_cast(gv_bf16x8_t, a);
 #pragma unroll
             for (int t = 0; t < MT; ++t)
@@ -656,8 +669,9 @@ void k_qgemm(GemvBatch bt) {
                 float s = acc[t][i];
 #pragma unroll
                 for (int w2 = 0; w2 < GM_WAVES - 1; ++w2) s += red[(size_t)w2 * (MT * 16 * WAVE) + (t * 16 + i) * WAVE + lane];
-                const int row = row0 + 8 * (i >> 2) + 4 * h + (i & 3);   // accumulator i of half h: tile row 8 (i / 4) + 4 h + i % 4
-                if (tok < m && row <= last_row) M.Y[(int64_t)tok * M.ldy + row] = M.norms[row] * s;
+                const int tile_row = 8 * (i >> 2) + 4 * h + (i & 3);    // accumulator i of half h
+                const int row = row0 + tile_row;
+                if (tok < m && tile_row < rows && row <= last_row) M.Y[(int64_t)tok * M.ldy + row] = M.norms[row] * s;
             }
         }
     }
@@ -751,6 +765,12 @@ hipError_t launch_matmul_batch(const MatmulItem *items, int n, int xdtype, int m
     for (int i = 0; i < n; ++i) order[i] = i;
     if (m > GV_MAX_M)
         std::stable_sort(order, order + n, [&](int a, int b) { return items[a].d_in > items[b].d_in; });
+    // Matrix-core kernel: a launch whose matrices make at most GM_HALF_TILE_MAX_WGS workgroups of 32 rows (one 4096-row
+    // projection makes 128) is cut into workgroups of 16 rows, so that it reaches every CU; a row's result does not
+    // depend on the cut.
+    int64_t tiles32 = 0;
+    for (int i = 0; i < n; ++i) tiles32 += (items[i].d_out + GM_ROWS - 1) / GM_ROWS;
+    bt.gm_rows = tiles32 <= GM_HALF_TILE_MAX_WGS ? GM_ROWS / 2 : GM_ROWS;
     for (int i = 0; i < n; ++i) {
         const MatmulItem &it = items[order[i]];
         Problem q = p;
@@ -782,9 +802,9 @@ hipError_t launch_matmul_batch(const MatmulItem *items, int n, int xdtype, int m
         if (groups_per_wg > GV_MAX_ROWS_PER_WG / GV_RG) groups_per_wg = GV_MAX_ROWS_PER_WG / GV_RG;
         while (groups_per_wg > 1 && (M.d_out + groups_per_wg * GV_RG - 1) / (groups_per_wg * GV_RG) < GV_MIN_WGS) groups_per_wg >>= 1;
         M.rows_per_wg = groups_per_wg * GV_RG;
-        if (m > GV_MAX_M) {                                     // matrix-core kernel: one 32-row tile per workgroup
+        if (m > GV_MAX_M) {                                     // matrix-core kernel: one tile, or half of one, per workgroup
             if ((int64_t)M.d_out * M.row_bytes > 0x7fffffff) return hipErrorNotSupported;   // 32-bit byte offsets into the packed matrix
-            M.rows_per_wg = GM_ROWS;
+            M.rows_per_wg = bt.gm_rows;
         }
         bt.rot_begin[i] = (int)rot;
         bt.grp_begin[i] = (int)groups;

@@ -616,6 +616,33 @@ def test_fused_matmul_self_rotating_forms(codebooks, m, d_out):
         assert torch.equal(Yp, Y), f"kernel path {path}"
 
 
+@pytest.mark.parametrize("bits,m", [(11, 20), (7, 40)])
+def test_fused_matmul_tile_height_does_not_change_bits(codebooks, bits, m):
+    """The matrix-core kernel gives a workgroup 32 weight rows, or 16 when the launch would otherwise make at most 256
+    workgroups.  A matrix of 8232 rows (258 workgroups of 32) in one call, and its two halves of 4116 rows (129 + 129
+    workgroups of 32, so each call is cut into 16-row ones; 4116 = 257 x 16 + 4, a ragged last workgroup) give the same
+    bits; the whole against X times the decoder's fp32 output in fp64 (bar 2^-8 ||x|| ||w_i||: bf16 operands)."""
+    say(f"[matmul tile height] B={bits} m={m}")
+    block, d_in, d_out = 256, 768, 8232
+    g = torch.Generator("cuda").manual_seed(8100 + bits + m)
+    cb = torch.from_numpy(np.asarray(codebooks[bits], dtype=np.float32)).cuda()
+    pk = torch.randint(0, 256, (d_out, qamw.packed_row_bytes(d_in, bits)), dtype=torch.uint8, device="cuda", generator=g)
+    nr = torch.rand(d_out, device="cuda", generator=g) + 0.5
+    X = torch.randn((m, d_in), device="cuda", generator=g).to(torch.bfloat16)
+    whole = qamw.matmul(X, pk, nr, cb, bits, block)
+    half = d_out // 2
+    top = qamw.matmul(X, pk[:half], nr[:half], cb, bits, block)
+    bottom = qamw.matmul(X, pk[half:], nr[half:], cb, bits, block)
+    torch.cuda.synchronize()
+    assert torch.equal(whole[:, :half], top) and torch.equal(whole[:, half:], bottom)
+    W = qamw.decode(pk, nr, d_in, cb, bits, block, f32=True).double()
+    Yref = X.double() @ W.t()
+    bar = 2.0 ** -8 * X.double().norm(dim=1)[:, None] * W.norm(dim=1)[None, :] + 1e-30
+    worst = float(((whole.double() - Yref).abs() / bar).max())
+    say(f"    worst error / bar = {worst:.3f}")
+    assert worst <= 1.0
+
+
 @pytest.mark.parametrize("m", [1, 3, 20])
 def test_fused_matmul_batch_equals_single_calls(orc, codebooks, m):
     """Several independent products in one call give, bit for bit, what one call per matrix gives (vector kernel
