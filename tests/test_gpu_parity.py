@@ -461,6 +461,63 @@ def test_fused_matmul_matches_oracle(orc, codebooks, seed, d_out, d_in, bits, bl
             assert np.array_equal(Yp.cpu().numpy(), Y), f"kernel path {path}"
 
 
+def test_codec_random_shapes(orc, codebooks):
+    """Many small matrices with every option drawn at random -- bit width, block size 2 ... 1024, row count, column
+    count (any multiple of the block), element type, channel scales / sign mask / pair scales present or absent, a padded
+    row stride, all-zero rows, the kernel path -- each encoded and decoded (fp32 and bf16, into a padded output) and held
+    to the same bars as the fixed shapes; the pruned search must give the same bytes wherever it applies."""
+    rng = np.random.default_rng(314159)
+    grids = {}
+    total = dict(pairs=0, mismatches=0, near_ties=0, norm_ulp_rows=0)
+    for it in range(160):
+        bits = int(rng.choice(sorted(codebooks)))
+        block = int(2 ** rng.integers(1, 11))
+        d_in = block * int(rng.integers(1, max(2, min(40, 14336 // block) + 1)))
+        d_out = int(rng.integers(1, 80))
+        dtype = str(rng.choice(["f32", "bf16"]))
+        scale, signs = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+        sigma = "calibrated" if rng.integers(0, 3) else None
+        ldw = d_in + int(rng.choice([0, 0, 8, 24]))
+        path = int(rng.choice([0, 0, 1, 2]))
+        row_sigma = float(rng.choice([0.0, 0.5, 2.0]))
+        say(f"[random {it}] {d_out}x{d_in} B={bits} b={block} {dtype} scale={scale} signs={signs} sigma={sigma} ldw={ldw} "
+            f"path={path} row_sigma={row_sigma}")
+        case = Case(orc, 5000 + it, d_out, d_in, bits, block, dtype=dtype, scale=scale, signs=signs, sigma=sigma,
+                    row_sigma=row_sigma, codebook=codebooks[bits], ldw=ldw)
+        if it % 5 == 0:                                          # an all-zero row: norm 0, index of the codeword nearest the origin
+            case.W[d_out // 2] = 0.0
+            case.W_dev[d_out // 2] = 0.0
+            if sigma is not None:
+                case.sigma = orc.calibrate_sigma(case.W, block, chan_scale=case.s, signs=case.sg)
+                case.sigma_dev = torch.from_numpy(np.asarray(case.sigma, dtype=np.float32)).cuda()
+        ref = case.oracle_encode(orc, threads=16)
+        prev = qamw.set_kernel_path(path)
+        try:
+            packed, norms = case.gpu_encode()
+            rep = {}
+            check_encode(orc, case, packed, norms, ref, report=rep)
+            for k in total:
+                total[k] += rep[k]
+            got = orc.unpack(packed, d_in, bits)
+            f32 = case.gpu_decode(packed, norms, f32=True, ldo=d_in + int(rng.choice([0, 8])))
+            b16 = case.gpu_decode(packed, norms, f32=False)
+            check_decode(orc, case, got, norms, got_f32=f32, got_bf16=b16, threads=16)
+            if sigma is not None:
+                sg = qamw.calibrate_sigma(case.W_dev, block, chan_scale=case.s_dev, signs=case.sg_dev)
+                torch.cuda.synchronize()
+                np.testing.assert_allclose(sg.cpu().numpy(), case.sigma, rtol=1e-6, atol=0)
+            if path == 0 and bits >= 5 and block >= 64 and d_in % max(block, 16) == 0:
+                if bits not in grids:
+                    grids[bits] = torch.from_numpy(qamw.search_grid(codebooks[bits], bits)[0]).cuda()
+                pk2, _ = qamw.encode_pruned(case.W_dev, case.cb_dev, grids[bits], bits, block, chan_scale=case.s_dev,
+                                            signs=case.sg_dev, pair_sigma=case.sigma_dev)
+                torch.cuda.synchronize()
+                assert np.array_equal(pk2.cpu().numpy(), packed)
+        finally:
+            qamw.set_kernel_path(prev)
+    say(f"    {total}")
+
+
 GEMM_CASES = [
     # seed d_out d_in bits block m xdtype
     (51, 70, 2048, 11, 128, 9, "f32"),        # a ragged last workgroup (70 = 2 x 32 + 6 rows), one token tile, one chunk per wave
