@@ -254,8 +254,8 @@ template <int N> __device__ __forceinline__ void gv_reduce_rows(float (&a)[N], i
 // the result from the transform's lane order to the natural one -- the same z in the same lanes, so the same Y, bit for
 // bit, without the first launch; for launches so small that a second launch costs more than the repeated rotations.
 // AHEAD (self-rotating kernels only): the wave keeps two steps' packed words in registers; one activation row fits
-// three waves per SIMD (768 resident workgroups, which covers the launches that rotate for themselves), two rows fit
-// two (512 workgroups: the host picks the plain form for larger two-row launches).
+// three waves per SIMD (768 resident workgroups: a launch of up to 1024 finishes its last quarter in a second round),
+// two rows fit two (512 workgroups: the host picks the plain form for larger two-row launches).
 #define QAMW_GV_WAVES_PER_EU (AHEAD ? (MT == 1 ? 3 : 2) : 1)
 template <int BITS, int MT, int RB, int AHEAD>
 __global__ __launch_bounds__(GV_THREADS) __attribute__((amdgpu_waves_per_eu(QAMW_GV_WAVES_PER_EU)))
