@@ -49,14 +49,6 @@ template <int BITS> __device__ __forceinline__ uint32_t field_x8(const uint32_t 
     return v & mask8;
 }
 
-// Reciprocal with one Newton step: the correctly rounded quotient in all but a few rare cases
-// (then one ulp off), at a third of the cost of the IEEE division sequence.
-__device__ __forceinline__ float fast_recip(float s) {
-    float q = __builtin_amdgcn_rcpf(s);
-    float e = __builtin_fmaf(-s, q, 1.0f);
-    return __builtin_fmaf(q, e, q);
-}
-
 // Per-lane column constants of 16 consecutive columns starting at c (a multiple of 16):
 // qs[e] = 1 / s_j carrying the sign mask in its sign bit, sig[k] = sigma of the lane's 8 pairs.
 // (The transform's lane sign is not folded in here: it rides on the row factor, one multiply per row instead of 16

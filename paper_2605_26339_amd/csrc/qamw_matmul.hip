@@ -125,6 +125,8 @@ __device__ __forceinline__ void gv_rotate_load(GvRotIn<MT> &in, const GemvMat &M
         for (int e = 0; e < 8; ++e) in.sigma[e] = M.pair_sigma[(c >> 1) + e];
     }
 }
+// The arithmetic: x times the reciprocal of the channel scale (the decoder's reciprocal, one Newton step), the sign mask,
+// the transform, and one factor per pair -- lane sign of the transform x 1/sqrt(b) x sigma.
 template <int B, int MT>
 __device__ __forceinline__ void gv_rotate_compute(float (&y)[16], const GvRotIn<MT> &in, int t, const GemvBatch &bt, const GemvMat &M, int lane) {
     const LaneSigns<B> ls(lane);
@@ -132,19 +134,19 @@ __device__ __forceinline__ void gv_rotate_compute(float (&y)[16], const GvRotIn<
     for (int e = 0; e < 16; ++e) y[e] = in.x[t][e];
     if (M.chan_scale) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) y[e] = y[e] * (1.0f / in.scale[e]);         // times fl32(1/s_j), as the decoder does
+        for (int e = 0; e < 16; ++e) y[e] = y[e] * fast_recip(in.scale[e]);
     }
     if (M.signs) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) y[e] = (in.sign[e] < 0) ? -y[e] : y[e];
     }
     fwht_wave<B>(y, ls);
-    const float sigma_default = M.sigma_default;
+    const float k = ls.parity * bt.inv_sqrt_block;
+    float g[8];
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-        const float sg = M.pair_sigma ? in.sigma[e >> 1] : sigma_default;
-        y[e] = ((y[e] * ls.parity) * bt.inv_sqrt_block) * sg;
-    }
+    for (int q = 0; q < 8; ++q) g[q] = k * (M.pair_sigma ? in.sigma[q] : M.sigma_default);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = y[e] * g[e >> 1];
 }
 template <int XDTYPE, int B>
 __device__ __forceinline__ void gv_rotate_slab(float (&y)[16], const GemvBatch &bt, const GemvMat &M, int tok, int slab, int lane) {
