@@ -21,30 +21,44 @@ __global__ __launch_bounds__(CF_THREADS) void k_row_norms_vec(const void *__rest
     const int row = __builtin_amdgcn_readfirstlane(blockIdx.x * CF_WAVES + (threadIdx.x >> 6));
     if (row >= n_rows) return;
     constexpr int V = DTYPE == 0 ? 4 : 8;                       // elements per 16-byte load
+    constexpr int U = 4;                                        // loads requested together: a wave alone on its row has
+                                                                // nothing else to hide the memory round trip behind
+    const char *base = reinterpret_cast<const char *>(W) + (int64_t)row * ldw * (DTYPE == 0 ? 4 : 2);
     double acc = 0.0;
-    for (int j = lane * V; j < d_in; j += WAVE * V) {
-        float w[V];
-        if (DTYPE == 0) {
-            float4 v = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(W) + (int64_t)row * ldw + j);
-            w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
-        } else {
-            uint4 v = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(W) + (int64_t)row * ldw + j);
-            const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+    for (int j0 = lane * V; j0 < d_in; j0 += U * WAVE * V) {
+        uint4 raw[U];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                w[2 * q] = __uint_as_float(u[q] << 16);
-                w[2 * q + 1] = __uint_as_float(u[q] & 0xFFFF0000u);
-            }
-        }
-        if (s) {
-#pragma unroll
-            for (int t = 0; t < V; t += 4) {
-                float4 sv = *reinterpret_cast<const float4 *>(s + j + t);
-                w[t] *= sv.x; w[t + 1] *= sv.y; w[t + 2] *= sv.z; w[t + 3] *= sv.w;
-            }
+        for (int u = 0; u < U; ++u) {
+            const int j = j0 + u * WAVE * V;
+            raw[u] = make_uint4(0, 0, 0, 0);
+            if (j < d_in) raw[u] = *reinterpret_cast<const uint4 *>(base + (int64_t)j * (DTYPE == 0 ? 4 : 2));
         }
 #pragma unroll
-        for (int t = 0; t < V; ++t) acc += (double)w[t] * (double)w[t];
+        for (int u = 0; u < U; ++u) {
+            const int j = j0 + u * WAVE * V;
+            if (j >= d_in) break;
+            float w[V];
+            const uint32_t q4[4] = {raw[u].x, raw[u].y, raw[u].z, raw[u].w};
+            if (DTYPE == 0) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) w[q] = __uint_as_float(q4[q]);
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    w[2 * q] = __uint_as_float(q4[q] << 16);
+                    w[2 * q + 1] = __uint_as_float(q4[q] & 0xFFFF0000u);
+                }
+            }
+            if (s) {
+#pragma unroll
+                for (int t = 0; t < V; t += 4) {
+                    float4 sv = *reinterpret_cast<const float4 *>(s + j + t);
+                    w[t] *= sv.x; w[t + 1] *= sv.y; w[t + 2] *= sv.z; w[t + 3] *= sv.w;
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < V; ++t) acc += (double)w[t] * (double)w[t];
+        }
     }
     acc = wave_sum(acc);
     if (lane == 0) norms[row] = (float)sqrt(acc);

@@ -20,6 +20,8 @@
 // square or in a cell with more than 5 candidates (1.3 % of Gaussian pairs at K = 2048) takes the
 // global record; a lane reads at most two of them per item and leaves any further such pair to the
 // exact scan.
+#include <atomic>
+
 #include "qamw_front.hpp"
 
 namespace qamw {
@@ -321,6 +323,26 @@ static bool grid_encode_supported(const Problem &p) {
     return p.bits >= 1 && p.bits <= 12;
 }
 
+// More than the default 64 KB of LDS per workgroup has to be asked for: a host-side setting per kernel and device, made
+// once per kernel instantiation and device (the devices' bits of `done`).
+template <int DTYPE, int B> static bool grid_allow_large_lds() {
+    static std::atomic<uint64_t> done{0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        (void)hipGetLastError();
+        return false;
+    }
+    if (done.load(std::memory_order_acquire) & (1ull << dev)) return true;
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_grid_lds<DTYPE, B>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)GL_MAX_LDS_BYTES);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    done.fetch_or(1ull << dev, std::memory_order_release);
+    return true;
+}
+
 template <int DTYPE, int B>
 static hipError_t launch_gdb(const void *W, int64_t ldw, const Problem &p, const SearchGridView &g, const float *norms,
                              uint8_t *packed) {
@@ -346,14 +368,7 @@ static hipError_t launch_gdb(const void *W, int64_t ldw, const Problem &p, const
     }
     // one workgroup of 16 waves per CU, each wave a strided share of the items
     const size_t lds = (size_t)p.K * sizeof(float2) + (size_t)gc * gc * sizeof(uint2);
-    if (lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_encode_grid_lds<DTYPE, B>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)GL_MAX_LDS_BYTES);
-        if (e != hipSuccess) {
-            (void)hipGetLastError();
-            return hipErrorNotSupported;
-        }
-    }
+    if (lds > 64 * 1024 && !grid_allow_large_lds<DTYPE, B>()) return hipErrorNotSupported;
     const int64_t want = (n_items + GL_WAVES - 1) / GL_WAVES;
     const unsigned blocks = (unsigned)(want < cus ? want : cus);
     hipLaunchKernelGGL((k_encode_grid_lds<DTYPE, B>), dim3(blocks), dim3(GL_THREADS), lds, p.stream, W, ldw, p, table, g.G, gc,
